@@ -1,0 +1,308 @@
+/*
+ * ELSA oracle -- TEST INFRASTRUCTURE, not a product path.
+ *
+ * A plain, slow, single-threaded IEEE FP64 CPU implementation of what the ELSA
+ * hot path computes.  Only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg may call it.  It shares no code with the HIP library.
+ *
+ * Layout everywhere: contiguous row-major [B][H][n][d], d_v == d.  Inputs are
+ * float arrays (FP16 experiments pass FP16-representable floats), widened
+ * exactly to double before any arithmetic.  A "row" is the flat query index
+ * r = (b*H + h)*n + i.
+ *
+ * Parity pins (tests/test_oracle_*.py): hand-computed closed forms (n = 1,
+ * n = 2 sigmoid mixture, q = 0 column mean), a library float64 softmax used as
+ * a black box, agreement of the definition with the sequential fold and with
+ * arbitrary merge trees, the monoid laws, shift invariance, one-hot dominance,
+ * causal-prefix equivalence, key-permutation invariance.  The paper prints no
+ * worked softmax example, so exact output values beyond those closed forms are
+ * pinned by these independent formulations only.
+ *
+ * Readings where the paper is silent:
+ *   - a masked key is the identity element (skipped); causal means key j is
+ *     visible to query i iff j <= i; key padding means j < kv_len[b];
+ *   - a row with no visible key outputs zeros (state stays at the identity,
+ *     0/0 := 0);
+ *   - a merge whose two maxima are both -inf returns the identity (the case
+ *     form of the merge would otherwise evaluate exp(-inf - -inf)).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+/* number of keys visible to query i of batch b */
+static int64_t visible_keys(int64_t i, int64_t n, int causal, const int32_t *kv_len, int64_t b)
+{
+    int64_t lim = kv_len ? (int64_t)kv_len[b] : n;
+    if (lim > n) lim = n;
+    if (lim < 0) lim = 0;
+    if (causal && i + 1 < lim) lim = i + 1;
+    return lim;
+}
+
+/* s_j = scale * <q_i, k_j>   (Sec. 3, score definition above Eq. 1) */
+static double score(const float *qi, const float *kj, int d, double scale)
+{
+    double acc = 0.0;
+    for (int t = 0; t < d; ++t) acc += (double)qi[t] * (double)kj[t];
+    return scale * acc;
+}
+
+/*
+ * Definition: y_i = sum_j e^{s_ij} v_j / sum_j e^{s_ij}  (Eq. 1), evaluated in
+ * the max-subtracted form of the vectorized reference (Eq. 12): m = max_j s,
+ * E = exp(s - m), y = (E V) / sum(E).
+ * out: [nrows][d] doubles.  Returns 0, or -1 on allocation failure.
+ */
+int elsa_oracle_attn_rows(const float *q, const float *k, const float *v,
+                          int B, int H, int n, int d, double scale, int causal,
+                          const int32_t *kv_len,
+                          const int64_t *rows, int64_t nrows, double *out)
+{
+    (void)B;
+    double *s = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    if (!s) return -1;
+    for (int64_t r = 0; r < nrows; ++r) {
+        int64_t row = rows[r];
+        int64_t i = row % n, bh = row / n, b = bh / H;
+        const float *qi = q + (size_t)row * d;
+        const float *kb = k + (size_t)bh * n * d;
+        const float *vb = v + (size_t)bh * n * d;
+        double *o = out + (size_t)r * d;
+        int64_t L = visible_keys(i, n, causal, kv_len, b);
+        for (int t = 0; t < d; ++t) o[t] = 0.0;
+        if (L <= 0) continue;
+        double m = -INFINITY;
+        for (int64_t j = 0; j < L; ++j) {
+            s[j] = score(qi, kb + (size_t)j * d, d, scale);
+            if (s[j] > m) m = s[j];
+        }
+        double S = 0.0;
+        for (int64_t j = 0; j < L; ++j) {
+            double e = exp(s[j] - m);
+            S += e;
+            const float *vj = vb + (size_t)j * d;
+            for (int t = 0; t < d; ++t) o[t] += e * (double)vj[t];
+        }
+        for (int t = 0; t < d; ++t) o[t] /= S;
+    }
+    free(s);
+    return 0;
+}
+
+/*
+ * Per-query sequential formulation (Alg. 1): start from the identity
+ * (-inf, 0, 0); for each key either keep the maximum and add exp(s - m) (max
+ * unchanged), or move the maximum to s, rescale the past by exp(m_old - s) and
+ * add weight 1 (new maximum); finish with y = W_n / S_n.
+ */
+int elsa_oracle_fold_rows(const float *q, const float *k, const float *v,
+                          int B, int H, int n, int d, double scale, int causal,
+                          const int32_t *kv_len,
+                          const int64_t *rows, int64_t nrows, double *out)
+{
+    (void)B;
+    double *W = (double *)malloc(sizeof(double) * (size_t)(d > 0 ? d : 1));
+    if (!W) return -1;
+    for (int64_t r = 0; r < nrows; ++r) {
+        int64_t row = rows[r];
+        int64_t i = row % n, bh = row / n, b = bh / H;
+        const float *qi = q + (size_t)row * d;
+        const float *kb = k + (size_t)bh * n * d;
+        const float *vb = v + (size_t)bh * n * d;
+        double *o = out + (size_t)r * d;
+        int64_t L = visible_keys(i, n, causal, kv_len, b);
+        double m = -INFINITY, S = 0.0;
+        for (int t = 0; t < d; ++t) W[t] = 0.0;
+        for (int64_t j = 0; j < L; ++j) {
+            double sj = score(qi, kb + (size_t)j * d, d, scale);
+            const float *vj = vb + (size_t)j * d;
+            if (m >= sj) {
+                double alpha = exp(sj - m);
+                S += alpha;
+                for (int t = 0; t < d; ++t) W[t] += alpha * (double)vj[t];
+            } else {
+                double beta = exp(m - sj);  /* exp(-inf) = 0 on the first key */
+                m = sj;
+                S = S * beta + 1.0;
+                for (int t = 0; t < d; ++t) W[t] = W[t] * beta + (double)vj[t];
+            }
+        }
+        for (int t = 0; t < d; ++t) o[t] = (L > 0) ? W[t] / S : 0.0;
+    }
+    free(W);
+    return 0;
+}
+
+/*
+ * Block states for Prop. 1 / the split-KV contract.  Chunk c of C covers keys
+ * [c*ceil(n/C), min(n, (c+1)*ceil(n/C))).  For each sampled row and chunk the
+ * state over the *visible* keys of that chunk is
+ *   m_c = max s_j,  S_c = sum e^{s_j - m_c},  W_c = sum e^{s_j - m_c} v_j
+ * (the normalized state of Sec. 3.2), or the identity (-inf, 0, 0) when no key
+ * of the chunk is visible.
+ * part_m, part_S: [nrows][C]; part_W: [nrows][C][d].
+ */
+int elsa_oracle_partials_rows(const float *q, const float *k, const float *v,
+                              int B, int H, int n, int d, double scale, int causal,
+                              const int32_t *kv_len, int num_splits,
+                              const int64_t *rows, int64_t nrows,
+                              double *part_m, double *part_S, double *part_W)
+{
+    (void)B;
+    int C = num_splits;
+    int64_t chunk = ((int64_t)n + C - 1) / C;
+    double *s = (double *)malloc(sizeof(double) * (size_t)(chunk > 0 ? chunk : 1));
+    if (!s) return -1;
+    for (int64_t r = 0; r < nrows; ++r) {
+        int64_t row = rows[r];
+        int64_t i = row % n, bh = row / n, b = bh / H;
+        const float *qi = q + (size_t)row * d;
+        const float *kb = k + (size_t)bh * n * d;
+        const float *vb = v + (size_t)bh * n * d;
+        int64_t L = visible_keys(i, n, causal, kv_len, b);
+        for (int c = 0; c < C; ++c) {
+            int64_t lo = (int64_t)c * chunk, hi = lo + chunk;
+            if (hi > L) hi = L;
+            double *Wc = part_W + ((size_t)r * C + c) * d;
+            double m = -INFINITY, S = 0.0;
+            for (int t = 0; t < d; ++t) Wc[t] = 0.0;
+            for (int64_t j = lo; j < hi; ++j) {
+                s[j - lo] = score(qi, kb + (size_t)j * d, d, scale);
+                if (s[j - lo] > m) m = s[j - lo];
+            }
+            for (int64_t j = lo; j < hi; ++j) {
+                double e = exp(s[j - lo] - m);
+                S += e;
+                const float *vj = vb + (size_t)j * d;
+                for (int t = 0; t < d; ++t) Wc[t] += e * (double)vj[t];
+            }
+            part_m[(size_t)r * C + c] = m;
+            part_S[(size_t)r * C + c] = S;
+        }
+    }
+    free(s);
+    return 0;
+}
+
+/*
+ * Merge operator, case form (Eq. 3): keep the larger maximum, scale the other
+ * operand by exp(m_small - m_large) <= 1.  Both maxima -inf -> identity.
+ * Wa, Wb, Wo: d doubles.  Wo may alias neither input.
+ */
+void elsa_oracle_merge_case(double ma, double Sa, const double *Wa,
+                            double mb, double Sb, const double *Wb, int d,
+                            double *mo, double *So, double *Wo)
+{
+    if (ma == -INFINITY && mb == -INFINITY) {
+        *mo = -INFINITY; *So = 0.0;
+        for (int t = 0; t < d; ++t) Wo[t] = 0.0;
+        return;
+    }
+    if (ma >= mb) {
+        double f = exp(mb - ma);
+        *mo = ma; *So = Sa + Sb * f;
+        for (int t = 0; t < d; ++t) Wo[t] = Wa[t] + Wb[t] * f;
+    } else {
+        double f = exp(ma - mb);
+        *mo = mb; *So = Sb + Sa * f;
+        for (int t = 0; t < d; ++t) Wo[t] = Wb[t] + Wa[t] * f;
+    }
+}
+
+/*
+ * Merge operator, compact form (Eq. 4): renorm(max(ma, mb), un(a) + un(b)) with
+ * un(m,S,W) = (S e^m, W e^m) and renorm(m,S~,W~) = (m, S~ e^-m, W~ e^-m).
+ * Literal: overflows for |m| beyond ~700, so tests keep m moderate.
+ */
+void elsa_oracle_merge_unsum(double ma, double Sa, const double *Wa,
+                             double mb, double Sb, const double *Wb, int d,
+                             double *mo, double *So, double *Wo)
+{
+    double m = ma > mb ? ma : mb;
+    if (m == -INFINITY) {
+        *mo = m; *So = 0.0;
+        for (int t = 0; t < d; ++t) Wo[t] = 0.0;
+        return;
+    }
+    double ea = exp(ma), eb = exp(mb), em = exp(-m);
+    *mo = m;
+    *So = (Sa * ea + Sb * eb) * em;
+    for (int t = 0; t < d; ++t) Wo[t] = (Wa[t] * ea + Wb[t] * eb) * em;
+}
+
+/*
+ * Combine (Prop. 1): left-to-right merge of C chunk states per row with the
+ * case-form operator, then y = W / S; all-identity rows give zeros.
+ * part_m, part_S: [nrows][C]; part_W: [nrows][C][d]; out: [nrows][d].
+ */
+int elsa_oracle_combine_rows(const double *part_m, const double *part_S, const double *part_W,
+                             int64_t nrows, int C, int d, double *out)
+{
+    double *Wa = (double *)malloc(sizeof(double) * (size_t)(d > 0 ? d : 1) * 2);
+    if (!Wa) return -1;
+    double *Wt = Wa + d;
+    for (int64_t r = 0; r < nrows; ++r) {
+        double m = -INFINITY, S = 0.0;
+        for (int t = 0; t < d; ++t) Wa[t] = 0.0;
+        for (int c = 0; c < C; ++c) {
+            double mo, So;
+            elsa_oracle_merge_case(m, S, Wa, part_m[(size_t)r * C + c], part_S[(size_t)r * C + c],
+                                   part_W + ((size_t)r * C + c) * d, d, &mo, &So, Wt);
+            m = mo; S = So;
+            memcpy(Wa, Wt, sizeof(double) * (size_t)d);
+        }
+        for (int t = 0; t < d; ++t) out[(size_t)r * d + t] = (S > 0.0) ? Wa[t] / S : 0.0;
+    }
+    free(Wa);
+    return 0;
+}
+
+/*
+ * FP32 ladder (diagnostic only): the sequential fold of Alg. 1 carried out
+ * entirely in IEEE single precision (float products, float sums, expf).  It
+ * shows what error any FP32-accumulating evaluation carries on a given input,
+ * so that a tolerance violation can be attributed to the conditioning of the
+ * metric rather than to a kernel defect.  out: [nrows][d] floats.
+ */
+int elsa_ladder_f32_fold_rows(const float *q, const float *k, const float *v,
+                              int B, int H, int n, int d, float scale, int causal,
+                              const int32_t *kv_len,
+                              const int64_t *rows, int64_t nrows, float *out)
+{
+    (void)B;
+    float *W = (float *)malloc(sizeof(float) * (size_t)(d > 0 ? d : 1));
+    if (!W) return -1;
+    for (int64_t r = 0; r < nrows; ++r) {
+        int64_t row = rows[r];
+        int64_t i = row % n, bh = row / n, b = bh / H;
+        const float *qi = q + (size_t)row * d;
+        const float *kb = k + (size_t)bh * n * d;
+        const float *vb = v + (size_t)bh * n * d;
+        float *o = out + (size_t)r * d;
+        int64_t L = visible_keys(i, n, causal, kv_len, b);
+        float m = -INFINITY, S = 0.0f;
+        for (int t = 0; t < d; ++t) W[t] = 0.0f;
+        for (int64_t j = 0; j < L; ++j) {
+            const float *kj = kb + (size_t)j * d;
+            const float *vj = vb + (size_t)j * d;
+            volatile float acc = 0.0f;          /* volatile: forbid FMA contraction / widening */
+            for (int t = 0; t < d; ++t) { volatile float p = qi[t] * kj[t]; acc = acc + p; }
+            float sj = scale * acc;
+            if (m >= sj) {
+                float alpha = expf(sj - m);
+                S += alpha;
+                for (int t = 0; t < d; ++t) { volatile float p = alpha * vj[t]; W[t] = W[t] + p; }
+            } else {
+                float beta = expf(m - sj);
+                m = sj;
+                S = S * beta + 1.0f;
+                for (int t = 0; t < d; ++t) { volatile float p = W[t] * beta; W[t] = p + vj[t]; }
+            }
+        }
+        for (int t = 0; t < d; ++t) o[t] = (L > 0) ? W[t] / S : 0.0f;
+    }
+    free(W);
+    return 0;
+}

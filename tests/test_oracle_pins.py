@@ -1,0 +1,193 @@
+"""Pins of the FP64 oracle against things other than itself.
+
+Each test is chosen so that a plausible mistake in the oracle (dropped scale,
+wrong sign in the exponent, transposed operand, wrong mask edge, wrong chunk
+bounds) fails at least one of them.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2604_23798_amd import inputs
+
+RT = 1e-13  # FP64 agreement level between two exact formulations
+
+
+def _rand(B, H, n, d, seed, sigma=1.0):
+    cnt = B * H * n * d
+    sh = (B, H, n, d)
+    return (inputs.normal(seed, 0, 0, cnt, sigma).reshape(sh),
+            inputs.normal(seed, 1, 0, cnt, sigma).reshape(sh),
+            inputs.normal(seed, 2, 0, cnt).reshape(sh))
+
+
+def _close(a, b, tol=RT):
+    a, b = np.asarray(a, np.float64), np.asarray(b, np.float64)
+    assert a.shape == b.shape
+    assert np.all(np.abs(a - b) <= tol * (1.0 + np.abs(b))), float(np.max(np.abs(a - b)))
+
+
+# ---- hand-computed closed forms -------------------------------------------------------------
+
+def test_single_key_returns_value():
+    q, k, v = _rand(1, 2, 1, 4, 11)
+    _close(oracle.attn_rows(q, k, v, 0.5), v.reshape(2, 4))
+    _close(oracle.fold_rows(q, k, v, 0.5), v.reshape(2, 4))
+
+
+def test_two_keys_sigmoid_mixture():
+    # n = 2: y = sigma(s1 - s2) v1 + sigma(s2 - s1) v2 with s_j = scale <q, k_j>, typed by hand.
+    q = np.array([[[[1.0, -2.0], [0.5, 0.25]]]], np.float32)      # [1,1,2,2]
+    k = np.array([[[[3.0, 1.0], [-1.0, 2.0]]]], np.float32)
+    v = np.array([[[[10.0, -4.0], [2.0, 8.0]]]], np.float32)
+    scale = 0.7
+    # row 0: q=(1,-2): s1 = .7*(3-2) = .7 ; s2 = .7*(-1-4) = -3.5
+    # row 1: q=(.5,.25): s1 = .7*(1.5+.25) = 1.225 ; s2 = .7*(-.5+.5) = 0
+    exp = []
+    for s1, s2 in ((0.7, -3.5), (1.225, 0.0)):
+        w1 = 1.0 / (1.0 + math.exp(s2 - s1))
+        exp.append([w1 * 10.0 + (1 - w1) * 2.0, w1 * -4.0 + (1 - w1) * 8.0])
+    _close(oracle.attn_rows(q, k, v, scale), np.array(exp))
+    _close(oracle.fold_rows(q, k, v, scale), np.array(exp))
+    # causal: row 0 sees only key 0
+    out = oracle.attn_rows(q, k, v, scale, causal=True)
+    _close(out[0], [10.0, -4.0])
+    _close(out[1], exp[1])
+
+
+def test_three_keys_brute_force_unshifted():
+    # Eq. 1 literally, without max subtraction, in Python floats.
+    q, k, v = _rand(1, 1, 3, 2, 5)
+    scale = 1.0 / math.sqrt(2)
+    out = oracle.attn_rows(q, k, v, scale)
+    for i in range(3):
+        s = [scale * sum(float(q[0, 0, i, t]) * float(k[0, 0, j, t]) for t in range(2)) for j in range(3)]
+        den = sum(math.exp(x) for x in s)
+        y = [sum(math.exp(s[j]) * float(v[0, 0, j, t]) for j in range(3)) / den for t in range(2)]
+        _close(out[i], y)
+
+
+def test_zero_query_gives_column_mean():
+    q, k, v = _rand(2, 2, 37, 8, 3)
+    q[:] = 0
+    out = oracle.attn_rows(q, k, v, 0.3).reshape(2, 2, 37, 8)
+    mean = v.astype(np.float64).mean(axis=2, keepdims=True)
+    _close(out, np.broadcast_to(mean, out.shape))
+    # causal: row i = mean of v[0..i]
+    outc = oracle.attn_rows(q, k, v, 0.3, causal=True).reshape(2, 2, 37, 8)
+    cm = np.cumsum(v.astype(np.float64), axis=2) / np.arange(1, 38).reshape(1, 1, 37, 1)
+    _close(outc, cm)
+
+
+# ---- library routine as a black box ---------------------------------------------------------
+
+@pytest.mark.parametrize("causal", [False, True])
+@pytest.mark.parametrize("shape", [(1, 2, 33, 8), (2, 3, 130, 16), (1, 1, 257, 64)])
+def test_against_torch_float64_softmax(shape, causal):
+    B, H, n, d = shape
+    q, k, v = _rand(B, H, n, d, 17 + n)
+    scale = 1.0 / math.sqrt(d)
+    tq, tk, tv = (torch.from_numpy(t).double() for t in (q, k, v))
+    s = (tq @ tk.transpose(-1, -2)) * scale
+    if causal:
+        s = s.masked_fill(torch.ones(n, n).triu(1).bool(), float("-inf"))
+    ref = (torch.softmax(s, dim=-1) @ tv).numpy().reshape(-1, d)
+    _close(oracle.attn_rows(q, k, v, scale, causal=causal), ref, 1e-12)
+    _close(oracle.fold_rows(q, k, v, scale, causal=causal), ref, 1e-12)
+
+
+def test_against_torch_sdpa_with_key_padding():
+    B, H, n, d = 3, 2, 50, 16
+    q, k, v = _rand(B, H, n, d, 23)
+    kv_len = np.array([50, 1, 29], np.int32)
+    scale = 0.25
+    tq, tk, tv = (torch.from_numpy(t).double() for t in (q, k, v))
+    mask = (torch.arange(n)[None, :] < torch.from_numpy(kv_len)[:, None])[:, None, None, :]
+    ref = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv, attn_mask=mask, scale=scale)
+    _close(oracle.attn_rows(q, k, v, scale, kv_len=kv_len), ref.numpy().reshape(-1, d), 1e-12)
+    # kv_len = 1 => every row of that batch returns v_0 (padded query rows are still computed)
+    out = oracle.attn_rows(q, k, v, scale, kv_len=kv_len).reshape(B, H, n, d)
+    _close(out[1], np.broadcast_to(v[1, :, :1, :].astype(np.float64), (H, n, d)))
+    # kv_len = n equals no mask
+    _close(oracle.attn_rows(q, k, v, scale, kv_len=np.full(B, n, np.int32)), oracle.attn_rows(q, k, v, scale))
+
+
+# ---- invariants ------------------------------------------------------------------------------
+
+def test_fold_equals_definition():
+    q, k, v = _rand(1, 2, 300, 32, 41)
+    for causal in (False, True):
+        _close(oracle.fold_rows(q, k, v, 0.2, causal=causal), oracle.attn_rows(q, k, v, 0.2, causal=causal))
+
+
+def test_causal_row_equals_prefix_problem():
+    q, k, v = _rand(1, 1, 40, 8, 9)
+    full = oracle.attn_rows(q, k, v, 0.4, causal=True)
+    _close(full[0], v[0, 0, 0])                       # the first row sees only itself
+    for i in (0, 1, 7, 39):
+        # non-causal problem restricted to keys 0..i, evaluated for query i
+        qq = np.repeat(q[:, :, i:i + 1], i + 1, axis=2)
+        ref = oracle.attn_rows(qq, k[:, :, :i + 1], v[:, :, :i + 1], 0.4)[0]
+        _close(full[i], ref)
+
+
+def test_shift_invariance_through_the_inputs():
+    # Reserve coordinate 0: q[..., 0] = 1 and k[..., 0] += c / scale shifts every score by c.
+    q, k, v = _rand(1, 2, 64, 8, 77)
+    scale = 0.5
+    q[..., 0] = 1.0
+    k[..., 0] = np.round(k[..., 0] * 4) / 4          # keep k0 + c/scale exactly representable
+    base = oracle.attn_rows(q, k, v, scale)
+    for c in (-1000.0, 40.0, 10000.0):
+        k2 = k.copy()
+        k2[..., 0] += np.float32(c / scale)
+        _close(oracle.attn_rows(q, k2, v, scale), base, 1e-10)
+        _close(oracle.fold_rows(q, k2, v, scale), base, 1e-10)
+
+
+def test_one_hot_when_one_score_dominates():
+    B, H, n, d = 1, 1, 50, 8
+    q, k, v = _rand(B, H, n, d, 31)
+    j = 17
+    k[0, 0, j] = q[0, 0, 3] * 60.0                    # score gap of hundreds for query 3
+    out = oracle.attn_rows(q, k, v, 1.0, rows=np.array([3]))
+    _close(out[0], v[0, 0, j], 1e-15)
+
+
+def test_key_permutation_invariance():
+    q, k, v = _rand(1, 2, 90, 16, 55)
+    perm = np.argsort(inputs.uniform01(3, 0, 0, 90))
+    _close(oracle.attn_rows(q, k[:, :, perm], v[:, :, perm], 0.25), oracle.attn_rows(q, k, v, 0.25), 1e-12)
+
+
+def test_no_visible_key_outputs_zero():
+    q, k, v = _rand(2, 1, 5, 4, 2)
+    out = oracle.attn_rows(q, k, v, 1.0, kv_len=np.array([0, 5], np.int32)).reshape(2, 5, 4)
+    assert np.all(out[0] == 0.0) and np.all(np.isfinite(out))
+    assert np.all(oracle.fold_rows(q, k, v, 1.0, kv_len=np.array([0, 5], np.int32)).reshape(2, 5, 4)[0] == 0)
+
+
+def test_wide_scores_stay_finite():
+    # config-5-like: scores with sigma ~ 64; every exponent argument is <= 0 so nothing overflows.
+    q, k, v = _rand(1, 1, 512, 64, 99, sigma=8.0)
+    out = oracle.attn_rows(q, k, v, 0.125)
+    assert np.all(np.isfinite(out))
+    _close(oracle.fold_rows(q, k, v, 0.125), out, 1e-12)
+
+
+def test_row_subset_matches_full():
+    q, k, v = _rand(2, 2, 31, 8, 8)
+    full = oracle.attn_rows(q, k, v, 0.3, causal=True)
+    rows = np.array([0, 5, 30, 31, 61, 123], np.int64)
+    assert np.array_equal(oracle.attn_rows(q, k, v, 0.3, causal=True, rows=rows), full[rows])
+
+
+def test_ladder_f32_is_close_but_not_exact():
+    q, k, v = _rand(1, 1, 256, 64, 4)
+    ref = oracle.attn_rows(q, k, v, 0.125)
+    lad = oracle.ladder_f32_fold_rows(q, k, v, 0.125).astype(np.float64)
+    err = np.linalg.norm(lad - ref, axis=1) / np.linalg.norm(ref, axis=1)
+    assert 0 < err.max() < 1e-5
