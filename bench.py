@@ -1,0 +1,133 @@
+#!/usr/bin/env python3
+"""Benchmark of the ELSA attention hot path on one MI355X.
+
+A step is one pass of the whole path (one ``elsa_attn_fwd`` call: score tiles, monoid fold,
+PV accumulation, normalise/store; plus the combine pass when the library splits keys) over
+one batch of seeded synthetic input that is already resident in HBM.  The default workload is
+the one the headline metric is quoted on: the long-sequence sweep at n = 16384, d = 64
+(B = 1, H = 16), FP32.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--path auto|fma|mfma]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_FP32_TFLOPS = 157.3      # MI355X dense FP32 (matrix = vector peak): 256 CU x 256 flop/clk x 2.4 GHz
+
+
+def cpu_baseline(w, q, k, v, kv_len, gpu_out, budget_rows):
+    """Time the FP64 oracle (single thread, as it stands) on a bounded row sample of the same
+    workload, and use the same rows as a parity spot check of the timed GPU output."""
+    import numpy as np
+    import oracle
+    from paper_2604_23798_amd import inputs
+    from tests.parity import metrics, tolerance
+    per_head = max(2, budget_rows // (w.B * w.H))
+    rows = inputs.sample_rows(w, per_head=per_head)
+    f32 = lambda t: t.astype(np.float32)
+    qq, kk, vv = f32(q), f32(k), f32(v)
+    oracle.attn_rows(qq, kk, vv, w.scale, causal=w.causal, kv_len=kv_len, rows=rows[:4])   # page in
+    t0 = time.perf_counter()
+    ref = oracle.attn_rows(qq, kk, vv, w.scale, causal=w.causal, kv_len=kv_len, rows=rows)
+    dt = time.perf_counter() - t0
+    i = rows % w.n
+    vis = np.minimum(i + 1, w.n) if w.causal else np.full(rows.shape, w.n)
+    if kv_len is not None:
+        vis = np.minimum(vis, kv_len[rows // (w.n * w.H)])
+    flops = float(4 * w.d * vis.sum())
+    tol = tolerance(w.n, w.fp16)
+    par = metrics(gpu_out.reshape(-1, w.d)[rows], ref, tol)
+    par["tol"] = tol
+    par["pass"] = bool(par["e_row"] <= tol and par["e_mix"] <= tol)
+    base = {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+            "sample": "%d query rows (%d per head: first, last, tile-boundary neighbours, random) of %s, "
+                      "all their keys, FP64 single thread, %.1f s" % (rows.size, per_head, w.name, dt)}
+    return base, par
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="sweep_n16384")
+    ap.add_argument("--path", default="auto", choices=["auto", "fma", "mfma"])
+    ap.add_argument("--variant", type=int, default=0)
+    ap.add_argument("--xcd-map", type=int, default=0)
+    ap.add_argument("--oracle-rows", type=int, default=4096, help="row budget of the cpu_baseline leg (0 = skip)")
+    a = ap.parse_args()
+    if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)."
+              % a.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2604_23798_amd import elsa, inputs          # fails loudly if libelsa.so is missing
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    w = inputs.WORKLOADS[a.workload]
+    q, k, v, kv_len = inputs.make(w)
+    tq, tk, tv = (torch.from_numpy(t).cuda() for t in (q, k, v))
+    tl = None if kv_len is None else torch.from_numpy(kv_len).cuda()
+    out = torch.empty_like(tq)
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    elsa.elsa_set_workspace(ws)
+    elsa.elsa_set_option(elsa.OPT_PATH, {"auto": 0, "fma": 1, "mfma": 2}[a.path])
+    elsa.elsa_set_option(elsa.OPT_VARIANT, a.variant)
+    elsa.elsa_set_option(elsa.OPT_XCD_MAP, a.xcd_map)
+
+    def step():
+        elsa.elsa_attn_fwd_masked(tq, tk, tv, out, w.scale, w.causal, tl)
+
+    for _ in range(a.warmup):
+        step()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()                       # on torch's current stream: the stream the kernels are launched on
+    for _ in range(a.steps):
+        step()
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / a.steps
+    ms_kernel = ev0.elapsed_time(ev1) / a.steps
+    kernel = elsa.elsa_last_kernel()
+
+    flops = w.flops                    # 4 B H n^2 d, the square count the metric is defined on
+    value = flops / (ms_step * 1e-3) / 1e12
+    achieved = flops / (ms_kernel * 1e-3) / 1e12
+    rec = {
+        "metric": "FP32 attention TFLOP/s at n=16K, d=64 (4*B*H*n^2*d / time)" if a.workload == "sweep_n16384"
+        else "attention TFLOP/s (4*B*H*n^2*d / time)",
+        "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16 io / f32 accumulate" if w.fp16 else "f32", "data": "synthetic",
+        "pct_of_fp32_peak": 100.0 * value / PEAK_FP32_TFLOPS,
+        "config": {"workload": w.name, "B": w.B, "H": w.H, "n": w.n, "d": w.d, "causal": w.causal,
+                   "padded": w.padded, "kernel": kernel, "path": a.path},
+        "roofline": {"bound": "alu" if kernel.startswith("fma") else "mfma", "achieved": achieved,
+                     "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_TFLOPS,
+                     "traffic": None, "kernel_ms": ms_kernel},
+    }
+    if w.causal:
+        rec["causal_effective_tflops"] = 4.0 * w.B * w.H * w.d * (w.n * (w.n + 1) / 2) / (ms_step * 1e-3) / 1e12
+    if a.oracle_rows > 0:
+        base, par = cpu_baseline(w, q, k, v, kv_len, out.double().cpu().numpy(), a.oracle_rows)
+        rec["cpu_baseline"] = base
+        rec["parity"] = par
+    elsa.elsa_set_workspace(None)
+    print(json.dumps(rec))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,127 @@
+/*
+ * libelsa -- exact softmax attention as a reduction over the (m, S, W) monoid,
+ * hand-written HIP for gfx950 (MI355X).  C ABI.
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
+ *     never allocates, frees or retains them (except the workspace registered
+ *     with elsa_set_workspace, which it borrows until replaced).
+ *   - Q, K, V, out are contiguous row-major [B][H][n][d] with d_v == d,
+ *     self-attention (n queries, n keys).  d must be 64 or 128.
+ *   - dtype: ELSA_F32 = FP32 in/out; ELSA_F16 = IEEE FP16 in/out.  Scores, the
+ *     running maximum m, the normaliser S and the weighted sum W are always FP32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     only enqueue work on it; they never synchronise and never allocate.
+ *   - Return ELSA_OK or an error code; nothing aborts, throws or prints.
+ *     Arguments are validated before anything is launched.
+ *   - Results are deterministic: no atomics; two calls on the same inputs with
+ *     the same options are bit-identical.
+ *   - Masks.  causal != 0: key j is visible to query i iff j <= i.  kv_len
+ *     (device int32 [B], may be NULL): key j of batch b is visible iff
+ *     j < kv_len[b]; values are clamped to [0, n]; query rows beyond kv_len are
+ *     still computed.  A masked key is the identity element of the monoid.  A
+ *     row with no visible key outputs zeros.
+ */
+#ifndef ELSA_H
+#define ELSA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    ELSA_OK = 0,
+    ELSA_ERR_INVALID_ARG = 1,  /* null pointer, B/H/n <= 0, num_splits out of range, non-finite scale */
+    ELSA_ERR_UNSUPPORTED = 2,  /* d not in {64,128}, dtype not in {0,1}, unknown option */
+    ELSA_ERR_WORKSPACE = 3,    /* registered workspace too small / misaligned */
+    ELSA_ERR_HIP = 4           /* the HIP runtime reported a launch failure */
+};
+
+enum { ELSA_F32 = 0, ELSA_F16 = 1 };
+
+/*
+ * y_i = sum_j e^{s_ij} v_j / sum_j e^{s_ij},  s_ij = scale * <q_i, k_j>   (Eq. 1),
+ * evaluated as the reduction u_1 (+) ... (+) u_n of per-key states (s_j, 1, v_j)
+ * under the merge operator of Eq. 3 and normalised by W/S (Alg. 1, last line).
+ * Runs single-pass unless a workspace is registered and the problem is too small
+ * to fill the GPU, in which case it splits the key range internally and combines.
+ */
+int elsa_attn_fwd(const void *q, const void *k, const void *v, void *out,
+                  int B, int H, int n, int d, float scale, int causal,
+                  int dtype, void *stream);
+
+/* Same, with a per-batch key-padding mask kv_len (device int32 [B], NULL = none). */
+int elsa_attn_fwd_masked(const void *q, const void *k, const void *v, void *out,
+                         int B, int H, int n, int d, float scale, int causal,
+                         const int32_t *kv_len, int dtype, void *stream);
+
+/*
+ * Block states of Prop. 1.  The key range is cut into num_splits contiguous
+ * chunks; chunk c covers keys [c*ceil(n/C), min(n, (c+1)*ceil(n/C))).  For every
+ * query row and chunk the kernel emits the normalised state over the visible
+ * keys of the chunk:
+ *   part_m[b][h][c][i]    = max_j s_ij              (natural-log units)
+ *   part_S[b][h][c][i]    = sum_j e^{s_ij - m}
+ *   part_W[b][h][c][i][:] = sum_j e^{s_ij - m} v_j  (FP32, d values)
+ * or the identity (-inf, 0, 0) when no key of the chunk is visible.
+ * 1 <= num_splits <= min(n, 65535).
+ */
+int elsa_attn_fwd_split_kv(const void *q, const void *k, const void *v,
+                           float *part_m, float *part_S, float *part_W,
+                           int B, int H, int n, int d, float scale, int causal,
+                           const int32_t *kv_len, int num_splits, int dtype, void *stream);
+
+/*
+ * out = W/S of part[...,0,...] (+) ... (+) part[...,C-1,...]   (Prop. 1, Eq. 3).
+ * Accepts identity states; an all-identity row gives zeros.  Layouts as above.
+ */
+int elsa_combine(const float *part_m, const float *part_S, const float *part_W, void *out,
+                 int B, int H, int n, int d, int num_splits, int dtype, void *stream);
+
+/* Bytes of FP32 workspace that hold part_m, part_S and part_W for these sizes
+ * (0 for invalid sizes).  Layout: part_m | part_S | part_W, each 256-byte aligned. */
+size_t elsa_split_kv_workspace_bytes(int B, int H, int n, int d, int num_splits);
+
+/*
+ * Lend the library a device buffer (256-byte aligned) that elsa_attn_fwd[_masked]
+ * may use to split the key range when B*H*ceil(n/T_q) is too small to fill the
+ * GPU.  Pass (NULL, 0) to withdraw it.  The buffer is shared by all later calls:
+ * calls that overlap on different streams must not both use it.
+ */
+int elsa_set_workspace(void *dev_ptr, size_t bytes);
+
+/*
+ * Measurement / tuning knobs (process-wide, not thread-safe).  Defaults are 0.
+ *   ELSA_OPT_PATH     0 = auto (FP32 MFMA), 1 = FP32 FMA (vector ALU), 2 = FP32 MFMA
+ *   ELSA_OPT_VARIANT  0 = auto, otherwise a tile configuration id (see elsa_variant_name)
+ *   ELSA_OPT_SPLITS   0 = auto, otherwise the number of key chunks elsa_attn_fwd uses
+ *                     when a workspace is registered
+ *   ELSA_OPT_XCD_MAP  0 = auto, 1 = linear block order, 2 = heads pinned to XCDs
+ */
+enum { ELSA_OPT_PATH = 0, ELSA_OPT_VARIANT = 1, ELSA_OPT_SPLITS = 2, ELSA_OPT_XCD_MAP = 3 };
+int elsa_set_option(int option, int value);
+int elsa_get_option(int option, int *value);
+
+/* Name of tile configuration `variant` for path `path` (NULL when out of range). */
+const char *elsa_variant_name(int path, int variant);
+
+/* Name of the kernel configuration the last successful forward call launched. */
+const char *elsa_last_kernel(void);
+
+const char *elsa_status_string(int code);
+
+/*
+ * Test hook, not part of the attention path: one wavefront reports how
+ * v_mfma_f32_32x32x2_f32 lays out its result and what the half-wave exchange
+ * returns, so a test can check the operand maps the forward kernel is built on.
+ * out: device buffer of 5*16*64 floats.
+ */
+int elsa_debug_layout_probe(float *out_5x16x64, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ELSA_H */

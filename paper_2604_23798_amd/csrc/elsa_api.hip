@@ -1,0 +1,215 @@
+// C ABI of libelsa: argument checks, configuration choice, launches.  No allocation, no sync.
+#include <cmath>
+
+#include "../../include/elsa.h"
+#include "elsa_common.hpp"
+
+namespace {
+
+struct State {
+    int opt[4] = {0, 0, 0, 0};
+    void *ws = nullptr;
+    size_t ws_bytes = 0;
+    const char *last = "";
+} g;
+
+constexpr int kMaxSplits = 65535;
+constexpr int kNumCu = 256;
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int check_common(int B, int H, int n, int d, int dtype) {
+    if (B <= 0 || H <= 0 || n <= 0) return ELSA_ERR_INVALID_ARG;
+    if ((long long)B * H > 0x7fffffffLL / 64) return ELSA_ERR_INVALID_ARG;
+    if (d != 64 && d != 128) return ELSA_ERR_UNSUPPORTED;
+    if (dtype != ELSA_F32 && dtype != ELSA_F16) return ELSA_ERR_UNSUPPORTED;
+    return ELSA_OK;
+}
+
+int variant_count(int path) { return path == 1 ? elsa::kFmaVariants : elsa::kMfmaVariants; }
+int variant_tq(int path, int variant, int d) {
+    return path == 1 ? elsa::fma_variant_tq(variant, d) : elsa::mfma_variant_tq(variant, d);
+}
+
+// Tile configuration when the caller did not force one: the largest query tile that
+// still yields about two blocks per CU, otherwise the configuration whose waves split
+// the key range so that a short sequence still spreads over many blocks.
+int pick_variant(int path, long long BH, int n, int d, int splits) {
+    if (g.opt[ELSA_OPT_VARIANT] >= 1 && g.opt[ELSA_OPT_VARIANT] <= variant_count(path)) return g.opt[ELSA_OPT_VARIANT];
+    if (path == 1) {
+        const long long blocks = BH * ((n + 255) / 256) * splits;
+        return blocks >= kNumCu ? 1 : 2;
+    }
+    const long long b128 = BH * ((n + 127) / 128) * splits;
+    return b128 >= 2 * kNumCu ? 1 : (b128 >= kNumCu / 2 ? 1 : 3);
+}
+
+int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
+                int B, int H, int n, int d, float scale, int causal, const int32_t *kv_len,
+                int num_splits, int emit, int m_natural, int dtype, void *stream) {
+    const int path = g.opt[ELSA_OPT_PATH] == 1 ? 1 : 2;
+    const int variant = pick_variant(path, (long long)B * H, n, d, num_splits);
+    const int tq = variant_tq(path, variant, d);
+    if (tq <= 0) return ELSA_ERR_UNSUPPORTED;
+    elsa::FwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.out = out;
+    p.part_m = pm; p.part_S = pS; p.part_W = pW;
+    p.kv_len = kv_len;
+    p.B = B; p.H = H; p.n = n;
+    p.qscale = scale * elsa::kLog2e;
+    p.causal = causal ? 1 : 0;
+    p.num_splits = num_splits;
+    p.chunk = (n + num_splits - 1) / num_splits;
+    p.emit_partials = emit;
+    p.m_natural = m_natural;
+    p.q_tiles = (n + tq - 1) / tq;
+    const int xm = g.opt[ELSA_OPT_XCD_MAP];
+    p.xcd_map = xm == 2 ? 1 : 0;
+    const long long total = (long long)p.q_tiles * B * H * num_splits;
+    if (total > 0x7fffffffLL - 8) return ELSA_ERR_INVALID_ARG;
+    const char *name = nullptr;
+    const hipStream_t s = static_cast<hipStream_t>(stream);
+    const int rc = path == 1 ? elsa::launch_fwd_fma(p, d, dtype == ELSA_F16, variant, s, &name)
+                             : elsa::launch_fwd_mfma(p, d, dtype == ELSA_F16, variant, s, &name);
+    if (rc != 0) return ELSA_ERR_HIP;
+    g.last = name ? name : "";
+    return ELSA_OK;
+}
+
+void carve(void *ws, int B, int H, int n, int d, int C, float **pm, float **pS, float **pW) {
+    const size_t rows = (size_t)B * H * C * n;
+    char *base = static_cast<char *>(ws);
+    *pm = reinterpret_cast<float *>(base);
+    *pS = reinterpret_cast<float *>(base + align256(rows * 4));
+    *pW = reinterpret_cast<float *>(base + 2 * align256(rows * 4));
+    (void)d;
+}
+
+// Number of key chunks for elsa_attn_fwd when a workspace is lent: enough blocks for
+// about two per CU, chunks no shorter than 256 keys, and only if the workspace holds them.
+int auto_splits(int B, int H, int n, int d) {
+    int C = g.opt[ELSA_OPT_SPLITS];
+    if (C <= 0) {
+        const long long blocks = (long long)B * H * ((n + 127) / 128);
+        C = 1;
+        if (blocks < 2 * kNumCu) {
+            C = (int)((2 * kNumCu + blocks - 1) / blocks);
+            const int cap = n / 256 > 1 ? n / 256 : 1;
+            if (C > cap) C = cap;
+            if (C > 16) C = 16;
+        }
+    }
+    if (C > n) C = n;
+    if (C > kMaxSplits) C = kMaxSplits;
+    while (C > 1 && elsa_split_kv_workspace_bytes(B, H, n, d, C) > g.ws_bytes) --C;
+    return C < 1 ? 1 : C;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t elsa_split_kv_workspace_bytes(int B, int H, int n, int d, int num_splits) {
+    if (B <= 0 || H <= 0 || n <= 0 || (d != 64 && d != 128) || num_splits < 1) return 0;
+    const size_t rows = (size_t)B * H * num_splits * n;
+    return 2 * align256(rows * 4) + align256(rows * d * 4);
+}
+
+int elsa_set_workspace(void *dev_ptr, size_t bytes) {
+    if ((dev_ptr == nullptr) != (bytes == 0)) return ELSA_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(dev_ptr) & 255) return ELSA_ERR_WORKSPACE;
+    g.ws = dev_ptr;
+    g.ws_bytes = bytes;
+    return ELSA_OK;
+}
+
+int elsa_attn_fwd_masked(const void *q, const void *k, const void *v, void *out,
+                         int B, int H, int n, int d, float scale, int causal,
+                         const int32_t *kv_len, int dtype, void *stream) {
+    if (!q || !k || !v || !out) return ELSA_ERR_INVALID_ARG;
+    if (!std::isfinite(scale)) return ELSA_ERR_INVALID_ARG;
+    int rc = check_common(B, H, n, d, dtype);
+    if (rc != ELSA_OK) return rc;
+    const int C = g.ws ? auto_splits(B, H, n, d) : 1;
+    if (C == 1)
+        return run_forward(q, k, v, out, nullptr, nullptr, nullptr, B, H, n, d, scale, causal, kv_len, 1, 0, 0, dtype,
+                           stream);
+    float *pm, *pS, *pW;
+    carve(g.ws, B, H, n, d, C, &pm, &pS, &pW);
+    // internal split: maxima stay in log2 units, so the second pass adds no rounding of m
+    rc = run_forward(q, k, v, nullptr, pm, pS, pW, B, H, n, d, scale, causal, kv_len, C, 1, 0, dtype, stream);
+    if (rc != ELSA_OK) return rc;
+    elsa::CombineParams cp{pm, pS, pW, out, (long long)B * H * n, n, C, 0, dtype == ELSA_F16};
+    return elsa::launch_combine(cp, d, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
+}
+
+int elsa_attn_fwd(const void *q, const void *k, const void *v, void *out,
+                  int B, int H, int n, int d, float scale, int causal, int dtype, void *stream) {
+    return elsa_attn_fwd_masked(q, k, v, out, B, H, n, d, scale, causal, nullptr, dtype, stream);
+}
+
+int elsa_attn_fwd_split_kv(const void *q, const void *k, const void *v,
+                           float *part_m, float *part_S, float *part_W,
+                           int B, int H, int n, int d, float scale, int causal,
+                           const int32_t *kv_len, int num_splits, int dtype, void *stream) {
+    if (!q || !k || !v || !part_m || !part_S || !part_W) return ELSA_ERR_INVALID_ARG;
+    if (!std::isfinite(scale)) return ELSA_ERR_INVALID_ARG;
+    int rc = check_common(B, H, n, d, dtype);
+    if (rc != ELSA_OK) return rc;
+    if (num_splits < 1 || num_splits > n || num_splits > kMaxSplits) return ELSA_ERR_INVALID_ARG;
+    return run_forward(q, k, v, nullptr, part_m, part_S, part_W, B, H, n, d, scale, causal, kv_len, num_splits, 1, 1,
+                       dtype, stream);
+}
+
+int elsa_combine(const float *part_m, const float *part_S, const float *part_W, void *out,
+                 int B, int H, int n, int d, int num_splits, int dtype, void *stream) {
+    if (!part_m || !part_S || !part_W || !out) return ELSA_ERR_INVALID_ARG;
+    int rc = check_common(B, H, n, d, dtype);
+    if (rc != ELSA_OK) return rc;
+    if (num_splits < 1 || num_splits > n || num_splits > kMaxSplits) return ELSA_ERR_INVALID_ARG;
+    elsa::CombineParams cp{part_m, part_S, part_W, out, (long long)B * H * n, n, num_splits, 1, dtype == ELSA_F16};
+    return elsa::launch_combine(cp, d, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
+}
+
+int elsa_set_option(int option, int value) {
+    if (option < 0 || option > 3) return ELSA_ERR_UNSUPPORTED;
+    if (value < 0) return ELSA_ERR_INVALID_ARG;
+    if (option == ELSA_OPT_PATH && value > 2) return ELSA_ERR_INVALID_ARG;
+    if (option == ELSA_OPT_XCD_MAP && value > 2) return ELSA_ERR_INVALID_ARG;
+    if (option == ELSA_OPT_SPLITS && value > kMaxSplits) return ELSA_ERR_INVALID_ARG;
+    if (option == ELSA_OPT_VARIANT && value > 16) return ELSA_ERR_INVALID_ARG;
+    g.opt[option] = value;
+    return ELSA_OK;
+}
+
+int elsa_get_option(int option, int *value) {
+    if (option < 0 || option > 3) return ELSA_ERR_UNSUPPORTED;
+    if (!value) return ELSA_ERR_INVALID_ARG;
+    *value = g.opt[option];
+    return ELSA_OK;
+}
+
+const char *elsa_variant_name(int path, int variant) {
+    return path == 1 ? elsa::fma_variant_name(variant) : elsa::mfma_variant_name(variant);
+}
+
+const char *elsa_last_kernel(void) { return g.last; }
+
+const char *elsa_status_string(int code) {
+    switch (code) {
+        case ELSA_OK: return "ok";
+        case ELSA_ERR_INVALID_ARG: return "invalid argument";
+        case ELSA_ERR_UNSUPPORTED: return "unsupported head dimension, dtype or option";
+        case ELSA_ERR_WORKSPACE: return "workspace too small or misaligned";
+        case ELSA_ERR_HIP: return "HIP launch failure";
+        default: return "unknown status";
+    }
+}
+
+// Test hook (not part of the attention path): runs the device layout probe, see elsa_combine.hip.
+int elsa_debug_layout_probe(float *out_5x16x64, void *stream) {
+    if (!out_5x16x64) return ELSA_ERR_INVALID_ARG;
+    return elsa::launch_probe(out_5x16x64, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,105 @@
+// Shared device helpers for the ELSA kernels (gfx950 only).
+#pragma once
+#include <hip/hip_fp16.h>
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace elsa {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr int kNumXcd = 8;  // MI355X: 8 accelerator dies, blocks are dealt to them round-robin
+
+// One forward launch.  Scores are held in log2 units inside the kernels: Q is
+// multiplied by qscale = scale * log2(e) once when it is loaded, so every
+// exponential is a bare 2^x.
+struct FwdParams {
+    const void *q, *k, *v;
+    void *out;                       // [B][H][n][d], used when num_splits == 1 && !emit_partials
+    float *part_m, *part_S, *part_W; // [BH][C][n], [BH][C][n], [BH][C][n][d]
+    const int32_t *kv_len;           // device [B] or nullptr
+    int B, H, n;
+    float qscale;
+    int causal;
+    int num_splits;                  // C >= 1
+    int chunk;                       // ceil(n / C) keys per split
+    int emit_partials;               // 1: write (m,S,W) states instead of out
+    int m_natural;                   // 1: part_m in natural-log units, 0: log2 units (internal)
+    int xcd_map;                     // 1: heads pinned to XCDs
+    int q_tiles;                     // ceil(n / T_q) for the launched configuration
+};
+
+struct CombineParams {
+    const float *part_m, *part_S, *part_W;
+    void *out;
+    long long rows;                  // B*H*n
+    int n, num_splits;
+    int m_natural;
+    int f16_out;
+};
+
+__device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// The two half-waves (lanes l and l ^ 32) trade one register with v_permlane32_swap:
+// afterwards r[0] holds the lower half's value and r[1] the upper half's value in
+// every lane, so a symmetric reduction needs no lane test.
+__device__ __forceinline__ float half_max(float x) {
+    unsigned u = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float half_sum(float x) {
+    unsigned u = __float_as_uint(x);
+    auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Work item handled by this block.  Blocks are dealt round-robin to the 8 XCDs
+// (each with a private L2), so with xcd_map on, consecutive work items -- which
+// share a head's K and V -- are steered to the same XCD.
+__device__ __forceinline__ long long work_index(long long total, int xcd_map) {
+    long long lin = blockIdx.x;
+    if (!xcd_map) return lin;
+    long long per = (total + kNumXcd - 1) / kNumXcd;
+    return (lin % kNumXcd) * per + lin / kNumXcd;   // may be >= total: caller exits
+}
+
+template <typename T> struct Io;
+template <> struct Io<float> {
+    static __device__ __forceinline__ f32x4 load4(const void *base, long long elem) {
+        return *reinterpret_cast<const f32x4 *>(static_cast<const float *>(base) + elem);
+    }
+    static __device__ __forceinline__ void store4(void *base, long long elem, f32x4 x) {
+        *reinterpret_cast<f32x4 *>(static_cast<float *>(base) + elem) = x;
+    }
+};
+template <> struct Io<_Float16> {
+    static __device__ __forceinline__ f32x4 load4(const void *base, long long elem) {
+        f16x4 h = *reinterpret_cast<const f16x4 *>(static_cast<const _Float16 *>(base) + elem);
+        return f32x4{(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
+    }
+    static __device__ __forceinline__ void store4(void *base, long long elem, f32x4 x) {
+        f16x4 h = {(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3]};
+        *reinterpret_cast<f16x4 *>(static_cast<_Float16 *>(base) + elem) = h;
+    }
+};
+
+// Launchers implemented in the kernel translation units.  Each returns a hipError_t as int.
+int launch_fwd_mfma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name);
+int launch_fwd_fma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name);
+int launch_combine(const CombineParams &p, int d, hipStream_t s);
+int launch_probe(float *out, hipStream_t s);
+int mfma_variant_tq(int variant, int d);   // queries per block of a variant (0 if unknown)
+int fma_variant_tq(int variant, int d);
+const char *mfma_variant_name(int variant);
+const char *fma_variant_name(int variant);
+constexpr int kMfmaVariants = 4;
+constexpr int kFmaVariants = 2;
+
+}  // namespace elsa

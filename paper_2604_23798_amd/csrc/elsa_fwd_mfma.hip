@@ -1,0 +1,382 @@
+// ELSA forward, FP32 MFMA path (gfx950).
+//
+// One block owns T_q = 32*NQ*WQ query rows of one (batch, head) and one key
+// chunk; its WQ*WK waves share K/V tiles staged in LDS.  A wave owns NQ groups of
+// 32 queries and, of every tile, a slice of KS keys.  Per 32-key step it
+//   1. forms the transposed score tile S^T = K Q^T with v_mfma_f32_32x32x2_f32
+//      (keys are the M rows, queries the N columns), so that lane l holds 16 keys
+//      of ONE query (column l%32) and lane l^32 holds the other 16;
+//   2. folds the tile into the running state (m, S, W) of that query -- the merge
+//      operator of Eq. 3 applied to the tile's state: in-lane max/sum over the 16
+//      scores, one v_permlane32_swap across the two half-waves, rescale by
+//      2^(m_old - m_new)  (scores are kept in log2 units);
+//   3. accumulates W^T += V^T P^T with the same MFMA: the exponentials sit in the
+//      accumulator registers exactly where the B operand of the next MFMA wants
+//      them, so P never moves between lanes and never touches LDS.
+// When WK > 1 the waves that split the key range merge their states through LDS
+// (log2(WK) levels of the same operator).  The block then writes either
+// out = W / S (Alg. 1, last line) or the state itself (Prop. 1 block state).
+#include "elsa_common.hpp"
+
+namespace elsa {
+
+__device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
+}
+
+template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE>
+__global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p) {
+    constexpr int NT = 64 * WQ * WK;
+    constexpr int TQ = 32 * NQ * WQ;
+    constexpr int TKB = KS * WK;            // keys per LDS tile
+    constexpr int KROW = D + 4;             // padded K row: 16-byte reads of 32 rows hit distinct banks
+    constexpr int VROW = D;
+    constexpr int KBUF = TKB * KROW;
+    constexpr int VBUF = TKB * VROW;
+    constexpr int QPR = D / 4;              // 4-element groups per row
+    constexpr int LPT = TKB * QPR / NT;     // staged groups per thread per tensor
+    constexpr int MB = D / 32;              // 32-row blocks of W^T
+    static_assert(TKB * QPR % NT == 0, "tile must divide evenly over the threads");
+    static_assert(KS % 32 == 0, "a wave consumes keys 32 at a time");
+
+    extern __shared__ __align__(16) float smem[];
+    float *Ks = smem;                       // [2][KBUF]
+    float *Vs = smem + 2 * KBUF;            // [2][VBUF]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wq = wave % WQ, wk = wave / WQ;
+    const int j = lane & 31, h = lane >> 5;
+
+    const long long BH = (long long)p.B * p.H;
+    const long long total = (long long)p.q_tiles * BH * p.num_splits;
+    const long long w = work_index(total, p.xcd_map);
+    if (w >= total) return;
+    int qt = (int)(w % p.q_tiles);
+    const long long r = w / p.q_tiles;
+    const int c = (int)(r % p.num_splits);
+    const long long bh = r / p.num_splits;
+    if (p.causal) qt = p.q_tiles - 1 - qt;  // longest rows first
+    const int n = p.n;
+    int L = n;
+    if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), n);
+    const int q0 = qt * TQ;
+    const int kbeg = c * p.chunk;
+    int kend = min(kbeg + p.chunk, L);
+    if (p.causal) kend = min(kend, q0 + TQ);
+    const int ntiles = kend > kbeg ? (kend - kbeg + TKB - 1) / TKB : 0;
+
+    const long long head_off = bh * (long long)n * D;
+    const int wrow0 = q0 + wq * NQ * 32;    // first query row of this wave
+
+    // ---- Q fragments (B operand).  MFMA step s = 4*cc + t contracts columns
+    // 8*cc + t (lower half-wave) and 8*cc + 4 + t (upper); K uses the same map.
+    float qf[NQ][D / 2];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        const int row = wrow0 + nq * 32 + j;
+#pragma unroll
+        for (int cc = 0; cc < D / 8; ++cc) {
+            f32x4 x = {0.f, 0.f, 0.f, 0.f};
+            if (row < n) x = Io<T>::load4(p.q, head_off + (long long)row * D + 8 * cc + 4 * h);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) qf[nq][4 * cc + t] = x[t] * p.qscale;
+        }
+    }
+
+    float mrun[NQ], srun[NQ];
+    f32x16 oacc[NQ][MB];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        mrun[nq] = -INFINITY;
+        srun[nq] = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[nq][mb][i] = 0.f;
+    }
+
+    f32x4 kst[LPT], vst[LPT];
+    auto gload = [&](int t) {
+        const int kb0 = kbeg + t * TKB;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) {
+            const int e = tid + i * NT;
+            const int row = e / QPR, c4 = e % QPR;
+            const int key = kb0 + row;
+            f32x4 kx = {0.f, 0.f, 0.f, 0.f}, vx = {0.f, 0.f, 0.f, 0.f};
+            if (key < kend) {               // rows past the chunk are zero (and masked below)
+                const long long off = head_off + (long long)key * D + 4 * c4;
+                kx = Io<T>::load4(p.k, off);
+                vx = Io<T>::load4(p.v, off);
+            }
+            kst[i] = kx;
+            vst[i] = vx;
+        }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) {
+            const int e = tid + i * NT;
+            const int row = e / QPR, c4 = e % QPR;
+            *reinterpret_cast<f32x4 *>(&Ks[buf * KBUF + row * KROW + 4 * c4]) = kst[i];
+            *reinterpret_cast<f32x4 *>(&Vs[buf * VBUF + row * VROW + 4 * c4]) = vst[i];
+        }
+    };
+
+    if (ntiles > 0) {
+        gload(0);
+        lstore(0);
+        __syncthreads();
+    }
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) gload(t + 1);
+        const float *Kb = Ks + buf * KBUF;
+        const float *Vb = Vs + buf * VBUF;
+#pragma unroll
+        for (int ks = 0; ks < KS / 32; ++ks) {
+            const int kl = wk * KS + ks * 32;           // first key of the step inside the tile
+            const int kg = kbeg + t * TKB + kl;         // its global index
+            const int wave_last_row = wrow0 + NQ * 32 - 1;
+            if (kg >= kend || (p.causal && kg > wave_last_row)) continue;   // nothing visible (wave-uniform)
+
+            // ---- (a1) S^T = K Q^T
+            f32x16 sacc[NQ];
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[nq][i] = 0.f;
+#pragma unroll
+            for (int cc = 0; cc < D / 8; ++cc) {
+                const f32x4 kf = *reinterpret_cast<const f32x4 *>(&Kb[(kl + j) * KROW + 8 * cc + 4 * h]);
+#pragma unroll
+                for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq) sacc[nq] = mfma32(kf[tt], qf[nq][4 * cc + tt], sacc[nq]);
+            }
+
+            // ---- (a2) masks: only on steps that straddle the chunk end or the diagonal
+            const bool need_mask = (kg + 32 > kend) || (p.causal && kg + 31 > wrow0);
+            if (need_mask) {
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) {
+                    const int row = wrow0 + nq * 32 + j;
+                    const int lim = p.causal ? min(kend, row + 1) : kend;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = kg + 8 * (i >> 2) + 4 * h + (i & 3);
+                        if (key >= lim) sacc[nq][i] = -INFINITY;
+                    }
+                }
+            }
+
+            // ---- (a3) fold the tile into (m, S, W): merge operator with the tile's state
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq) {
+                float mt = sacc[nq][0];
+#pragma unroll
+                for (int i = 1; i < 16; ++i) mt = fmaxf(mt, sacc[nq][i]);
+                mt = half_max(mt);                       // the other 16 keys of this query
+                const float mnew = fmaxf(mrun[nq], mt);
+                const float msafe = (mnew == -INFINITY) ? 0.f : mnew;   // identity (+) identity = identity
+                const float alpha = exp2_fast(mrun[nq] - msafe);
+                mrun[nq] = mnew;
+                float ps = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float e = exp2_fast(sacc[nq][i] - msafe);
+                    sacc[nq][i] = e;
+                    ps += e;
+                }
+                srun[nq] = srun[nq] * alpha + ps;
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
+            }
+
+            // ---- (a4) W^T += V^T P^T.  Step i contracts keys 8g+t (lower half-wave) and
+            // 8g+4+t (upper), which is where accumulator register i = 4g+t holds them.
+            // Row r of block mb of W^T is value column MB*r + mb.
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int key = kl + 8 * (i >> 2) + 4 * h + (i & 3);
+                if constexpr (MB == 2) {
+                    const f32x2 vf = *reinterpret_cast<const f32x2 *>(&Vb[key * VROW + 2 * j]);
+#pragma unroll
+                    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+                        for (int nq = 0; nq < NQ; ++nq) oacc[nq][mb] = mfma32(vf[mb], sacc[nq][i], oacc[nq][mb]);
+                } else {
+                    const f32x4 vf = *reinterpret_cast<const f32x4 *>(&Vb[key * VROW + 4 * j]);
+#pragma unroll
+                    for (int mb = 0; mb < 4; ++mb)
+#pragma unroll
+                        for (int nq = 0; nq < NQ; ++nq) oacc[nq][mb] = mfma32(vf[mb], sacc[nq][i], oacc[nq][mb]);
+                }
+            }
+        }
+        if (t + 1 < ntiles) lstore(buf ^ 1);
+        __syncthreads();
+    }
+
+    // per-query normaliser: the two half-waves hold disjoint keys under the same maximum
+    float stot[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) stot[nq] = half_sum(srun[nq]);
+
+    // ---- (a5) waves that split the key range merge their states through LDS
+    if constexpr (WK > 1) {
+        constexpr int NS = NQ * (2 + MB * 16);          // floats of state per lane
+        float *xs = smem;                               // K/V tiles are dead: every wave passed the last barrier
+#pragma unroll
+        for (int s = WK / 2; s >= 1; s >>= 1) {
+            if (wk >= s && wk < 2 * s) {
+                float *dst = xs + ((wk - s) * WQ + wq) * NS * 64 + lane;
+                int idx = 0;
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) {
+                    dst[64 * idx++] = mrun[nq];
+                    dst[64 * idx++] = stot[nq];
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) dst[64 * idx++] = oacc[nq][mb][i];
+                }
+            }
+            __syncthreads();
+            if (wk < s) {
+                const float *src = xs + (wk * WQ + wq) * NS * 64 + lane;
+                int idx = 0;
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) {
+                    const float mb_ = src[64 * idx++];
+                    const float sb = src[64 * idx++];
+                    const float mnew = fmaxf(mrun[nq], mb_);
+                    const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+                    const float fa = exp2_fast(mrun[nq] - msafe);
+                    const float fb = exp2_fast(mb_ - msafe);
+                    mrun[nq] = mnew;
+                    stot[nq] = stot[nq] * fa + sb * fb;
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            oacc[nq][mb][i] = oacc[nq][mb][i] * fa + src[64 * idx++] * fb;
+                }
+            }
+            __syncthreads();
+        }
+        if (wk != 0) return;
+    }
+
+    // ---- (a7) normalise and store, or emit the block state
+    const bool partial = p.emit_partials != 0;
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        const int row = wrow0 + nq * 32 + j;
+        if (row >= n) continue;
+        float f = 1.f;
+        long long obase;
+        if (partial) {
+            const long long prow = (bh * p.num_splits + c) * (long long)n + row;
+            if (h == 0) {
+                p.part_m[prow] = p.m_natural ? mrun[nq] * kLn2 : mrun[nq];
+                p.part_S[prow] = stot[nq];
+            }
+            obase = prow * D;
+        } else {
+            f = stot[nq] > 0.f ? 1.f / stot[nq] : 0.f;
+            obase = head_off + (long long)row * D;
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            if constexpr (MB == 2) {
+#pragma unroll
+                for (int t2 = 0; t2 < 4; t2 += 2) {
+                    const f32x4 x = {oacc[nq][0][4 * g + t2] * f, oacc[nq][1][4 * g + t2] * f,
+                                     oacc[nq][0][4 * g + t2 + 1] * f, oacc[nq][1][4 * g + t2 + 1] * f};
+                    const int dv = 2 * (8 * g + 4 * h + t2);
+                    if (partial) Io<float>::store4(p.part_W, obase + dv, x);
+                    else Io<T>::store4(p.out, obase + dv, x);
+                }
+            } else {
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const f32x4 x = {oacc[nq][0][4 * g + t] * f, oacc[nq][1][4 * g + t] * f,
+                                     oacc[nq][2][4 * g + t] * f, oacc[nq][3][4 * g + t] * f};
+                    const int dv = 4 * (8 * g + 4 * h + t);
+                    if (partial) Io<float>::store4(p.part_W, obase + dv, x);
+                    else Io<T>::store4(p.out, obase + dv, x);
+                }
+            }
+        }
+    }
+}
+
+// ---- variants -------------------------------------------------------------------------------
+
+struct MfmaVariant {
+    const char *name;
+    int tq;
+};
+//                                   id 1            id 2             id 3                 id 4
+static const MfmaVariant kVariants[kMfmaVariants] = {
+    {"mfma_q128_w4", 128}, {"mfma_q256_w4", 256}, {"mfma_xwave", 32}, {"mfma_q256_w8", 256}};
+
+int mfma_variant_tq(int variant, int d) {
+    if (variant < 1 || variant > kMfmaVariants) return 0;
+    if (variant == 3 && d == 128) return 64;    // two query waves x two key waves
+    return kVariants[variant - 1].tq;
+}
+const char *mfma_variant_name(int variant) {
+    return (variant >= 1 && variant <= kMfmaVariants) ? kVariants[variant - 1].name : nullptr;
+}
+
+template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE>
+static int launch_one(const FwdParams &p, hipStream_t s) {
+    constexpr int TKB = KS * WK;
+    constexpr size_t kv_bytes = (size_t)2 * (TKB * (D + 4) + TKB * D) * sizeof(float);
+    constexpr size_t xw_bytes = WK > 1 ? (size_t)(WK / 2) * WQ * NQ * (2 + D / 2) * 64 * sizeof(float) : 0;
+    constexpr size_t smem = kv_bytes > xw_bytes ? kv_bytes : xw_bytes;
+    auto kern = fwd_mfma_kernel<D, T, NQ, WQ, WK, KS, WPE>;
+    static bool attr_done = false;          // per instantiation; idempotent, so a race is harmless
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return (int)e;
+        attr_done = true;
+    }
+    const long long total = (long long)p.q_tiles * p.B * p.H * p.num_splits;
+    long long blocks = total;
+    if (p.xcd_map) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * WQ * WK), smem, s, p);
+    return (int)hipGetLastError();
+}
+
+template <int D, typename T>
+static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
+    // tile height per LDS buffer is 64 keys for d = 64 and 32 keys for d = 128 (same bytes)
+    constexpr int KS = D == 64 ? 64 : 32;
+    switch (variant) {
+        case 1: return launch_one<D, T, 1, 4, 1, KS, 2>(p, s);
+        case 2: return launch_one<D, T, 2, 4, 1, KS, 2>(p, s);
+        case 3:
+            if constexpr (D == 64) return launch_one<D, T, 1, 1, 4, 32, 2>(p, s);
+            else return launch_one<D, T, 1, 2, 2, 32, 2>(p, s);
+        case 4: return launch_one<D, T, 1, 8, 1, KS, 4>(p, s);
+        default: return (int)hipErrorInvalidValue;
+    }
+}
+
+int launch_fwd_mfma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name) {
+    if (name) *name = mfma_variant_name(variant);
+    if (d == 64) return f16 ? launch_variant<64, _Float16>(p, variant, s) : launch_variant<64, float>(p, variant, s);
+    if (d == 128) return f16 ? launch_variant<128, _Float16>(p, variant, s) : launch_variant<128, float>(p, variant, s);
+    return (int)hipErrorInvalidValue;
+}
+
+}  // namespace elsa

@@ -1,0 +1,171 @@
+"""ctypes binding of libelsa.so: argument marshalling only.
+
+Every step of the attention path runs in the HIP kernels behind the C ABI
+declared in ``include/elsa.h``; PyTorch is used for device memory and streams.
+Importing this module fails loudly when the library has not been built --
+there is no CPU fallback.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libelsa.so")
+
+F32, F16 = 0, 1
+OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP = 0, 1, 2, 3
+PATH_AUTO, PATH_FMA, PATH_MFMA = 0, 1, 2
+
+EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_split_kv", "elsa_combine",
+           "elsa_split_kv_workspace_bytes", "elsa_set_workspace", "elsa_set_option", "elsa_get_option",
+           "elsa_variant_name", "elsa_last_kernel", "elsa_status_string", "elsa_debug_layout_probe")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("libelsa.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
+                      "(or python paper_2604_23798_amd/build.py) first; there is no fallback path")
+
+_lib = ctypes.CDLL(LIB_PATH)
+_vp, _i, _f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
+_lib.elsa_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _i, _vp]
+_lib.elsa_attn_fwd_masked.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
+_lib.elsa_attn_fwd_split_kv.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _i, _vp]
+_lib.elsa_combine.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]
+_lib.elsa_split_kv_workspace_bytes.argtypes = [_i, _i, _i, _i, _i]
+_lib.elsa_split_kv_workspace_bytes.restype = ctypes.c_size_t
+_lib.elsa_set_workspace.argtypes = [_vp, ctypes.c_size_t]
+_lib.elsa_set_option.argtypes = [_i, _i]
+_lib.elsa_get_option.argtypes = [_i, ctypes.POINTER(_i)]
+_lib.elsa_variant_name.argtypes = [_i, _i]
+_lib.elsa_variant_name.restype = ctypes.c_char_p
+_lib.elsa_last_kernel.restype = ctypes.c_char_p
+_lib.elsa_status_string.argtypes = [_i]
+_lib.elsa_status_string.restype = ctypes.c_char_p
+_lib.elsa_debug_layout_probe.argtypes = [_vp, _vp]
+
+
+class ElsaError(RuntimeError):
+    def __init__(self, code):
+        self.code = code
+        super().__init__("libelsa: %s (code %d)" % (status_string(code), code))
+
+
+def status_string(code: int) -> str:
+    return _lib.elsa_status_string(int(code)).decode()
+
+
+def _check(rc):
+    if rc != 0:
+        raise ElsaError(rc)
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.float16:
+        return F16
+    raise TypeError("q/k/v must be float32 or float16")
+
+
+def _shape(q, k, v):
+    assert q.is_cuda and k.is_cuda and v.is_cuda, "device tensors required"
+    assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
+    assert q.dim() == 4 and q.shape == k.shape == v.shape and q.dtype == k.dtype == v.dtype
+    return tuple(int(x) for x in q.shape)
+
+
+def elsa_attn_fwd(q, k, v, out, scale, causal=False, stream=None):
+    B, H, n, d = _shape(q, k, v)
+    assert out.is_contiguous() and out.shape == q.shape and out.dtype == q.dtype
+    _check(_lib.elsa_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, n, d, float(scale), int(bool(causal)),
+                              _dtype_code(q), _stream(stream)))
+    return out
+
+
+def elsa_attn_fwd_masked(q, k, v, out, scale, causal=False, kv_len=None, stream=None):
+    import torch
+    B, H, n, d = _shape(q, k, v)
+    assert out.is_contiguous() and out.shape == q.shape and out.dtype == q.dtype
+    if kv_len is not None:
+        assert kv_len.is_cuda and kv_len.dtype == torch.int32 and kv_len.shape == (B,) and kv_len.is_contiguous()
+    _check(_lib.elsa_attn_fwd_masked(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, n, d, float(scale),
+                                     int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
+    return out
+
+
+def elsa_attn_fwd_split_kv(q, k, v, part_m, part_S, part_W, scale, num_splits, causal=False, kv_len=None,
+                           stream=None):
+    import torch
+    B, H, n, d = _shape(q, k, v)
+    C = int(num_splits)
+    for t, shp in ((part_m, (B, H, C, n)), (part_S, (B, H, C, n)), (part_W, (B, H, C, n, d))):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == shp
+    _check(_lib.elsa_attn_fwd_split_kv(_ptr(q), _ptr(k), _ptr(v), _ptr(part_m), _ptr(part_S), _ptr(part_W),
+                                       B, H, n, d, float(scale), int(bool(causal)), _ptr(kv_len), C,
+                                       _dtype_code(q), _stream(stream)))
+    return part_m, part_S, part_W
+
+
+def elsa_combine(part_m, part_S, part_W, out, stream=None):
+    import torch
+    B, H, C, n, d = (int(x) for x in part_W.shape)
+    assert tuple(part_m.shape) == (B, H, C, n) == tuple(part_S.shape)
+    for t in (part_m, part_S, part_W):
+        assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32
+    assert out.is_cuda and out.is_contiguous() and tuple(out.shape) == (B, H, n, d)
+    _check(_lib.elsa_combine(_ptr(part_m), _ptr(part_S), _ptr(part_W), _ptr(out), B, H, n, d, C,
+                             _dtype_code(out), _stream(stream)))
+    return out
+
+
+def elsa_split_kv_workspace_bytes(B, H, n, d, num_splits) -> int:
+    return int(_lib.elsa_split_kv_workspace_bytes(B, H, n, d, num_splits))
+
+
+def elsa_set_workspace(buf):
+    """Lend a device byte buffer (torch uint8 tensor, kept alive by the caller) or None."""
+    if buf is None:
+        _check(_lib.elsa_set_workspace(None, 0))
+    else:
+        assert buf.is_cuda and buf.is_contiguous()
+        _check(_lib.elsa_set_workspace(_ptr(buf), buf.numel() * buf.element_size()))
+
+
+def elsa_set_option(option, value):
+    _check(_lib.elsa_set_option(int(option), int(value)))
+
+
+def elsa_get_option(option) -> int:
+    v = ctypes.c_int(0)
+    _check(_lib.elsa_get_option(int(option), ctypes.byref(v)))
+    return v.value
+
+
+def elsa_variant_name(path, variant):
+    r = _lib.elsa_variant_name(int(path), int(variant))
+    return None if r is None else r.decode()
+
+
+def elsa_last_kernel() -> str:
+    return _lib.elsa_last_kernel().decode()
+
+
+def elsa_debug_layout_probe(out, stream=None):
+    _check(_lib.elsa_debug_layout_probe(_ptr(out), _stream(stream)))
+    return out
+
+
+def raw():
+    """The ctypes library handle (for ABI tests)."""
+    return _lib

@@ -1,0 +1,74 @@
+"""GPU parity at the full workload sizes, in the launch configuration the benchmark times
+(library defaults), on seeded row samples the oracle computes one by one (first/last row,
+tile-boundary neighbours, random rows per head).  Rows are independent, so a sampled row is a
+complete check of that row."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_23798_amd import inputs
+from tests import gpu_util as G
+from tests.parity import assert_parity, tolerance
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not G.have_gpu():
+        pytest.skip("no GPU")
+    from paper_2604_23798_amd import elsa  # noqa: F401
+
+
+def _check(w, per_head, **opts):
+    q, k, v, kv_len = inputs.make(w)
+    rows = inputs.sample_rows(w, per_head=per_head)
+    f32 = lambda t: t.astype(np.float32)
+    ref = oracle.attn_rows(f32(q), f32(k), f32(v), w.scale, causal=w.causal, kv_len=kv_len, rows=rows)
+    with G.Options(**opts):
+        out = G.fwd(q, k, v, w.scale, causal=w.causal, kv_len=kv_len, rows=rows)
+    return assert_parity(out, ref, tolerance(w.n, w.fp16), "%s %s" % (w.name, opts or "default"))
+
+
+def test_vit_b16_224_all_rows():
+    w = inputs.WORKLOADS["vit_b16_224"]
+    _check(w, per_head=w.n)
+
+
+@pytest.mark.parametrize("name", ["bert_base", "bert_base_padded"])
+def test_bert_base(name):
+    _check(inputs.WORKLOADS[name], per_head=12)
+
+
+@pytest.mark.parametrize("fp16", [False, True])
+@pytest.mark.parametrize("n", [1024, 2048, 4096, 8192, 16384])
+def test_long_sequence_sweep(n, fp16):
+    _check(inputs.sweep(n, fp16), per_head=24)
+
+
+def test_sweep_16k_vector_fma_path():
+    _check(inputs.sweep(16384), per_head=8, path=1)
+
+
+@pytest.mark.parametrize("name", ["llama13b_32k", "llama13b_32k_fp16"])
+def test_llama13b_causal_32k(name):
+    _check(inputs.WORKLOADS[name], per_head=12)
+
+
+def test_hires_vit_64k_wide_scores():
+    m = _check(inputs.WORKLOADS["hires_vit_64k"], per_head=24)
+    assert m["max_abs"] < 1e-3
+
+
+def test_small_workloads_with_workspace_split():
+    """The two short workloads again with a lent workspace, so the library splits the key range."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    elsa.elsa_set_workspace(ws)
+    try:
+        _check(inputs.WORKLOADS["vit_b16_224"], per_head=197, splits=2)
+        _check(inputs.sweep(1024), per_head=24)
+        _check(inputs.sweep(2048), per_head=24)
+    finally:
+        elsa.elsa_set_workspace(None)

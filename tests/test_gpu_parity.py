@@ -1,0 +1,246 @@
+"""GPU parity: the HIP path (through the C ABI) against the FP64 oracle, element by element,
+on seeded inputs small enough for the full oracle yet spanning several tiles and ragged tails."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_23798_amd import inputs
+from tests import gpu_util as G
+from tests.parity import assert_parity, tolerance
+
+pytestmark = pytest.mark.gpu
+
+MFMA, FMA = 2, 1
+ALL_KERNELS = [(MFMA, 1), (MFMA, 2), (MFMA, 3), (MFMA, 4), (FMA, 1), (FMA, 2)]
+
+
+def _rand(B, H, n, d, seed, sigma=1.0, fp16=False):
+    cnt = B * H * n * d
+    sh = (B, H, n, d)
+    q = inputs.normal(seed, 0, 0, cnt, sigma).reshape(sh)
+    k = inputs.normal(seed, 1, 0, cnt, sigma).reshape(sh)
+    v = inputs.normal(seed, 2, 0, cnt).reshape(sh)
+    if fp16:
+        q, k, v = (t.astype(np.float16) for t in (q, k, v))
+    return q, k, v
+
+
+def _f32(*ts):
+    return tuple(t.astype(np.float32) for t in ts)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not G.have_gpu():
+        pytest.skip("no GPU")
+    from paper_2604_23798_amd import elsa  # noqa: F401  (fails loudly if the library is missing)
+
+
+def test_mfma_layout_and_half_wave_exchange():
+    """The operand maps the forward kernel is built on, read back from the hardware."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    out = torch.zeros(5 * 16 * 64, device="cuda")
+    elsa.elsa_debug_layout_probe(out)
+    torch.cuda.synchronize()
+    r = out.cpu().numpy().reshape(5, 16, 64)
+    lane = np.arange(64)
+    for i in range(16):
+        assert np.array_equal(r[0, i], 8 * (i // 4) + 4 * (lane // 32) + (i % 4) + 1), ("row map", i)
+        assert np.array_equal(r[1, i], lane % 32 + 1), ("column map", i)
+        assert np.all(r[2, i] == 1.0), ("k index = lane / 32", i)
+    assert np.array_equal(r[3, 0], lane % 32 + 32)
+    assert np.array_equal(r[3, 1], 2 * (lane % 32) + 32)
+    ex = 2.0 ** (-lane / 8.0)
+    assert np.all(np.abs(r[4, 0] - ex) <= 4 * 2.0 ** -24 * ex)
+
+
+@pytest.mark.parametrize("path,variant", ALL_KERNELS)
+@pytest.mark.parametrize("shape", [(1, 2, 197, 64), (2, 2, 330, 64), (1, 2, 300, 128)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_small_problems_every_kernel(path, variant, shape, causal):
+    B, H, n, d = shape
+    q, k, v = _rand(B, H, n, d, 100 + n)
+    scale = 1.0 / math.sqrt(d)
+    ref = oracle.attn_rows(q, k, v, scale, causal=causal)
+    with G.Options(path=path, variant=variant):
+        out = G.fwd(q, k, v, scale, causal=causal)
+    assert_parity(out, ref, tolerance(n), "path%d v%d %s causal=%d" % (path, variant, shape, causal))
+
+
+@pytest.mark.parametrize("path,variant", [(MFMA, 1), (MFMA, 3), (FMA, 1)])
+@pytest.mark.parametrize("d", [64, 128])
+def test_fp16_io(path, variant, d):
+    B, H, n = 1, 3, 450
+    q, k, v = _rand(B, H, n, d, 7, fp16=True)
+    scale = 1.0 / math.sqrt(d)
+    for causal in (False, True):
+        ref = oracle.attn_rows(*_f32(q, k, v), scale, causal=causal)
+        with G.Options(path=path, variant=variant):
+            out = G.fwd(q, k, v, scale, causal=causal)
+        assert_parity(out, ref, tolerance(n, fp16=True), "fp16 path%d v%d d%d causal=%d" % (path, variant, d, causal))
+
+
+@pytest.mark.parametrize("path,variant", ALL_KERNELS)
+def test_key_padding_mask(path, variant):
+    B, H, n, d = 5, 2, 200, 64
+    q, k, v = _rand(B, H, n, d, 21)
+    kv_len = np.array([200, 1, 0, 129, 64], np.int32)
+    for causal in (False, True):
+        ref = oracle.attn_rows(q, k, v, 0.125, causal=causal, kv_len=kv_len)
+        with G.Options(path=path, variant=variant):
+            out = G.fwd(q, k, v, 0.125, causal=causal, kv_len=kv_len)
+        assert_parity(out, ref, tolerance(n), "padding path%d v%d causal=%d" % (path, variant, causal))
+        o = out.reshape(B, H, n, d)
+        assert np.all(o[2] == 0.0)                                   # no visible key -> zeros
+        if not causal:
+            assert np.all(np.abs(o[1] - v[1, :, :1].astype(np.float64)) <= 1e-6)   # kv_len = 1 -> v_0
+    # kv_len = n through the masked entry point equals the unmasked call bit for bit
+    with G.Options(path=path, variant=variant):
+        a = G.fwd(q, k, v, 0.125, kv_len=np.full(B, n, np.int32))
+        b = G.fwd(q, k, v, 0.125)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("path,variant", [(MFMA, 1), (MFMA, 3), (FMA, 1), (FMA, 2)])
+@pytest.mark.parametrize("C", [1, 2, 3, 7])
+@pytest.mark.parametrize("causal", [False, True])
+def test_split_kv_states_and_combine(path, variant, C, causal):
+    import torch
+    from paper_2604_23798_amd import elsa
+    B, H, n, d = 1, 2, 300, 64
+    q, k, v = _rand(B, H, n, d, 33)
+    scale = 0.125
+    tol = tolerance(n)
+    om, oS, oW = oracle.partials_rows(q, k, v, scale, C, causal=causal)
+    with G.Options(path=path, variant=variant):
+        pm, pS, pW = G.split_kv(q, k, v, scale, C, causal=causal)
+    gm, gS, gW = G.parts_to_rows(pm, pS, pW)
+    ident = np.isneginf(om)
+    # masked chunks are the identity exactly
+    assert np.array_equal(np.isneginf(gm), ident)
+    assert np.all(gS[ident] == 0.0) and np.all(gW[ident] == 0.0)
+    live = ~ident
+    # the chunk maximum in natural-log units
+    assert np.all(np.abs(gm[live] - om[live]) <= 4e-6 * (1 + np.abs(om[live])))
+    # canonical form: log of the unnormalised mass, and the chunk's own weighted mean
+    lse_g = gm[live] + np.log(gS[live])
+    lse_o = om[live] + np.log(oS[live])
+    assert np.all(np.abs(lse_g - lse_o) <= 1e-5)
+    assert_parity((gW[live] / gS[live][:, None]), (oW[live] / oS[live][:, None]), tol, "chunk means C=%d" % C)
+    # second pass on the device states
+    out = torch.full((B, H, n, d), float("nan"), device="cuda")
+    elsa.elsa_combine(pm, pS, pW, out)
+    torch.cuda.synchronize()
+    ref = oracle.attn_rows(q, k, v, scale, causal=causal)
+    assert_parity(out.reshape(-1, d).double().cpu().numpy(), ref, tol, "combine C=%d causal=%d" % (C, causal))
+
+
+@pytest.mark.parametrize("d,fp16_out", [(64, False), (128, False), (64, True)])
+def test_combine_alone_on_oracle_states(d, fp16_out):
+    """elsa_combine fed with block states written by the oracle (incl. identities)."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    B, H, n, C = 1, 2, 150, 5
+    q, k, v = _rand(B, H, n, d, 44)
+    om, oS, oW = oracle.partials_rows(q, k, v, 0.2, C, causal=True)
+    pm = torch.from_numpy(om.reshape(B, H, n, C).transpose(0, 1, 3, 2).astype(np.float32).copy()).cuda()
+    pS = torch.from_numpy(oS.reshape(B, H, n, C).transpose(0, 1, 3, 2).astype(np.float32).copy()).cuda()
+    pW = torch.from_numpy(oW.reshape(B, H, n, C, d).transpose(0, 1, 3, 2, 4).astype(np.float32).copy()).cuda()
+    out = torch.full((B, H, n, d), float("nan"), device="cuda", dtype=torch.float16 if fp16_out else torch.float32)
+    elsa.elsa_combine(pm, pS, pW, out)
+    torch.cuda.synchronize()
+    ref = oracle.attn_rows(q, k, v, 0.2, causal=True)
+    assert_parity(out.reshape(-1, d).double().cpu().numpy(), ref, tolerance(n, fp16_out), "combine alone d=%d" % d)
+    # all-identity rows give zeros
+    pm[:] = float("-inf")
+    pS[:] = 0
+    pW[:] = 0
+    elsa.elsa_combine(pm, pS, pW, out)
+    torch.cuda.synchronize()
+    assert torch.all(out == 0)
+
+
+@pytest.mark.parametrize("path", [MFMA, FMA])
+def test_internal_split_through_workspace(path):
+    import torch
+    from paper_2604_23798_amd import elsa
+    B, H, n, d = 1, 2, 1100, 64
+    q, k, v = _rand(B, H, n, d, 55)
+    ref = oracle.attn_rows(q, k, v, 0.125)
+    refc = oracle.attn_rows(q, k, v, 0.125, causal=True)
+    ws = torch.empty(elsa.elsa_split_kv_workspace_bytes(B, H, n, d, 4), dtype=torch.uint8, device="cuda")
+    elsa.elsa_set_workspace(ws)
+    try:
+        with G.Options(path=path, splits=4):
+            out = G.fwd(q, k, v, 0.125)
+            outc = G.fwd(q, k, v, 0.125, causal=True)
+        with G.Options(path=path):           # auto: small problem + workspace -> splits on its own
+            outa = G.fwd(q, k, v, 0.125)
+    finally:
+        elsa.elsa_set_workspace(None)
+    assert_parity(out, ref, tolerance(n), "workspace split")
+    assert_parity(outc, refc, tolerance(n), "workspace split causal")
+    assert_parity(outa, ref, tolerance(n), "workspace auto split")
+
+
+@pytest.mark.parametrize("path,variant", ALL_KERNELS)
+def test_degenerate_sizes(path, variant):
+    for n in (1, 2, 31, 32, 33, 64, 65):
+        q, k, v = _rand(1, 1, n, 64, 60 + n)
+        with G.Options(path=path, variant=variant):
+            out = G.fwd(q, k, v, 0.125)
+            outc = G.fwd(q, k, v, 0.125, causal=True)
+        assert_parity(out, oracle.attn_rows(q, k, v, 0.125), 2e-5, "n=%d" % n)
+        assert_parity(outc, oracle.attn_rows(q, k, v, 0.125, causal=True), 2e-5, "n=%d causal" % n)
+        assert np.all(np.abs(outc[0] - v[0, 0, 0]) <= 1e-6)              # causal row 0 sees only itself
+
+
+@pytest.mark.parametrize("path,variant", [(MFMA, 1), (MFMA, 3), (FMA, 1)])
+def test_wide_scores_one_hot_and_shift(path, variant):
+    # scores with sigma ~ 64 (the high-resolution ViT recipe): rescaling path, no inf/nan
+    q, k, v = _rand(1, 2, 700, 64, 71, sigma=8.0)
+    with G.Options(path=path, variant=variant):
+        out = G.fwd(q, k, v, 0.125)
+    assert_parity(out, oracle.attn_rows(q, k, v, 0.125), 1e-4, "wide scores")
+    # one dominant key per row -> its value row, to FP32 roundoff
+    q, k, v = _rand(1, 1, 256, 64, 72)
+    k[0, 0, 100] = 0
+    q[..., 0] = 1.0
+    k[..., 0] = 0
+    k[0, 0, 100, 0] = 2000.0                 # scaled gap 250 >> 104: every other weight underflows to 0
+    with G.Options(path=path, variant=variant):
+        out = G.fwd(q, k, v, 0.125)
+    assert np.all(out == v[0, 0, 100].astype(np.float64)[None, :])
+    # Shifting every score of a row by a constant c leaves the output unchanged in real arithmetic.
+    # In FP32 the shifted dot products are rounded at ulp(|c|), so the weights move by about
+    # u*|c| per accumulation step: the bound below is 32*u*|c| (plus the ordinary tolerance).
+    q, k, v = _rand(1, 2, 300, 64, 73)
+    q[..., 0] = 1.0
+    k[..., 0] = np.round(k[..., 0] * 4) / 4
+    ref = oracle.attn_rows(q, k, v, 0.125)
+    for c in (-30.0, 50.0, -400.0, 1000.0):
+        k2 = k.copy()
+        k2[..., 0] += np.float32(c / 0.125)
+        with G.Options(path=path, variant=variant):
+            out = G.fwd(q, k2, v, 0.125)
+        assert_parity(out, ref, 2e-5 + 32 * 2.0 ** -24 * abs(c), "shift %g" % c)
+
+
+def test_deterministic_and_option_reporting():
+    from paper_2604_23798_amd import elsa
+    q, k, v = _rand(1, 4, 777, 64, 81)
+    for path, variant in ALL_KERNELS:
+        with G.Options(path=path, variant=variant):
+            a = G.fwd(q, k, v, 0.125)
+            name = elsa.elsa_last_kernel()
+            b = G.fwd(q, k, v, 0.125)
+        assert np.array_equal(a, b)
+        assert name == elsa.elsa_variant_name(path, variant)
+    with G.Options(path=MFMA, variant=1, xcd_map=2):
+        c = G.fwd(q, k, v, 0.125)
+    with G.Options(path=MFMA, variant=1, xcd_map=1):
+        d_ = G.fwd(q, k, v, 0.125)
+    assert np.array_equal(c, d_)            # the block-to-work mapping does not change any result
