@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--xcd-map", type=int, default=0)
     ap.add_argument("--oracle-rows", type=int, default=4096, help="row budget of the cpu_baseline leg (0 = skip)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
     a = ap.parse_args()
     if a.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus %d is not supported (no collectives, no sharding)."
@@ -84,6 +86,12 @@ def main():
     elsa.elsa_set_option(elsa.OPT_PATH, {"auto": 0, "fma": 1, "mfma": 2}[a.path])
     elsa.elsa_set_option(elsa.OPT_VARIANT, a.variant)
     elsa.elsa_set_option(elsa.OPT_XCD_MAP, a.xcd_map)
+
+    if a.calibrate_copy:               # a copy kernel of known size: 256 MiB read + 256 MiB written
+        src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
 
     def step():
         elsa.elsa_attn_fwd_masked(tq, tk, tv, out, w.scale, w.causal, tl)

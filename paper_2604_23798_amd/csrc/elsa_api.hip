@@ -31,17 +31,19 @@ int variant_tq(int path, int variant, int d) {
     return path == 1 ? elsa::fma_variant_tq(variant, d) : elsa::mfma_variant_tq(variant, d);
 }
 
-// Tile configuration when the caller did not force one: the largest query tile that
-// still yields about two blocks per CU, otherwise the configuration whose waves split
-// the key range so that a short sequence still spreads over many blocks.
+// Tile configuration when the caller did not force one.  Measured on MI355X: the 256-row tile
+// (two query groups per wave) wins once it still yields two blocks per CU; below that the
+// 128-row tile; when even that leaves CUs idle, the configuration whose waves split the keys.
 int pick_variant(int path, long long BH, int n, int d, int splits) {
     if (g.opt[ELSA_OPT_VARIANT] >= 1 && g.opt[ELSA_OPT_VARIANT] <= variant_count(path)) return g.opt[ELSA_OPT_VARIANT];
     if (path == 1) {
         const long long blocks = BH * ((n + 255) / 256) * splits;
         return blocks >= kNumCu ? 1 : 2;
     }
+    const long long b256 = BH * ((n + 255) / 256) * splits;
     const long long b128 = BH * ((n + 127) / 128) * splits;
-    return b128 >= 2 * kNumCu ? 1 : (b128 >= kNumCu / 2 ? 1 : 3);
+    if (d == 64 && b256 >= 2 * kNumCu) return 2;
+    return b128 >= (3 * kNumCu) / 4 ? 1 : 3;
 }
 
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
@@ -85,8 +87,8 @@ void carve(void *ws, int B, int H, int n, int d, int C, float **pm, float **pS, 
     (void)d;
 }
 
-// Number of key chunks for elsa_attn_fwd when a workspace is lent: enough blocks for
-// about two per CU, chunks no shorter than 256 keys, and only if the workspace holds them.
+// Number of key chunks for elsa_attn_fwd when a workspace is lent: enough 128-row blocks for
+// two per CU, chunks no shorter than 256 keys, at most 8, and only if the workspace holds them.
 int auto_splits(int B, int H, int n, int d) {
     int C = g.opt[ELSA_OPT_SPLITS];
     if (C <= 0) {
@@ -96,7 +98,7 @@ int auto_splits(int B, int H, int n, int d) {
             C = (int)((2 * kNumCu + blocks - 1) / blocks);
             const int cap = n / 256 > 1 ? n / 256 : 1;
             if (C > cap) C = cap;
-            if (C > 16) C = 16;
+            if (C > 8) C = 8;
         }
     }
     if (C > n) C = n;

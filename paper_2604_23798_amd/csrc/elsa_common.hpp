@@ -99,7 +99,7 @@ int mfma_variant_tq(int variant, int d);   // queries per block of a variant (0 
 int fma_variant_tq(int variant, int d);
 const char *mfma_variant_name(int variant);
 const char *fma_variant_name(int variant);
-constexpr int kMfmaVariants = 4;
+constexpr int kMfmaVariants = 6;
 constexpr int kFmaVariants = 2;
 
 }  // namespace elsa

@@ -24,7 +24,7 @@ __device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
-template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE>
+template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int SCHED>
 __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p) {
     constexpr int NT = 64 * WQ * WK;
     constexpr int TQ = 32 * NQ * WQ;
@@ -130,31 +130,63 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
         lstore(0);
         __syncthreads();
     }
+    // first key that no lane of this wave can see
+    const int wave_lim = p.causal ? min(kend, wrow0 + NQ * 32) : kend;
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1;
         if (t + 1 < ntiles) gload(t + 1);
         const float *Kb = Ks + buf * KBUF;
         const float *Vb = Vs + buf * VBUF;
-#pragma unroll
-        for (int ks = 0; ks < KS / 32; ++ks) {
+        // 32-key steps of this tile in which this wave sees at least one key (wave-uniform count)
+        const int kg0 = kbeg + t * TKB + wk * KS;
+        const int nact = min(KS / 32, max(0, (wave_lim - kg0 + 31) / 32));
+#pragma unroll 1
+        for (int ks = 0; ks < nact; ++ks) {
             const int kl = wk * KS + ks * 32;           // first key of the step inside the tile
-            const int kg = kbeg + t * TKB + kl;         // its global index
-            const int wave_last_row = wrow0 + NQ * 32 - 1;
-            if (kg >= kend || (p.causal && kg > wave_last_row)) continue;   // nothing visible (wave-uniform)
+            const int kg = kg0 + ks * 32;               // its global index
 
-            // ---- (a1) S^T = K Q^T
+            // ---- (a1) S^T = K Q^T.  NACC independent accumulation chains, summed pairwise:
+            // fewer roundings at the magnitude of the full dot product.
             f32x16 sacc[NQ];
+            {
+                f32x16 part[NQ][NACC];
 #pragma unroll
-            for (int nq = 0; nq < NQ; ++nq)
+                for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) sacc[nq][i] = 0.f;
+                    for (int a = 0; a < NACC; ++a)
 #pragma unroll
-            for (int cc = 0; cc < D / 8; ++cc) {
-                const f32x4 kf = *reinterpret_cast<const f32x4 *>(&Kb[(kl + j) * KROW + 8 * cc + 4 * h]);
+                        for (int i = 0; i < 16; ++i) part[nq][a][i] = 0.f;
+                if constexpr (SCHED & 1) __builtin_amdgcn_s_setprio(1);
+                // K fragments are fetched one column group ahead of the MFMAs that consume them
+                const float *krow = &Kb[(kl + j) * KROW + 4 * h];
+                f32x4 kf = *reinterpret_cast<const f32x4 *>(krow);
 #pragma unroll
-                for (int tt = 0; tt < 4; ++tt)
+                for (int cc = 0; cc < D / 8; ++cc) {
+                    f32x4 kn = kf;
+                    if (cc + 1 < D / 8) kn = *reinterpret_cast<const f32x4 *>(krow + 8 * (cc + 1));
+                    constexpr int CPA = (D / 8) / NACC;     // column groups per chain
 #pragma unroll
-                    for (int nq = 0; nq < NQ; ++nq) sacc[nq] = mfma32(kf[tt], qf[nq][4 * cc + tt], sacc[nq]);
+                    for (int tt = 0; tt < 4; ++tt)
+#pragma unroll
+                        for (int nq = 0; nq < NQ; ++nq)
+                            part[nq][cc / CPA] = mfma32(kf[tt], qf[nq][4 * cc + tt], part[nq][cc / CPA]);
+                    kf = kn;
+                }
+                // pin the order: two fragment reads in flight ahead of every group of MFMAs
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+                for (int cc = 0; cc < D / 8 - 2; ++cc) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 4 * NQ, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 8 * NQ, 0);
+                if constexpr (SCHED & 1) __builtin_amdgcn_s_setprio(0);
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) {
+                    if constexpr (NACC == 1) sacc[nq] = part[nq][0];
+                    else if constexpr (NACC == 2) sacc[nq] = part[nq][0] + part[nq][1];
+                    else sacc[nq] = (part[nq][0] + part[nq][1]) + (part[nq][2] + part[nq][3]);
+                }
             }
 
             // ---- (a2) masks: only on steps that straddle the chunk end or the diagonal
@@ -181,8 +213,16 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                 mt = half_max(mt);                       // the other 16 keys of this query
                 const float mnew = fmaxf(mrun[nq], mt);
                 const float msafe = (mnew == -INFINITY) ? 0.f : mnew;   // identity (+) identity = identity
-                const float alpha = exp2_fast(mrun[nq] - msafe);
-                mrun[nq] = mnew;
+                // the running state is rescaled only when some row of the wave moved its maximum
+                if (__builtin_amdgcn_ballot_w64(mnew > mrun[nq]) != 0) {
+                    const float alpha = exp2_fast(mrun[nq] - msafe);
+                    srun[nq] *= alpha;
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
+                    mrun[nq] = mnew;
+                }
                 float ps = 0.f;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
@@ -190,33 +230,37 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                     sacc[nq][i] = e;
                     ps += e;
                 }
-                srun[nq] = srun[nq] * alpha + ps;
-#pragma unroll
-                for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
+                srun[nq] += ps;
             }
 
             // ---- (a4) W^T += V^T P^T.  Step i contracts keys 8g+t (lower half-wave) and
             // 8g+4+t (upper), which is where accumulator register i = 4g+t holds them.
             // Row r of block mb of W^T is value column MB*r + mb.
+            if constexpr (SCHED & 2) __builtin_amdgcn_s_setprio(1);
+            {
+                typedef float vfrag __attribute__((ext_vector_type(MB)));
+                const float *vcol = &Vb[(kl + 4 * h) * VROW + MB * j];
+                vfrag vf = *reinterpret_cast<const vfrag *>(vcol);
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int key = kl + 8 * (i >> 2) + 4 * h + (i & 3);
-                if constexpr (MB == 2) {
-                    const f32x2 vf = *reinterpret_cast<const f32x2 *>(&Vb[key * VROW + 2 * j]);
+                for (int i = 0; i < 16; ++i) {
+                    vfrag vn = vf;                      // V fragments one key ahead of their MFMAs
+                    if (i + 1 < 16)
+                        vn = *reinterpret_cast<const vfrag *>(vcol + (8 * ((i + 1) >> 2) + ((i + 1) & 3)) * VROW);
 #pragma unroll
-                    for (int mb = 0; mb < 2; ++mb)
+                    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
                         for (int nq = 0; nq < NQ; ++nq) oacc[nq][mb] = mfma32(vf[mb], sacc[nq][i], oacc[nq][mb]);
-                } else {
-                    const f32x4 vf = *reinterpret_cast<const f32x4 *>(&Vb[key * VROW + 4 * j]);
-#pragma unroll
-                    for (int mb = 0; mb < 4; ++mb)
-#pragma unroll
-                        for (int nq = 0; nq < NQ; ++nq) oacc[nq][mb] = mfma32(vf[mb], sacc[nq][i], oacc[nq][mb]);
+                    vf = vn;
                 }
+                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+#pragma unroll
+                for (int i = 0; i < 14; ++i) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, MB * NQ, 0);
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                }
+                __builtin_amdgcn_sched_group_barrier(0x008, 2 * MB * NQ, 0);
             }
+            if constexpr (SCHED & 2) __builtin_amdgcn_s_setprio(0);
         }
         if (t + 1 < ntiles) lstore(buf ^ 1);
         __syncthreads();
@@ -317,31 +361,32 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 }
 
 // ---- variants -------------------------------------------------------------------------------
+// id: 1 q128: 4 query waves, 2 score chains      2 q256: 4 query waves x 2 query groups
+//     3 xwave: the waves split the key range      4 q256w8: 8 query waves (4 per SIMD), 1 chain
+//     5 q128 with 1 score chain                   6 q128 with 4 score chains
 
-struct MfmaVariant {
-    const char *name;
-    int tq;
-};
-//                                   id 1            id 2             id 3                 id 4
-static const MfmaVariant kVariants[kMfmaVariants] = {
-    {"mfma_q128_w4", 128}, {"mfma_q256_w4", 256}, {"mfma_xwave", 32}, {"mfma_q256_w8", 256}};
+static const char *kNames[kMfmaVariants] = {"mfma_q128_w4", "mfma_q256_w4", "mfma_xwave",
+                                            "mfma_q256_w8", "mfma_q128_acc1", "mfma_q128_acc4"};
 
 int mfma_variant_tq(int variant, int d) {
-    if (variant < 1 || variant > kMfmaVariants) return 0;
-    if (variant == 3 && d == 128) return 64;    // two query waves x two key waves
-    return kVariants[variant - 1].tq;
+    switch (variant) {
+        case 1: case 5: case 6: return 128;
+        case 2: case 4: return 256;
+        case 3: return d == 128 ? 64 : 32;      // d = 128: two query waves x two key waves
+        default: return 0;
+    }
 }
 const char *mfma_variant_name(int variant) {
-    return (variant >= 1 && variant <= kMfmaVariants) ? kVariants[variant - 1].name : nullptr;
+    return (variant >= 1 && variant <= kMfmaVariants) ? kNames[variant - 1] : nullptr;
 }
 
-template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE>
+template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int SCHED>
 static int launch_one(const FwdParams &p, hipStream_t s) {
     constexpr int TKB = KS * WK;
     constexpr size_t kv_bytes = (size_t)2 * (TKB * (D + 4) + TKB * D) * sizeof(float);
     constexpr size_t xw_bytes = WK > 1 ? (size_t)(WK / 2) * WQ * NQ * (2 + D / 2) * 64 * sizeof(float) : 0;
     constexpr size_t smem = kv_bytes > xw_bytes ? kv_bytes : xw_bytes;
-    auto kern = fwd_mfma_kernel<D, T, NQ, WQ, WK, KS, WPE>;
+    auto kern = fwd_mfma_kernel<D, T, NQ, WQ, WK, KS, WPE, NACC, SCHED>;
     static bool attr_done = false;          // per instantiation; idempotent, so a race is harmless
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -362,12 +407,14 @@ static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
     // tile height per LDS buffer is 64 keys for d = 64 and 32 keys for d = 128 (same bytes)
     constexpr int KS = D == 64 ? 64 : 32;
     switch (variant) {
-        case 1: return launch_one<D, T, 1, 4, 1, KS, 2>(p, s);
-        case 2: return launch_one<D, T, 2, 4, 1, KS, 2>(p, s);
+        case 1: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 0>(p, s);
+        case 2: return launch_one<D, T, 2, 4, 1, KS, 2, 2, 0>(p, s);
         case 3:
-            if constexpr (D == 64) return launch_one<D, T, 1, 1, 4, 32, 2>(p, s);
-            else return launch_one<D, T, 1, 2, 2, 32, 2>(p, s);
-        case 4: return launch_one<D, T, 1, 8, 1, KS, 4>(p, s);
+            if constexpr (D == 64) return launch_one<D, T, 1, 1, 4, 32, 2, 2, 0>(p, s);
+            else return launch_one<D, T, 1, 2, 2, 32, 2, 2, 0>(p, s);
+        case 4: return launch_one<D, T, 1, 8, 1, KS, 4, 1, 0>(p, s);
+        case 5: return launch_one<D, T, 1, 4, 1, KS, 2, 1, 0>(p, s);
+        case 6: return launch_one<D, T, 1, 4, 1, KS, 2, 4, 0>(p, s);
         default: return (int)hipErrorInvalidValue;
     }
 }
