@@ -9,7 +9,9 @@
  *   - Q, K, V, out are contiguous row-major [B][H][n][d] with d_v == d,
  *     self-attention (n queries, n keys).  d must be 64 or 128.
  *   - dtype: ELSA_F32 = FP32 in/out; ELSA_F16 = IEEE FP16 in/out.  Scores, the
- *     running maximum m, the normaliser S and the weighted sum W are always FP32.
+ *     running maximum m, the normaliser S and the weighted sum W are always FP32;
+ *     on the default FP16 path the exponentials are rounded to FP16 (nearest even)
+ *     as operands of the PV product.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     only enqueue work on it; they never synchronise and never allocate.
  *   - Return ELSA_OK or an error code; nothing aborts, throws or prints.
@@ -95,7 +97,9 @@ int elsa_set_workspace(void *dev_ptr, size_t bytes);
 
 /*
  * Measurement / tuning knobs (process-wide, not thread-safe).  Defaults are 0.
- *   ELSA_OPT_PATH     0 = auto (FP32 MFMA), 1 = FP32 FMA (vector ALU), 2 = FP32 MFMA
+ *   ELSA_OPT_PATH     0 = auto (FP32 I/O: FP32 MFMA; FP16 I/O: FP16 MFMA with FP32 state),
+ *                     1 = FP32 FMA (vector ALU), 2 = FP32 MFMA (FP16 inputs widened to FP32),
+ *                     3 = FP16 MFMA (FP16 I/O and scale != 0 only, else ELSA_ERR_UNSUPPORTED)
  *   ELSA_OPT_VARIANT  0 = auto, otherwise a tile configuration id (see elsa_variant_name)
  *   ELSA_OPT_SPLITS   0 = auto, otherwise the number of key chunks elsa_attn_fwd uses
  *                     when a workspace is registered

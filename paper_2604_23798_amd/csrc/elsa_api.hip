@@ -26,9 +26,13 @@ int check_common(int B, int H, int n, int d, int dtype) {
     return ELSA_OK;
 }
 
-int variant_count(int path) { return path == 1 ? elsa::kFmaVariants : elsa::kMfmaVariants; }
+// paths: 1 = FP32 vector FMA, 2 = FP32 MFMA, 3 = FP16 MFMA (FP16 I/O only)
+int variant_count(int path) {
+    return path == 1 ? elsa::kFmaVariants : path == 3 ? elsa::kMfma16Variants : elsa::kMfmaVariants;
+}
 int variant_tq(int path, int variant, int d) {
-    return path == 1 ? elsa::fma_variant_tq(variant, d) : elsa::mfma_variant_tq(variant, d);
+    return path == 1 ? elsa::fma_variant_tq(variant, d)
+         : path == 3 ? elsa::mfma16_variant_tq(variant, d) : elsa::mfma_variant_tq(variant, d);
 }
 
 // Tile configuration when the caller did not force one.  Measured on MI355X: the 256-row tile
@@ -42,6 +46,7 @@ int pick_variant(int path, long long BH, int n, int d, int splits) {
     }
     const long long b256 = BH * ((n + 255) / 256) * splits;
     const long long b128 = BH * ((n + 127) / 128) * splits;
+    if (path == 3) return (d == 64 && b256 >= 2 * kNumCu) ? 2 : (b128 >= (3 * kNumCu) / 4 ? 1 : 3);
     if (d == 64 && b256 >= 2 * kNumCu) return 2;
     return b128 >= (3 * kNumCu) / 4 ? 1 : 3;
 }
@@ -49,7 +54,10 @@ int pick_variant(int path, long long BH, int n, int d, int splits) {
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
                 int B, int H, int n, int d, float scale, int causal, const int32_t *kv_len,
                 int num_splits, int emit, int m_natural, int dtype, void *stream) {
-    const int path = g.opt[ELSA_OPT_PATH] == 1 ? 1 : 2;
+    // auto: FP32 I/O -> FP32 MFMA; FP16 I/O -> FP16 MFMA (needs a non-zero scale)
+    int path = g.opt[ELSA_OPT_PATH];
+    if (path == 0) path = (dtype == ELSA_F16 && scale != 0.f) ? 3 : 2;
+    if (path == 3 && (dtype != ELSA_F16 || scale == 0.f)) return ELSA_ERR_UNSUPPORTED;
     const int variant = pick_variant(path, (long long)B * H, n, d, num_splits);
     const int tq = variant_tq(path, variant, d);
     if (tq <= 0) return ELSA_ERR_UNSUPPORTED;
@@ -71,8 +79,9 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     if (total > 0x7fffffffLL - 8) return ELSA_ERR_INVALID_ARG;
     const char *name = nullptr;
     const hipStream_t s = static_cast<hipStream_t>(stream);
-    const int rc = path == 1 ? elsa::launch_fwd_fma(p, d, dtype == ELSA_F16, variant, s, &name)
-                             : elsa::launch_fwd_mfma(p, d, dtype == ELSA_F16, variant, s, &name);
+    const int rc = path == 1   ? elsa::launch_fwd_fma(p, d, dtype == ELSA_F16, variant, s, &name)
+                   : path == 3 ? elsa::launch_fwd_mfma16(p, d, variant, s, &name)
+                               : elsa::launch_fwd_mfma(p, d, dtype == ELSA_F16, variant, s, &name);
     if (rc != 0) return ELSA_ERR_HIP;
     g.last = name ? name : "";
     return ELSA_OK;
@@ -176,7 +185,7 @@ int elsa_combine(const float *part_m, const float *part_S, const float *part_W, 
 int elsa_set_option(int option, int value) {
     if (option < 0 || option > 3) return ELSA_ERR_UNSUPPORTED;
     if (value < 0) return ELSA_ERR_INVALID_ARG;
-    if (option == ELSA_OPT_PATH && value > 2) return ELSA_ERR_INVALID_ARG;
+    if (option == ELSA_OPT_PATH && value > 3) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_XCD_MAP && value > 2) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_SPLITS && value > kMaxSplits) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_VARIANT && value > 16) return ELSA_ERR_INVALID_ARG;
@@ -192,7 +201,8 @@ int elsa_get_option(int option, int *value) {
 }
 
 const char *elsa_variant_name(int path, int variant) {
-    return path == 1 ? elsa::fma_variant_name(variant) : elsa::mfma_variant_name(variant);
+    return path == 1 ? elsa::fma_variant_name(variant)
+         : path == 3 ? elsa::mfma16_variant_name(variant) : elsa::mfma_variant_name(variant);
 }
 
 const char *elsa_last_kernel(void) { return g.last; }

@@ -93,13 +93,17 @@ template <> struct Io<_Float16> {
 // Launchers implemented in the kernel translation units.  Each returns a hipError_t as int.
 int launch_fwd_mfma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name);
 int launch_fwd_fma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name);
+int launch_fwd_mfma16(const FwdParams &p, int d, int variant, hipStream_t s, const char **name);
 int launch_combine(const CombineParams &p, int d, hipStream_t s);
 int launch_probe(float *out, hipStream_t s);
 int mfma_variant_tq(int variant, int d);   // queries per block of a variant (0 if unknown)
 int fma_variant_tq(int variant, int d);
+int mfma16_variant_tq(int variant, int d);
+const char *mfma16_variant_name(int variant);
 const char *mfma_variant_name(int variant);
 const char *fma_variant_name(int variant);
 constexpr int kMfmaVariants = 6;
 constexpr int kFmaVariants = 2;
+constexpr int kMfma16Variants = 3;
 
 }  // namespace elsa

@@ -1,0 +1,385 @@
+// ELSA forward, FP16-I/O path on the FP16 matrix cores (gfx950), FP32 state.
+//
+// Same tiling and the same monoid fold as the FP32 MFMA kernel, with
+// v_mfma_f32_32x32x16_f16 for both contractions: Q, K, V stay FP16 (exact inputs), every
+// score, the running maximum m, the normaliser S and the weighted sum W are FP32, and the
+// exponentials are rounded to FP16 (nearest-even) only as the B operand of the PV product.
+// 16-bit MFMA operands are contiguous along the contraction index, so
+//   * K is staged row-major (contraction over d),
+//   * V is staged TRANSPOSED (V^T[dv][key], contraction over keys): the transposition is done
+//     by the 2-byte LDS writes of the staging step,
+//   * the contraction index of PV is permuted so that the 8 exponentials a lane already holds
+//     in accumulator registers 8u..8u+7 are its B operand as they are.
+// Scores stay in raw units (q.k); scale*log2(e) enters in the exponent, 2^(s*c - m*c), through
+// one FMA per score, so no rounding of Q is added.  Requires scale != 0 (the caller falls back
+// to the FP32-MFMA kernel otherwise).
+#include "elsa_common.hpp"
+
+namespace elsa {
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ f32x16 mfma16(f16x8 a, f16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, c, 0, 0, 0);
+}
+
+template <int D, int NQ, int WQ, int WK, int KS, int WPE>
+__global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams p) {
+    constexpr int NT = 64 * WQ * WK;
+    constexpr int TQ = 32 * NQ * WQ;
+    constexpr int TKB = KS * WK;             // keys per LDS tile
+    constexpr int KROWB = D * 2 + 16;        // bytes per K row: 16-byte reads of 32 rows hit distinct banks
+    constexpr int VROWB = TKB * 2 + 8;       // bytes per V^T row (one value column, TKB keys)
+    constexpr int KBUFB = TKB * KROWB;
+    constexpr int VBUFB = D * VROWB;
+    constexpr int CPR = D / 8;               // 16-byte chunks per K/V row in HBM
+    constexpr int LPT = TKB * CPR / NT;      // staged chunks per thread per tensor
+    constexpr int MB = D / 32;               // 32-row blocks of W^T
+    constexpr int KC = D / 16;               // MFMAs per score tile
+    static_assert(TKB * CPR % NT == 0, "tile must divide evenly over the threads");
+    static_assert(KS % 32 == 0, "a wave consumes keys 32 at a time");
+
+    extern __shared__ __align__(16) unsigned char smem_b[];
+    unsigned char *Ks = smem_b;                      // [2][KBUFB]
+    unsigned char *Vs = smem_b + 2 * KBUFB;          // [2][VBUFB]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wq = wave % WQ, wk = wave / WQ;
+    const int j = lane & 31, h = lane >> 5;
+
+    const long long BH = (long long)p.B * p.H;
+    const long long total = (long long)p.q_tiles * BH * p.num_splits;
+    const long long w = work_index(total, p.xcd_map);
+    if (w >= total) return;
+    int qt = (int)(w % p.q_tiles);
+    const long long r = w / p.q_tiles;
+    const int c = (int)(r % p.num_splits);
+    const long long bh = r / p.num_splits;
+    if (p.causal) qt = p.q_tiles - 1 - qt;
+    const int n = p.n;
+    int L = n;
+    if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), n);
+    const int q0 = qt * TQ;
+    const int kbeg = c * p.chunk;
+    int kend = min(kbeg + p.chunk, L);
+    if (p.causal) kend = min(kend, q0 + TQ);
+    const int ntiles = kend > kbeg ? (kend - kbeg + TKB - 1) / TKB : 0;
+
+    const long long head_off = bh * (long long)n * D;
+    const int wrow0 = q0 + wq * NQ * 32;
+    const _Float16 *qp = static_cast<const _Float16 *>(p.q);
+    const _Float16 *kp = static_cast<const _Float16 *>(p.k);
+    const _Float16 *vp = static_cast<const _Float16 *>(p.v);
+
+    // log2-unit score = (q.k) * qscale.  A negative scale is moved into Q (exact sign flip) so
+    // that the maximum of the raw scores is the maximum of the scaled ones.
+    const float cs = fabsf(p.qscale);
+    const bool flip = p.qscale < 0.f;
+
+    // ---- Q fragments (B operand): lane (j,h) holds columns 16*cc + 8*h .. +7 of query row j
+    f16x8 qf[NQ][KC];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        const int row = wrow0 + nq * 32 + j;
+#pragma unroll
+        for (int cc = 0; cc < KC; ++cc) {
+            f16x8 x = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (row < n) x = *reinterpret_cast<const f16x8 *>(qp + head_off + (long long)row * D + 16 * cc + 8 * h);
+            if (flip) x = -x;
+            qf[nq][cc] = x;
+        }
+    }
+
+    float mrun[NQ], srun[NQ];               // mrun in raw score units
+    f32x16 oacc[NQ][MB];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        mrun[nq] = -INFINITY;
+        srun[nq] = 0.f;
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) oacc[nq][mb][i] = 0.f;
+    }
+
+    f16x8 kst[LPT], vst[LPT];
+    auto gload = [&](int t) {
+        const int kb0 = kbeg + t * TKB;
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) {
+            const int e = tid + i * NT;
+            const int row = e / CPR, c8 = e % CPR;
+            const int key = kb0 + row;
+            f16x8 kx = {0, 0, 0, 0, 0, 0, 0, 0}, vx = {0, 0, 0, 0, 0, 0, 0, 0};
+            if (key < kend) {
+                const long long off = head_off + (long long)key * D + 8 * c8;
+                kx = *reinterpret_cast<const f16x8 *>(kp + off);
+                vx = *reinterpret_cast<const f16x8 *>(vp + off);
+            }
+            kst[i] = kx;
+            vst[i] = vx;
+        }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < LPT; ++i) {
+            const int e = tid + i * NT;
+            const int row = e / CPR, c8 = e % CPR;
+            *reinterpret_cast<f16x8 *>(Ks + buf * KBUFB + row * KROWB + 16 * c8) = kst[i];
+            unsigned char *vt = Vs + buf * VBUFB + (8 * c8) * VROWB + 2 * row;   // V^T[8*c8 + e8][row]
+#pragma unroll
+            for (int e8 = 0; e8 < 8; ++e8) *reinterpret_cast<_Float16 *>(vt + e8 * VROWB) = vst[i][e8];
+        }
+    };
+
+    if (ntiles > 0) {
+        gload(0);
+        lstore(0);
+        __syncthreads();
+    }
+    const int wave_lim = p.causal ? min(kend, wrow0 + NQ * 32) : kend;
+    for (int t = 0; t < ntiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < ntiles) gload(t + 1);
+        const unsigned char *Kb = Ks + buf * KBUFB;
+        const unsigned char *Vb = Vs + buf * VBUFB;
+        const int kg0 = kbeg + t * TKB + wk * KS;
+        const int nact = min(KS / 32, max(0, (wave_lim - kg0 + 31) / 32));
+#pragma unroll 1
+        for (int ks = 0; ks < nact; ++ks) {
+            const int kl = wk * KS + ks * 32;
+            const int kg = kg0 + ks * 32;
+
+            // ---- (a1) S^T = K Q^T, raw units
+            f32x16 sacc[NQ];
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) sacc[nq][i] = 0.f;
+#pragma unroll
+            for (int cc = 0; cc < KC; ++cc) {
+                const f16x8 kf = *reinterpret_cast<const f16x8 *>(Kb + (kl + j) * KROWB + 32 * cc + 16 * h);
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) sacc[nq] = mfma16(kf, qf[nq][cc], sacc[nq]);
+            }
+
+            // ---- (a2) masks
+            const bool need_mask = (kg + 32 > kend) || (p.causal && kg + 31 > wrow0);
+            if (need_mask) {
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) {
+                    const int row = wrow0 + nq * 32 + j;
+                    const int lim = p.causal ? min(kend, row + 1) : kend;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const int key = kg + 8 * (i >> 2) + 4 * h + (i & 3);
+                        if (key >= lim) sacc[nq][i] = -INFINITY;
+                    }
+                }
+            }
+
+            // ---- (a3) fold the tile into (m, S, W); exponent = s*cs - m*cs by one FMA per score
+            f16x8 pb[NQ][2];
+#pragma unroll
+            for (int nq = 0; nq < NQ; ++nq) {
+                float mt = sacc[nq][0];
+#pragma unroll
+                for (int i = 1; i < 16; ++i) mt = fmaxf(mt, sacc[nq][i]);
+                mt = half_max(mt);
+                const float mnew = fmaxf(mrun[nq], mt);
+                const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+                if (__builtin_amdgcn_ballot_w64(mnew > mrun[nq]) != 0) {
+                    const float alpha = (mrun[nq] == -INFINITY) ? 0.f : exp2_fast((mrun[nq] - msafe) * cs);
+                    srun[nq] *= alpha;
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
+                    mrun[nq] = mnew;
+                }
+                const float nmc = -msafe * cs;
+                float ps = 0.f;
+                float e[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    e[i] = exp2_fast(__builtin_fmaf(sacc[nq][i], cs, nmc));
+                    ps += e[i];
+                }
+                srun[nq] += ps;
+#pragma unroll
+                for (int u = 0; u < 2; ++u)
+#pragma unroll
+                    for (int e2 = 0; e2 < 4; ++e2) {
+                        const f32x2 pr = {e[8 * u + 2 * e2], e[8 * u + 2 * e2 + 1]};
+                        const f16x2 ph = __builtin_convertvector(pr, f16x2);    // round to nearest even
+                        pb[nq][u][2 * e2] = ph[0];
+                        pb[nq][u][2 * e2 + 1] = ph[1];
+                    }
+            }
+
+            // ---- (a4) W^T += V^T P^T.  MFMA u contracts the 16 keys held in registers 8u..8u+7 of
+            // the two half-waves: element e of lane (.,h) is key 16u + 8*(e/4) + 4h + e%4.
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+#pragma unroll
+                for (int mb = 0; mb < MB; ++mb) {
+                    const unsigned char *vrow = Vb + (32 * mb + j) * VROWB + 2 * (kl + 16 * u + 4 * h);
+                    typedef _Float16 f16x4v __attribute__((ext_vector_type(4)));
+                    const f16x4v lo = *reinterpret_cast<const f16x4v *>(vrow);
+                    const f16x4v hi = *reinterpret_cast<const f16x4v *>(vrow + 16);
+                    const f16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq) oacc[nq][mb] = mfma16(vf, pb[nq][u], oacc[nq][mb]);
+                }
+            }
+        }
+        if (t + 1 < ntiles) lstore(buf ^ 1);
+        __syncthreads();
+    }
+
+    // to log2 units; per-query normaliser across the two half-waves
+    float stot[NQ];
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        stot[nq] = half_sum(srun[nq]);
+        mrun[nq] = (mrun[nq] == -INFINITY) ? -INFINITY : mrun[nq] * cs;
+    }
+
+    // ---- (a5) waves that split the key range merge their states through LDS
+    if constexpr (WK > 1) {
+        constexpr int NS = NQ * (2 + MB * 16);
+        float *xs = reinterpret_cast<float *>(smem_b);
+#pragma unroll
+        for (int s = WK / 2; s >= 1; s >>= 1) {
+            if (wk >= s && wk < 2 * s) {
+                float *dst = xs + ((wk - s) * WQ + wq) * NS * 64 + lane;
+                int idx = 0;
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) {
+                    dst[64 * idx++] = mrun[nq];
+                    dst[64 * idx++] = stot[nq];
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) dst[64 * idx++] = oacc[nq][mb][i];
+                }
+            }
+            __syncthreads();
+            if (wk < s) {
+                const float *src = xs + (wk * WQ + wq) * NS * 64 + lane;
+                int idx = 0;
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) {
+                    const float mb_ = src[64 * idx++];
+                    const float sb = src[64 * idx++];
+                    const float mnew = fmaxf(mrun[nq], mb_);
+                    const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+                    const float fa = exp2_fast(mrun[nq] - msafe);
+                    const float fb = exp2_fast(mb_ - msafe);
+                    mrun[nq] = mnew;
+                    stot[nq] = stot[nq] * fa + sb * fb;
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                        for (int i = 0; i < 16; ++i)
+                            oacc[nq][mb][i] = oacc[nq][mb][i] * fa + src[64 * idx++] * fb;
+                }
+            }
+            __syncthreads();
+        }
+        if (wk != 0) return;
+    }
+
+    // ---- (a7) normalise and store (FP16), or emit the block state (FP32).
+    // Register 4g+t of block mb is value column 32*mb + 8g + 4h + t.
+    const bool partial = p.emit_partials != 0;
+#pragma unroll
+    for (int nq = 0; nq < NQ; ++nq) {
+        const int row = wrow0 + nq * 32 + j;
+        if (row >= n) continue;
+        float f = 1.f;
+        long long obase;
+        if (partial) {
+            const long long prow = (bh * p.num_splits + c) * (long long)n + row;
+            if (h == 0) {
+                p.part_m[prow] = p.m_natural ? mrun[nq] * kLn2 : mrun[nq];
+                p.part_S[prow] = stot[nq];
+            }
+            obase = prow * D;
+        } else {
+            f = stot[nq] > 0.f ? 1.f / stot[nq] : 0.f;
+            obase = head_off + (long long)row * D;
+        }
+#pragma unroll
+        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const f32x4 x = {oacc[nq][mb][4 * g] * f, oacc[nq][mb][4 * g + 1] * f, oacc[nq][mb][4 * g + 2] * f,
+                                 oacc[nq][mb][4 * g + 3] * f};
+                const int dv = 32 * mb + 8 * g + 4 * h;
+                if (partial) Io<float>::store4(p.part_W, obase + dv, x);
+                else Io<_Float16>::store4(p.out, obase + dv, x);
+            }
+    }
+}
+
+// ---- variants: 1 q128 (4 query waves)   2 q256 (4 waves x 2 query groups)   3 waves split the keys
+
+static const char *kNames16[kMfma16Variants] = {"mfma16_q128_w4", "mfma16_q256_w4", "mfma16_xwave"};
+
+int mfma16_variant_tq(int variant, int d) {
+    switch (variant) {
+        case 1: return 128;
+        case 2: return 256;
+        case 3: return d == 128 ? 64 : 32;
+        default: return 0;
+    }
+}
+const char *mfma16_variant_name(int variant) {
+    return (variant >= 1 && variant <= kMfma16Variants) ? kNames16[variant - 1] : nullptr;
+}
+
+template <int D, int NQ, int WQ, int WK, int KS, int WPE>
+static int launch_one16(const FwdParams &p, hipStream_t s) {
+    constexpr int TKB = KS * WK;
+    constexpr size_t kv_bytes = (size_t)2 * (TKB * (D * 2 + 16) + D * (TKB * 2 + 8));
+    constexpr size_t xw_bytes = WK > 1 ? (size_t)(WK / 2) * WQ * NQ * (2 + D / 2) * 64 * sizeof(float) : 0;
+    constexpr size_t smem = kv_bytes > xw_bytes ? kv_bytes : xw_bytes;
+    auto kern = fwd_mfma16_kernel<D, NQ, WQ, WK, KS, WPE>;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
+        if (e != hipSuccess) return (int)e;
+        attr_done = true;
+    }
+    const long long total = (long long)p.q_tiles * p.B * p.H * p.num_splits;
+    long long blocks = total;
+    if (p.xcd_map) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * WQ * WK), smem, s, p);
+    return (int)hipGetLastError();
+}
+
+template <int D>
+static int launch_variant16(const FwdParams &p, int variant, hipStream_t s) {
+    switch (variant) {
+        case 1: return launch_one16<D, 1, 4, 1, 64, 2>(p, s);
+        case 2: return launch_one16<D, 2, 4, 1, 64, 2>(p, s);
+        case 3:
+            if constexpr (D == 64) return launch_one16<D, 1, 1, 4, 32, 2>(p, s);
+            else return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
+        default: return (int)hipErrorInvalidValue;
+    }
+}
+
+int launch_fwd_mfma16(const FwdParams &p, int d, int variant, hipStream_t s, const char **name) {
+    if (name) *name = mfma16_variant_name(variant);
+    if (d == 64) return launch_variant16<64>(p, variant, s);
+    if (d == 128) return launch_variant16<128>(p, variant, s);
+    return (int)hipErrorInvalidValue;
+}
+
+}  // namespace elsa

@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libelsa.so")
 
 F32, F16 = 0, 1
 OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP = 0, 1, 2, 3
-PATH_AUTO, PATH_FMA, PATH_MFMA = 0, 1, 2
+PATH_AUTO, PATH_FMA, PATH_MFMA, PATH_MFMA16 = 0, 1, 2, 3
 
 EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_split_kv", "elsa_combine",
            "elsa_split_kv_workspace_bytes", "elsa_set_workspace", "elsa_set_option", "elsa_get_option",

@@ -38,11 +38,12 @@ def test_status_strings_and_options():
     assert elsa.elsa_get_option(elsa.OPT_PATH) == 1
     elsa.elsa_set_option(elsa.OPT_PATH, 0)
     with pytest.raises(elsa.ElsaError):
-        elsa.elsa_set_option(elsa.OPT_PATH, 3)
+        elsa.elsa_set_option(elsa.OPT_PATH, 4)
     with pytest.raises(elsa.ElsaError):
         elsa.elsa_set_option(9, 0)
     assert elsa.elsa_variant_name(2, 1).startswith("mfma") and elsa.elsa_variant_name(1, 1).startswith("fma")
     assert elsa.elsa_variant_name(2, 99) is None
+    assert elsa.elsa_variant_name(3, 1).startswith("mfma16") and elsa.elsa_variant_name(3, 4) is None
 
 
 def test_workspace_bytes():

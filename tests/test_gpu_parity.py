@@ -12,7 +12,7 @@ from tests.parity import assert_parity, tolerance
 
 pytestmark = pytest.mark.gpu
 
-MFMA, FMA = 2, 1
+MFMA, FMA, MFMA16 = 2, 1, 3
 ALL_KERNELS = [(MFMA, 1), (MFMA, 2), (MFMA, 3), (MFMA, 4), (MFMA, 5), (MFMA, 6), (FMA, 1), (FMA, 2)]
 
 
@@ -70,7 +70,7 @@ def test_small_problems_every_kernel(path, variant, shape, causal):
     assert_parity(out, ref, tolerance(n), "path%d v%d %s causal=%d" % (path, variant, shape, causal))
 
 
-@pytest.mark.parametrize("path,variant", [(MFMA, 1), (MFMA, 3), (FMA, 1)])
+@pytest.mark.parametrize("path,variant", [(MFMA, 1), (MFMA, 3), (FMA, 1), (MFMA16, 1), (MFMA16, 2), (MFMA16, 3)])
 @pytest.mark.parametrize("d", [64, 128])
 def test_fp16_io(path, variant, d):
     B, H, n = 1, 3, 450
@@ -81,6 +81,52 @@ def test_fp16_io(path, variant, d):
         with G.Options(path=path, variant=variant):
             out = G.fwd(q, k, v, scale, causal=causal)
         assert_parity(out, ref, tolerance(n, fp16=True), "fp16 path%d v%d d%d causal=%d" % (path, variant, d, causal))
+
+
+@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_fp16_matrix_core_path_masks_splits_and_edges(variant):
+    """The FP16-MFMA kernel through every feature: padding, causal, split-KV states, combine,
+    ragged sizes, negative and zero scale (zero falls back to the FP32-MFMA kernel)."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    tol = 2e-3
+    B, H, n, d = 3, 2, 333, 64
+    q, k, v = _rand(B, H, n, d, 91, fp16=True)
+    qf, kf, vf = _f32(q, k, v)
+    kv_len = np.array([333, 0, 77], np.int32)
+    for causal in (False, True):
+        with G.Options(path=MFMA16, variant=variant):
+            out = G.fwd(q, k, v, 0.125, causal=causal, kv_len=kv_len)
+        assert_parity(out, oracle.attn_rows(qf, kf, vf, 0.125, causal=causal, kv_len=kv_len), tol, "fp16 masks")
+        assert np.all(out.reshape(B, H, n, d)[1] == 0.0)
+    with G.Options(path=MFMA16, variant=variant):
+        out = G.fwd(q, k, v, -0.3)
+        name = elsa.elsa_last_kernel()
+    assert name.startswith("mfma16")
+    assert_parity(out, oracle.attn_rows(qf, kf, vf, -0.3), tol, "fp16 negative scale")
+    out = G.fwd(q, k, v, 0.0)                                   # auto path: FP32-MFMA fallback
+    assert not elsa.elsa_last_kernel().startswith("mfma16")
+    assert_parity(out, oracle.attn_rows(qf, kf, vf, 0.0), tol, "fp16 zero scale")
+    for nn in (1, 31, 33, 65):
+        q2, k2, v2 = _rand(1, 1, nn, 128, 92 + nn, fp16=True)
+        with G.Options(path=MFMA16, variant=variant):
+            o2 = G.fwd(q2, k2, v2, 0.09, causal=True)
+        assert_parity(o2, oracle.attn_rows(*_f32(q2, k2, v2), 0.09, causal=True), tol, "fp16 n=%d" % nn)
+    C = 3
+    with G.Options(path=MFMA16, variant=variant):
+        pm, pS, pW = G.split_kv(q, k, v, 0.125, C, causal=True)
+    gm, gS, gW = G.parts_to_rows(pm, pS, pW)
+    om, oS, oW = oracle.partials_rows(qf, kf, vf, 0.125, C, causal=True)
+    ident = np.isneginf(om)
+    assert np.array_equal(np.isneginf(gm), ident) and np.all(gS[ident] == 0) and np.all(gW[ident] == 0)
+    live = ~ident
+    assert np.all(np.abs(gm[live] - om[live]) <= 4e-6 * (1 + np.abs(om[live])))
+    assert np.all(np.abs(gm[live] + np.log(gS[live]) - om[live] - np.log(oS[live])) <= 1e-3)
+    out16 = torch.full((B, H, n, d), float("nan"), device="cuda", dtype=torch.float16)
+    elsa.elsa_combine(pm, pS, pW, out16)
+    torch.cuda.synchronize()
+    assert_parity(out16.reshape(-1, d).double().cpu().numpy(), oracle.attn_rows(qf, kf, vf, 0.125, causal=True), tol,
+                  "fp16 split + combine")
 
 
 @pytest.mark.parametrize("path,variant", ALL_KERNELS)
