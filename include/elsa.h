@@ -103,7 +103,9 @@ int elsa_set_workspace(void *dev_ptr, size_t bytes);
  *   ELSA_OPT_VARIANT  0 = auto, otherwise a tile configuration id (see elsa_variant_name)
  *   ELSA_OPT_SPLITS   0 = auto, otherwise the number of key chunks elsa_attn_fwd uses
  *                     when a workspace is registered
- *   ELSA_OPT_XCD_MAP  0 = auto, 1 = linear block order, 2 = heads pinned to XCDs
+ *   ELSA_OPT_XCD_MAP  block -> work order: 0 = head index fastest, longest causal tiles of all
+ *                     heads first (default); 1 = query tile fastest; 2 = as 1, consecutive work
+ *                     items steered to the same XCD
  */
 enum { ELSA_OPT_PATH = 0, ELSA_OPT_VARIANT = 1, ELSA_OPT_SPLITS = 2, ELSA_OPT_XCD_MAP = 3 };
 int elsa_set_option(int option, int value);

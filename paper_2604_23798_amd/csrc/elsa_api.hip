@@ -73,8 +73,7 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     p.emit_partials = emit;
     p.m_natural = m_natural;
     p.q_tiles = (n + tq - 1) / tq;
-    const int xm = g.opt[ELSA_OPT_XCD_MAP];
-    p.xcd_map = xm == 2 ? 1 : 0;
+    p.xcd_map = g.opt[ELSA_OPT_XCD_MAP];
     const long long total = (long long)p.q_tiles * B * H * num_splits;
     if (total > 0x7fffffffLL - 8) return ELSA_ERR_INVALID_ARG;
     const char *name = nullptr;

@@ -31,7 +31,7 @@ struct FwdParams {
     int chunk;                       // ceil(n / C) keys per split
     int emit_partials;               // 1: write (m,S,W) states instead of out
     int m_natural;                   // 1: part_m in natural-log units, 0: log2 units (internal)
-    int xcd_map;                     // 1: heads pinned to XCDs
+    int xcd_map;                     // block -> work item order, see decode_work
     int q_tiles;                     // ceil(n / T_q) for the launched configuration
 };
 
@@ -60,14 +60,42 @@ __device__ __forceinline__ float half_sum(float x) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-// Work item handled by this block.  Blocks are dealt round-robin to the 8 XCDs
-// (each with a private L2), so with xcd_map on, consecutive work items -- which
-// share a head's K and V -- are steered to the same XCD.
-__device__ __forceinline__ long long work_index(long long total, int xcd_map) {
-    long long lin = blockIdx.x;
-    if (!xcd_map) return lin;
-    long long per = (total + kNumXcd - 1) / kNumXcd;
-    return (lin % kNumXcd) * per + lin / kNumXcd;   // may be >= total: caller exits
+// Work item (query tile, key chunk, head) of this block.  Blocks are dealt round-robin to the
+// 8 XCDs, each with a private L2.
+//   order 0 (default): the head index runs fastest, the query tile slowest.  With B*H a
+//     multiple of 8 every XCD then serves a fixed subset of heads (their K and V stay in its
+//     L2), and a causal launch starts the longest query tiles of ALL heads first, which is
+//     what balances the triangular work over the CUs.
+//   order 1: the query tile runs fastest (consecutive blocks share a head).
+//   order 2: as order 1, with consecutive work items steered to the same XCD.
+struct Work {
+    int qt, c;
+    long long bh;
+    bool valid;
+};
+__device__ __forceinline__ Work decode_work(const FwdParams &p) {
+    const long long BH = (long long)p.B * p.H;
+    const long long total = (long long)p.q_tiles * BH * p.num_splits;
+    long long w = blockIdx.x;
+    Work r;
+    if (p.xcd_map == 2) {
+        const long long per = (total + kNumXcd - 1) / kNumXcd;
+        w = (w % kNumXcd) * per + w / kNumXcd;
+    }
+    r.valid = w < total;
+    if (p.xcd_map == 0) {
+        r.bh = w % BH;
+        const long long t = w / BH;
+        r.c = (int)(t % p.num_splits);
+        r.qt = (int)(t / p.num_splits);
+    } else {
+        r.qt = (int)(w % p.q_tiles);
+        const long long t = w / p.q_tiles;
+        r.c = (int)(t % p.num_splits);
+        r.bh = t / p.num_splits;
+    }
+    if (p.causal) r.qt = p.q_tiles - 1 - r.qt;   // longest rows first
+    return r;
 }
 
 template <typename T> struct Io;
@@ -102,7 +130,7 @@ int mfma16_variant_tq(int variant, int d);
 const char *mfma16_variant_name(int variant);
 const char *mfma_variant_name(int variant);
 const char *fma_variant_name(int variant);
-constexpr int kMfmaVariants = 6;
+constexpr int kMfmaVariants = 8;
 constexpr int kFmaVariants = 2;
 constexpr int kMfma16Variants = 3;
 

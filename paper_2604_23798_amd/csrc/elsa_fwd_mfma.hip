@@ -49,15 +49,10 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     const int wq = wave % WQ, wk = wave / WQ;
     const int j = lane & 31, h = lane >> 5;
 
-    const long long BH = (long long)p.B * p.H;
-    const long long total = (long long)p.q_tiles * BH * p.num_splits;
-    const long long w = work_index(total, p.xcd_map);
-    if (w >= total) return;
-    int qt = (int)(w % p.q_tiles);
-    const long long r = w / p.q_tiles;
-    const int c = (int)(r % p.num_splits);
-    const long long bh = r / p.num_splits;
-    if (p.causal) qt = p.q_tiles - 1 - qt;  // longest rows first
+    const Work wi = decode_work(p);
+    if (!wi.valid) return;
+    const int qt = wi.qt, c = wi.c;
+    const long long bh = wi.bh;
     const int n = p.n;
     int L = n;
     if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), n);
@@ -87,6 +82,11 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 
     float mrun[NQ], srun[NQ];
     f32x16 oacc[NQ][MB];
+    f32x16 negm[(SCHED & 4) ? NQ : 1];      // FOLD only: -anchor in every register (0 while no key was seen)
+#pragma unroll
+    for (int nq = 0; nq < ((SCHED & 4) ? NQ : 1); ++nq)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) negm[nq][i] = 0.f;
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
         mrun[nq] = -INFINITY;
@@ -156,6 +156,9 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                     for (int a = 0; a < NACC; ++a)
 #pragma unroll
                         for (int i = 0; i < 16; ++i) part[nq][a][i] = 0.f;
+                // FOLD: chain 0 starts from -anchor (held splat in 16 registers, as the C operand of
+                // the first MFMA), so the accumulator comes out as s - m and no subtraction follows
+                constexpr bool FOLD = (SCHED & 4) != 0;
                 if constexpr (SCHED & 1) __builtin_amdgcn_s_setprio(1);
                 // K fragments are fetched one column group ahead of the MFMAs that consume them
                 const float *krow = &Kb[(kl + j) * KROW + 4 * h];
@@ -169,7 +172,12 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                     for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
                         for (int nq = 0; nq < NQ; ++nq)
-                            part[nq][cc / CPA] = mfma32(kf[tt], qf[nq][4 * cc + tt], part[nq][cc / CPA]);
+                        {
+                            if (FOLD && cc == 0 && tt == 0)
+                                part[nq][0] = mfma32(kf[tt], qf[nq][4 * cc + tt], negm[nq]);
+                            else
+                                part[nq][cc / CPA] = mfma32(kf[tt], qf[nq][4 * cc + tt], part[nq][cc / CPA]);
+                        }
                     kf = kn;
                 }
                 // pin the order: two fragment reads in flight ahead of every group of MFMAs
@@ -211,26 +219,56 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 #pragma unroll
                 for (int i = 1; i < 16; ++i) mt = fmaxf(mt, sacc[nq][i]);
                 mt = half_max(mt);                       // the other 16 keys of this query
-                const float mnew = fmaxf(mrun[nq], mt);
-                const float msafe = (mnew == -INFINITY) ? 0.f : mnew;   // identity (+) identity = identity
-                // the running state is rescaled only when some row of the wave moved its maximum
-                if (__builtin_amdgcn_ballot_w64(mnew > mrun[nq]) != 0) {
-                    const float alpha = exp2_fast(mrun[nq] - msafe);
-                    srun[nq] *= alpha;
+                if constexpr ((SCHED & 4) != 0) {
+                    // scores arrive relative to the anchor (0 while the row has seen no key)
+                    const bool seen = mrun[nq] > -INFINITY;
+                    const bool grow = seen ? (mt > 0.f) : (mt > -INFINITY);
+                    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
+                        const float delta = grow ? mt : 0.f;
+                        const float alpha = seen ? exp2_fast(-delta) : 0.f;
+                        srun[nq] *= alpha;
 #pragma unroll
-                    for (int mb = 0; mb < MB; ++mb)
+                        for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
-                    mrun[nq] = mnew;
+                            for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
+                        if (grow) mrun[nq] = (seen ? mrun[nq] : 0.f) + delta;
+                        const float na = (mrun[nq] > -INFINITY) ? -mrun[nq] : 0.f;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            sacc[nq][i] -= delta;
+                            negm[nq][i] = na;
+                        }
+                    }
+                    float ps = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float e = exp2_fast(sacc[nq][i]);
+                        sacc[nq][i] = e;
+                        ps += e;
+                    }
+                    srun[nq] += ps;
+                } else {
+                    const float mnew = fmaxf(mrun[nq], mt);
+                    const float msafe = (mnew == -INFINITY) ? 0.f : mnew;   // identity (+) identity = identity
+                    // the running state is rescaled only when some row of the wave moved its maximum
+                    if (__builtin_amdgcn_ballot_w64(mnew > mrun[nq]) != 0) {
+                        const float alpha = exp2_fast(mrun[nq] - msafe);
+                        srun[nq] *= alpha;
+#pragma unroll
+                        for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
+                        mrun[nq] = mnew;
+                    }
+                    float ps = 0.f;
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        const float e = exp2_fast(sacc[nq][i] - msafe);
+                        sacc[nq][i] = e;
+                        ps += e;
+                    }
+                    srun[nq] += ps;
                 }
-                float ps = 0.f;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const float e = exp2_fast(sacc[nq][i] - msafe);
-                    sacc[nq][i] = e;
-                    ps += e;
-                }
-                srun[nq] += ps;
             }
 
             // ---- (a4) W^T += V^T P^T.  Step i contracts keys 8g+t (lower half-wave) and
@@ -364,13 +402,14 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 // id: 1 q128: 4 query waves, 2 score chains      2 q256: 4 query waves x 2 query groups
 //     3 xwave: the waves split the key range      4 q256w8: 8 query waves (4 per SIMD), 1 chain
 //     5 q128 with 1 score chain                   6 q128 with 4 score chains
+//     7 q128, anchor folded into the score MFMA   8 same with 1 score chain
 
-static const char *kNames[kMfmaVariants] = {"mfma_q128_w4", "mfma_q256_w4", "mfma_xwave",
-                                            "mfma_q256_w8", "mfma_q128_acc1", "mfma_q128_acc4"};
+static const char *kNames[kMfmaVariants] = {"mfma_q128_w4",   "mfma_q256_w4",   "mfma_xwave",     "mfma_q256_w8",
+                                            "mfma_q128_acc1", "mfma_q128_acc4", "mfma_q128_fold", "mfma_q128_fold1"};
 
 int mfma_variant_tq(int variant, int d) {
     switch (variant) {
-        case 1: case 5: case 6: return 128;
+        case 1: case 5: case 6: case 7: case 8: return 128;
         case 2: case 4: return 256;
         case 3: return d == 128 ? 64 : 32;      // d = 128: two query waves x two key waves
         default: return 0;
@@ -396,7 +435,7 @@ static int launch_one(const FwdParams &p, hipStream_t s) {
     }
     const long long total = (long long)p.q_tiles * p.B * p.H * p.num_splits;
     long long blocks = total;
-    if (p.xcd_map) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
+    if (p.xcd_map == 2) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * WQ * WK), smem, s, p);
     return (int)hipGetLastError();
@@ -412,9 +451,15 @@ static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
         case 3:
             if constexpr (D == 64) return launch_one<D, T, 1, 1, 4, 32, 2, 2, 0>(p, s);
             else return launch_one<D, T, 1, 2, 2, 32, 2, 2, 0>(p, s);
-        case 4: return launch_one<D, T, 1, 8, 1, KS, 4, 1, 0>(p, s);
+        case 4:
+            // d = 64: 4 waves per SIMD in 128 registers.  d = 128: one 8-wave block per CU with 64-key
+            // tiles (133 KB of LDS), so a barrier falls every second step instead of every step.
+            if constexpr (D == 64) return launch_one<D, T, 1, 8, 1, KS, 4, 1, 0>(p, s);
+            else return launch_one<D, T, 1, 8, 1, 64, 2, 2, 0>(p, s);
         case 5: return launch_one<D, T, 1, 4, 1, KS, 2, 1, 0>(p, s);
         case 6: return launch_one<D, T, 1, 4, 1, KS, 2, 4, 0>(p, s);
+        case 7: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 4>(p, s);
+        case 8: return launch_one<D, T, 1, 4, 1, KS, 2, 1, 4>(p, s);
         default: return (int)hipErrorInvalidValue;
     }
 }

@@ -49,15 +49,10 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
     const int wq = wave % WQ, wk = wave / WQ;
     const int j = lane & 31, h = lane >> 5;
 
-    const long long BH = (long long)p.B * p.H;
-    const long long total = (long long)p.q_tiles * BH * p.num_splits;
-    const long long w = work_index(total, p.xcd_map);
-    if (w >= total) return;
-    int qt = (int)(w % p.q_tiles);
-    const long long r = w / p.q_tiles;
-    const int c = (int)(r % p.num_splits);
-    const long long bh = r / p.num_splits;
-    if (p.causal) qt = p.q_tiles - 1 - qt;
+    const Work wi = decode_work(p);
+    if (!wi.valid) return;
+    const int qt = wi.qt, c = wi.c;
+    const long long bh = wi.bh;
     const int n = p.n;
     int L = n;
     if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), n);
@@ -357,7 +352,7 @@ static int launch_one16(const FwdParams &p, hipStream_t s) {
     }
     const long long total = (long long)p.q_tiles * p.B * p.H * p.num_splits;
     long long blocks = total;
-    if (p.xcd_map) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
+    if (p.xcd_map == 2) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * WQ * WK), smem, s, p);
     return (int)hipGetLastError();
