@@ -61,6 +61,19 @@ int elsa_attn_fwd_masked(const void *q, const void *k, const void *v, void *out,
                          const int32_t *kv_len, int dtype, void *stream);
 
 /*
+ * Padding-free variable-length batches (the packed layout of the paper's
+ * "padding-free variable-length" workload): Q, K, V, out are [total_tokens][H][d],
+ * sequence s owns tokens cu_seqlens[s] .. cu_seqlens[s+1]-1 (device int32
+ * [num_seqs+1], cu_seqlens[0] = 0, non-decreasing, last = total_tokens) and attends
+ * only within itself; Eq. 1 per sequence.  No layout conversion and no padding
+ * work: query tiles are cut per sequence.  max_seqlen (>= every length) only
+ * guides the tile choice.  1 <= num_seqs <= 4096.  Empty sequences are allowed.
+ */
+int elsa_attn_fwd_varlen(const void *q, const void *k, const void *v, void *out,
+                         const int32_t *cu_seqlens, int num_seqs, int total_tokens, int max_seqlen,
+                         int H, int d, float scale, int causal, int dtype, void *stream);
+
+/*
  * Block states of Prop. 1.  The key range is cut into num_splits contiguous
  * chunks; chunk c covers keys [c*ceil(n/C), min(n, (c+1)*ceil(n/C))).  For every
  * query row and chunk the kernel emits the normalised state over the visible

@@ -131,6 +131,26 @@ def partials_rows(q, k, v, scale, num_splits, causal=False, kv_len=None, rows=No
     return pm, pS, pW
 
 
+def attn_varlen(q, k, v, cu_seqlens, scale, causal=False):
+    """Packed sequences ``[total_tokens, H, d]``: the definition applied to every sequence on its
+    own (pure slicing around ``attn_rows``).  Returns float64 ``[total_tokens, H, d]``."""
+    q = np.asarray(q, dtype=np.float32)
+    k = np.asarray(k, dtype=np.float32)
+    v = np.asarray(v, dtype=np.float32)
+    T, H, d = q.shape
+    cu = np.asarray(cu_seqlens, dtype=np.int64)
+    assert cu[0] == 0 and cu[-1] == T and np.all(np.diff(cu) >= 0)
+    out = np.zeros((T, H, d), dtype=np.float64)
+    for s in range(cu.size - 1):
+        a, b = int(cu[s]), int(cu[s + 1])
+        if b == a:
+            continue
+        dense = lambda t: np.ascontiguousarray(t[a:b].transpose(1, 0, 2))[None]      # [1, H, len, d]
+        o = attn_rows(dense(q), dense(k), dense(v), scale, causal=causal)
+        out[a:b] = o.reshape(H, b - a, d).transpose(1, 0, 2)
+    return out
+
+
 def _merge(fn, a, b):
     ma, Sa, Wa = a
     mb, Sb, Wb = b

@@ -14,6 +14,7 @@ struct State {
 } g;
 
 constexpr int kMaxSplits = 65535;
+constexpr int kMaxSeqs = 4096;       // the tile -> sequence lookup walks the list linearly
 constexpr int kNumCu = 256;
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
@@ -53,7 +54,8 @@ int pick_variant(int path, long long BH, int n, int d, int splits) {
 
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
                 int B, int H, int n, int d, float scale, int causal, const int32_t *kv_len,
-                int num_splits, int emit, int m_natural, int dtype, void *stream) {
+                int num_splits, int emit, int m_natural, int dtype, void *stream,
+                const int32_t *cu_seqlens = nullptr, int num_seqs = 0, int total_tokens = 0) {
     // auto: FP32 I/O -> FP32 MFMA; FP16 I/O -> FP16 MFMA (needs a non-zero scale)
     int path = g.opt[ELSA_OPT_PATH];
     if (path == 0) path = (dtype == ELSA_F16 && scale != 0.f) ? 3 : 2;
@@ -73,6 +75,11 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     p.emit_partials = emit;
     p.m_natural = m_natural;
     p.q_tiles = (n + tq - 1) / tq;
+    p.tq = tq;
+    p.cu_seqlens = cu_seqlens;
+    p.num_seqs = num_seqs;
+    // every sequence wastes at most one partly filled tile
+    p.var_tiles = cu_seqlens ? (int)(((long long)total_tokens + tq - 1) / tq + num_seqs) : 0;
     p.xcd_map = g.opt[ELSA_OPT_XCD_MAP];
     const long long total = (long long)p.q_tiles * B * H * num_splits;
     if (total > 0x7fffffffLL - 8) return ELSA_ERR_INVALID_ARG;
@@ -197,6 +204,21 @@ int elsa_get_option(int option, int *value) {
     if (!value) return ELSA_ERR_INVALID_ARG;
     *value = g.opt[option];
     return ELSA_OK;
+}
+
+int elsa_attn_fwd_varlen(const void *q, const void *k, const void *v, void *out,
+                         const int32_t *cu_seqlens, int num_seqs, int total_tokens, int max_seqlen,
+                         int H, int d, float scale, int causal, int dtype, void *stream) {
+    if (!q || !k || !v || !out || !cu_seqlens) return ELSA_ERR_INVALID_ARG;
+    if (!std::isfinite(scale)) return ELSA_ERR_INVALID_ARG;
+    if (num_seqs <= 0 || num_seqs > kMaxSeqs || total_tokens <= 0 || max_seqlen <= 0 || max_seqlen > total_tokens)
+        return ELSA_ERR_INVALID_ARG;
+    const int rc = check_common(1, H, total_tokens, d, dtype);
+    if (rc != ELSA_OK) return rc;
+    if (((long long)total_tokens / 32 + num_seqs) * (long long)H > 0x7fffff00LL) return ELSA_ERR_INVALID_ARG;
+    // tile choice as for num_seqs problems of max_seqlen tokens; no key split on this path
+    return run_forward(q, k, v, out, nullptr, nullptr, nullptr, num_seqs, H, max_seqlen, d, scale, causal, nullptr, 1, 0,
+                       0, dtype, stream, cu_seqlens, num_seqs, total_tokens);
 }
 
 const char *elsa_variant_name(int path, int variant) {

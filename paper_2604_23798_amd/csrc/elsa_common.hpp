@@ -33,6 +33,11 @@ struct FwdParams {
     int m_natural;                   // 1: part_m in natural-log units, 0: log2 units (internal)
     int xcd_map;                     // block -> work item order, see decode_work
     int q_tiles;                     // ceil(n / T_q) for the launched configuration
+    int tq;                          // T_q of the launched configuration
+    // packed variable-length layout [total_tokens][H][d] (nullptr = dense [B][H][n][d]):
+    const int32_t *cu_seqlens;       // device [num_seqs + 1], token offsets of the sequences
+    int num_seqs;
+    int var_tiles;                   // upper bound of query tiles over all sequences
 };
 
 struct CombineParams {
@@ -72,12 +77,39 @@ struct Work {
     int qt, c;
     long long bh;
     bool valid;
+    int n;             // keys (= queries) of the sequence this block works on
+    long long base;    // element offset of token 0 of this (sequence, head)
+    long long ts;      // elements between consecutive tokens
 };
+template <int D>
 __device__ __forceinline__ Work decode_work(const FwdParams &p) {
+    Work r;
+    if (p.cu_seqlens) {
+        // packed sequences: the head index runs fastest; the tile's sequence is found by walking
+        // the (short) list of sequence lengths, every value being wave-uniform
+        const long long w = blockIdx.x;
+        const int hd = (int)(w % p.H);
+        const int t = (int)(w / p.H);
+        int s = 0, before = 0, len = 0, tiles = 0;
+        for (; s < p.num_seqs; ++s) {
+            len = p.cu_seqlens[s + 1] - p.cu_seqlens[s];
+            tiles = len > 0 ? (len + p.tq - 1) / p.tq : 0;
+            if (t < before + tiles) break;
+            before += tiles;
+        }
+        r.valid = s < p.num_seqs;
+        r.c = 0;
+        r.bh = (long long)s * p.H + hd;
+        r.n = r.valid ? len : 0;
+        r.qt = t - before;
+        if (p.causal) r.qt = tiles - 1 - r.qt;
+        r.ts = (long long)p.H * D;
+        r.base = r.valid ? (long long)p.cu_seqlens[s] * r.ts + (long long)hd * D : 0;
+        return r;
+    }
     const long long BH = (long long)p.B * p.H;
     const long long total = (long long)p.q_tiles * BH * p.num_splits;
     long long w = blockIdx.x;
-    Work r;
     if (p.xcd_map == 2) {
         const long long per = (total + kNumXcd - 1) / kNumXcd;
         w = (w % kNumXcd) * per + w / kNumXcd;
@@ -95,6 +127,9 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
         r.bh = t / p.num_splits;
     }
     if (p.causal) r.qt = p.q_tiles - 1 - r.qt;   // longest rows first
+    r.n = p.n;
+    r.ts = D;
+    r.base = r.bh * (long long)p.n * D;
     return r;
 }
 

@@ -22,11 +22,12 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wq = wave % WQ, wk = wave / WQ;
 
-    const Work wi = decode_work(p);
+    const Work wi = decode_work<D>(p);
     if (!wi.valid) return;
     const int qt = wi.qt, c = wi.c;
     const long long bh = wi.bh;
-    const int n = p.n;
+    const int n = wi.n;
+    const long long ts = wi.ts;          // elements between consecutive tokens
     int L = n;
     if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), n);
     const int q0 = qt * TQ;
@@ -42,7 +43,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
     const int wrow0 = q0 + wq * 64;
     if (p.causal) wend = min(wend, wrow0 + 64);
 
-    const long long head_off = bh * (long long)n * D;
+    const long long head_off = wi.base;
     const int row = wrow0 + lane;
     const int lim = p.causal ? min(wend, row + 1) : wend;      // keys >= lim are invisible to this row
 
@@ -50,7 +51,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
 #pragma unroll
     for (int c4 = 0; c4 < D / 4; ++c4) {
         f32x4 x = {0.f, 0.f, 0.f, 0.f};
-        if (row < n) x = Io<T>::load4(p.q, head_off + (long long)row * D + 4 * c4);
+        if (row < n) x = Io<T>::load4(p.q, head_off + (long long)row * ts + 4 * c4);
 #pragma unroll
         for (int t = 0; t < 4; ++t) qr[4 * c4 + t] = x[t] * p.qscale;
     }
@@ -68,7 +69,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int key = min(j0 + g, n - 1);                // clamp: never read past the tensor
-            const T *__restrict__ kj = kp + (long long)key * D;
+            const T *__restrict__ kj = kp + (long long)key * ts;
             float acc = 0.f;
 #pragma unroll
             for (int t = 0; t < D; ++t) acc = fmaf(qr[t], ld_uniform(kj, t), acc);
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const int key = min(j0 + g, n - 1);
-            const T *__restrict__ vj = vp + (long long)key * D;
+            const T *__restrict__ vj = vp + (long long)key * ts;
 #pragma unroll
             for (int t = 0; t < D; ++t) W[t] = fmaf(e[g], ld_uniform(vj, t), W[t]);
         }
@@ -140,7 +141,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
         const float f = S > 0.f ? 1.f / S : 0.f;
 #pragma unroll
         for (int c4 = 0; c4 < D / 4; ++c4)
-            Io<T>::store4(p.out, head_off + (long long)row * D + 4 * c4,
+            Io<T>::store4(p.out, head_off + (long long)row * ts + 4 * c4,
                           f32x4{W[4 * c4] * f, W[4 * c4 + 1] * f, W[4 * c4 + 2] * f, W[4 * c4 + 3] * f});
     }
 }
@@ -162,9 +163,9 @@ static int launch_one(const FwdParams &p, hipStream_t s) {
         if (e != hipSuccess) return (int)e;
         attr_done = true;
     }
-    const long long total = (long long)p.q_tiles * p.B * p.H * p.num_splits;
+    const long long total = p.cu_seqlens ? (long long)p.var_tiles * p.H : (long long)p.q_tiles * p.B * p.H * p.num_splits;
     long long blocks = total;
-    if (p.xcd_map == 2) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
+    if (p.xcd_map == 2 && !p.cu_seqlens) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * WQ * WK), smem, s, p);
     return (int)hipGetLastError();

@@ -49,11 +49,12 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     const int wq = wave % WQ, wk = wave / WQ;
     const int j = lane & 31, h = lane >> 5;
 
-    const Work wi = decode_work(p);
+    const Work wi = decode_work<D>(p);
     if (!wi.valid) return;
     const int qt = wi.qt, c = wi.c;
     const long long bh = wi.bh;
-    const int n = p.n;
+    const int n = wi.n;
+    const long long ts = wi.ts;          // elements between consecutive tokens
     int L = n;
     if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), n);
     const int q0 = qt * TQ;
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     if (p.causal) kend = min(kend, q0 + TQ);
     const int ntiles = kend > kbeg ? (kend - kbeg + TKB - 1) / TKB : 0;
 
-    const long long head_off = bh * (long long)n * D;
+    const long long head_off = wi.base;
     const int wrow0 = q0 + wq * NQ * 32;    // first query row of this wave
 
     // ---- Q fragments (B operand).  MFMA step s = 4*cc + t contracts columns
@@ -74,7 +75,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 #pragma unroll
         for (int cc = 0; cc < D / 8; ++cc) {
             f32x4 x = {0.f, 0.f, 0.f, 0.f};
-            if (row < n) x = Io<T>::load4(p.q, head_off + (long long)row * D + 8 * cc + 4 * h);
+            if (row < n) x = Io<T>::load4(p.q, head_off + (long long)row * ts + 8 * cc + 4 * h);
 #pragma unroll
             for (int t = 0; t < 4; ++t) qf[nq][4 * cc + t] = x[t] * p.qscale;
         }
@@ -107,7 +108,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
             const int key = kb0 + row;
             f32x4 kx = {0.f, 0.f, 0.f, 0.f}, vx = {0.f, 0.f, 0.f, 0.f};
             if (key < kend) {               // rows past the chunk are zero (and masked below)
-                const long long off = head_off + (long long)key * D + 4 * c4;
+                const long long off = head_off + (long long)key * ts + 4 * c4;
                 kx = Io<T>::load4(p.k, off);
                 vx = Io<T>::load4(p.v, off);
             }
@@ -371,7 +372,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
             obase = prow * D;
         } else {
             f = stot[nq] > 0.f ? 1.f / stot[nq] : 0.f;
-            obase = head_off + (long long)row * D;
+            obase = head_off + (long long)row * ts;
         }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
@@ -433,9 +434,9 @@ static int launch_one(const FwdParams &p, hipStream_t s) {
         if (e != hipSuccess) return (int)e;
         attr_done = true;
     }
-    const long long total = (long long)p.q_tiles * p.B * p.H * p.num_splits;
+    const long long total = p.cu_seqlens ? (long long)p.var_tiles * p.H : (long long)p.q_tiles * p.B * p.H * p.num_splits;
     long long blocks = total;
-    if (p.xcd_map == 2) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
+    if (p.xcd_map == 2 && !p.cu_seqlens) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * WQ * WK), smem, s, p);
     return (int)hipGetLastError();

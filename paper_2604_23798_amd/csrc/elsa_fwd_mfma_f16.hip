@@ -49,11 +49,12 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
     const int wq = wave % WQ, wk = wave / WQ;
     const int j = lane & 31, h = lane >> 5;
 
-    const Work wi = decode_work(p);
+    const Work wi = decode_work<D>(p);
     if (!wi.valid) return;
     const int qt = wi.qt, c = wi.c;
     const long long bh = wi.bh;
-    const int n = p.n;
+    const int n = wi.n;
+    const long long ts = wi.ts;          // elements between consecutive tokens
     int L = n;
     if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), n);
     const int q0 = qt * TQ;
@@ -62,7 +63,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
     if (p.causal) kend = min(kend, q0 + TQ);
     const int ntiles = kend > kbeg ? (kend - kbeg + TKB - 1) / TKB : 0;
 
-    const long long head_off = bh * (long long)n * D;
+    const long long head_off = wi.base;
     const int wrow0 = q0 + wq * NQ * 32;
     const _Float16 *qp = static_cast<const _Float16 *>(p.q);
     const _Float16 *kp = static_cast<const _Float16 *>(p.k);
@@ -81,7 +82,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
 #pragma unroll
         for (int cc = 0; cc < KC; ++cc) {
             f16x8 x = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (row < n) x = *reinterpret_cast<const f16x8 *>(qp + head_off + (long long)row * D + 16 * cc + 8 * h);
+            if (row < n) x = *reinterpret_cast<const f16x8 *>(qp + head_off + (long long)row * ts + 16 * cc + 8 * h);
             if (flip) x = -x;
             qf[nq][cc] = x;
         }
@@ -109,7 +110,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
             const int key = kb0 + row;
             f16x8 kx = {0, 0, 0, 0, 0, 0, 0, 0}, vx = {0, 0, 0, 0, 0, 0, 0, 0};
             if (key < kend) {
-                const long long off = head_off + (long long)key * D + 8 * c8;
+                const long long off = head_off + (long long)key * ts + 8 * c8;
                 kx = *reinterpret_cast<const f16x8 *>(kp + off);
                 vx = *reinterpret_cast<const f16x8 *>(vp + off);
             }
@@ -305,7 +306,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
             obase = prow * D;
         } else {
             f = stot[nq] > 0.f ? 1.f / stot[nq] : 0.f;
-            obase = head_off + (long long)row * D;
+            obase = head_off + (long long)row * ts;
         }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
@@ -350,9 +351,9 @@ static int launch_one16(const FwdParams &p, hipStream_t s) {
         if (e != hipSuccess) return (int)e;
         attr_done = true;
     }
-    const long long total = (long long)p.q_tiles * p.B * p.H * p.num_splits;
+    const long long total = p.cu_seqlens ? (long long)p.var_tiles * p.H : (long long)p.q_tiles * p.B * p.H * p.num_splits;
     long long blocks = total;
-    if (p.xcd_map == 2) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
+    if (p.xcd_map == 2 && !p.cu_seqlens) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
     hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(64 * WQ * WK), smem, s, p);
     return (int)hipGetLastError();

@@ -17,7 +17,7 @@ F32, F16 = 0, 1
 OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP = 0, 1, 2, 3
 PATH_AUTO, PATH_FMA, PATH_MFMA, PATH_MFMA16 = 0, 1, 2, 3
 
-EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_split_kv", "elsa_combine",
+EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
            "elsa_split_kv_workspace_bytes", "elsa_set_workspace", "elsa_set_option", "elsa_get_option",
            "elsa_variant_name", "elsa_last_kernel", "elsa_status_string", "elsa_debug_layout_probe")
 
@@ -29,6 +29,7 @@ _lib = ctypes.CDLL(LIB_PATH)
 _vp, _i, _f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
 _lib.elsa_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _i, _vp]
 _lib.elsa_attn_fwd_masked.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
+_lib.elsa_attn_fwd_varlen.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _i, _vp]
 _lib.elsa_attn_fwd_split_kv.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _i, _vp]
 _lib.elsa_combine.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]
 _lib.elsa_split_kv_workspace_bytes.argtypes = [_i, _i, _i, _i, _i]
@@ -101,6 +102,20 @@ def elsa_attn_fwd_masked(q, k, v, out, scale, causal=False, kv_len=None, stream=
         assert kv_len.is_cuda and kv_len.dtype == torch.int32 and kv_len.shape == (B,) and kv_len.is_contiguous()
     _check(_lib.elsa_attn_fwd_masked(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, n, d, float(scale),
                                      int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
+    return out
+
+
+def elsa_attn_fwd_varlen(q, k, v, out, cu_seqlens, max_seqlen, scale, causal=False, stream=None):
+    """Packed sequences: q, k, v, out are [total_tokens, H, d]; cu_seqlens is device int32 [num_seqs + 1]."""
+    import torch
+    assert q.is_cuda and q.dim() == 3 and q.shape == k.shape == v.shape == out.shape
+    assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and out.is_contiguous()
+    assert q.dtype == k.dtype == v.dtype == out.dtype
+    assert cu_seqlens.is_cuda and cu_seqlens.dtype == torch.int32 and cu_seqlens.dim() == 1
+    T, H, d = (int(x) for x in q.shape)
+    _check(_lib.elsa_attn_fwd_varlen(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(cu_seqlens),
+                                     int(cu_seqlens.numel()) - 1, T, int(max_seqlen), H, d, float(scale),
+                                     int(bool(causal)), _dtype_code(q), _stream(stream)))
     return out
 
 

@@ -161,6 +161,25 @@ def make(w: Workload):
     return q, k, v, kv_len
 
 
+def make_varlen(seed: int, num_seqs: int = 8, lo: int = 256, hi: int = 1792, H: int = 12, d: int = 64,
+                fp16: bool = False, lengths=None):
+    """Packed variable-length batch: ``num_seqs`` sequences with lengths uniform on [lo, hi] (the
+    paper's padding-free workload draws 8 lengths from [256, 1792]) or the given ``lengths``.
+
+    Returns ``(q, k, v, cu_seqlens)``: ``[total_tokens, H, d]`` arrays and int32 ``[num_seqs + 1]``."""
+    lens = integers(seed, STREAM_LEN, num_seqs, lo, hi) if lengths is None else np.asarray(lengths, np.int32)
+    cu = np.zeros(lens.size + 1, dtype=np.int32)
+    cu[1:] = np.cumsum(lens)
+    total = int(cu[-1])
+    shape = (total, H, d)
+    q = normal(seed, STREAM_Q, 0, total * H * d).reshape(shape)
+    k = normal(seed, STREAM_K, 0, total * H * d).reshape(shape)
+    v = normal(seed, STREAM_V, 0, total * H * d).reshape(shape)
+    if fp16:
+        q, k, v = (t.astype(np.float16) for t in (q, k, v))
+    return q, k, v, cu
+
+
 def sample_rows(w: Workload, per_head: int = 64, tile: int = 128, seed: int = 7) -> np.ndarray:
     """Seeded sample of flat query rows: per (b,h) the first and last row, the
     neighbours of a few tile boundaries, and random rows up to ``per_head``."""

@@ -72,3 +72,15 @@ def parts_to_rows(pm, pS, pW):
     S = pS.permute(0, 1, 3, 2).reshape(B * H * n, C).double().cpu().numpy()
     W = pW.permute(0, 1, 3, 2, 4).reshape(B * H * n, C, d).double().cpu().numpy()
     return m, S, W
+
+
+def fwd_varlen(q, k, v, cu, max_seqlen, scale, causal=False):
+    """elsa_attn_fwd_varlen on packed numpy inputs [T,H,d] -> float64 [T,H,d]."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    tq, tk, tv = to_dev(q), to_dev(k), to_dev(v)
+    tcu = torch.from_numpy(np.asarray(cu, np.int32)).cuda()
+    out = torch.full_like(tq, float("nan"))
+    elsa.elsa_attn_fwd_varlen(tq, tk, tv, out, tcu, max_seqlen, scale, causal)
+    torch.cuda.synchronize()
+    return out.double().cpu().numpy()

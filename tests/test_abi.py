@@ -77,3 +77,7 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert lib.elsa_set_workspace(ctypes.c_void_p(8), 1024) == 3
     assert lib.elsa_set_workspace(None, 0) == 0
     assert lib.elsa_debug_layout_probe(None, None) == INV
+    vl = lambda **kw: lib.elsa_attn_fwd_varlen(p, p, p, p, kw.get("cu", p), kw.get("ns", 2), kw.get("T", 64),
+                                               kw.get("mx", 40), 2, kw.get("d", 64), 0.125, 0, 0, None)
+    assert vl(cu=None) == INV and vl(ns=0) == INV and vl(ns=5000) == INV and vl(T=0) == INV
+    assert vl(mx=0) == INV and vl(mx=65) == INV and vl(d=96) == UNS

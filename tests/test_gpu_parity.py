@@ -276,6 +276,35 @@ def test_wide_scores_one_hot_and_shift(path, variant):
         assert_parity(out, ref, 2e-5 + 32 * 2.0 ** -24 * abs(c), "shift %g" % c)
 
 
+@pytest.mark.parametrize("path,variant", [(MFMA, 1), (MFMA, 2), (MFMA, 3), (FMA, 1), (FMA, 2)])
+def test_varlen_packed_sequences(path, variant):
+    lens = [197, 0, 1, 130, 64, 33, 300]
+    q, k, v, cu = inputs.make_varlen(17, lengths=lens, H=3, d=64)
+    T = q.shape[0]
+    for causal in (False, True):
+        ref = oracle.attn_varlen(q, k, v, cu, 0.125, causal=causal).reshape(T * 3, 64)
+        with G.Options(path=path, variant=variant):
+            out = G.fwd_varlen(q, k, v, cu, max(lens), 0.125, causal=causal).reshape(T * 3, 64)
+        assert_parity(out, ref, tolerance(max(lens)), "varlen path%d v%d causal=%d" % (path, variant, causal))
+    # a single packed sequence with one head is the dense problem: same kernel, same bits
+    q1, k1, v1, cu1 = inputs.make_varlen(18, lengths=[257], H=1, d=64)
+    with G.Options(path=path, variant=variant):
+        a = G.fwd_varlen(q1, k1, v1, cu1, 257, 0.125).reshape(257, 64)
+        b = G.fwd(q1.reshape(1, 1, 257, 64), k1.reshape(1, 1, 257, 64), v1.reshape(1, 1, 257, 64), 0.125)
+    assert np.array_equal(a, b)
+
+
+@pytest.mark.parametrize("d", [64, 128])
+def test_varlen_fp16_and_paper_recipe(d):
+    # 8 sequences with lengths uniform on [256, 1792] (the padding-free workload), default kernels
+    for fp16 in (False, True):
+        q, k, v, cu = inputs.make_varlen(19, 8, 256, 1792, H=2, d=d, fp16=fp16)
+        T = q.shape[0]
+        ref = oracle.attn_varlen(q, k, v, cu, d ** -0.5, causal=False).reshape(T * 2, d)
+        out = G.fwd_varlen(q, k, v, cu, int(np.diff(cu).max()), d ** -0.5).reshape(T * 2, d)
+        assert_parity(out, ref, tolerance(1792, fp16), "varlen recipe d=%d fp16=%d" % (d, fp16))
+
+
 def test_deterministic_and_option_reporting():
     from paper_2604_23798_amd import elsa
     q, k, v = _rand(1, 4, 777, 64, 81)

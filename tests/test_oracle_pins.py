@@ -191,3 +191,20 @@ def test_ladder_f32_is_close_but_not_exact():
     lad = oracle.ladder_f32_fold_rows(q, k, v, 0.125).astype(np.float64)
     err = np.linalg.norm(lad - ref, axis=1) / np.linalg.norm(ref, axis=1)
     assert 0 < err.max() < 1e-5
+
+
+def test_varlen_reduces_to_dense_problems():
+    # equal-length packed sequences are a dense batch in another layout; unequal ones are independent
+    B, H, n, d = 3, 2, 17, 8
+    q, k, v = _rand(B, H, n, d, 61)
+    pk = lambda t: np.ascontiguousarray(t.transpose(0, 2, 1, 3)).reshape(B * n, H, d)      # [B,n,H,d] packed
+    cu = np.arange(B + 1) * n
+    for causal in (False, True):
+        dense = oracle.attn_rows(q, k, v, 0.3, causal=causal).reshape(B, H, n, d)
+        _close(oracle.attn_varlen(pk(q), pk(k), pk(v), cu, 0.3, causal=causal).reshape(B, n, H, d),
+               dense.transpose(0, 2, 1, 3))
+    q2, k2, v2, cu2 = inputs.make_varlen(5, lengths=[4, 0, 1, 9], H=2, d=8)
+    out = oracle.attn_varlen(q2, k2, v2, cu2, 0.5)
+    _close(out[4], v2[4])                                    # the one-token sequence returns its value
+    _close(out[5:], oracle.attn_varlen(q2[5:], k2[5:], v2[5:], [0, 9], 0.5))
+    _close(out[:4], oracle.attn_varlen(q2[:4], k2[:4], v2[:4], [0, 4], 0.5))
