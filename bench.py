@@ -7,7 +7,10 @@ one batch of seeded synthetic input that is already resident in HBM.  The defaul
 the one the headline metric is quoted on: the long-sequence sweep at n = 16384, d = 64
 (B = 1, H = 16), FP32.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--path auto|fma|mfma]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--path auto|fma|mfma|mfma16]
+
+``--workload`` takes any name of ``paper_2604_23798_amd.inputs.WORKLOADS`` or ``varlen_8x1792``
+(8 packed sequences with lengths uniform on [256, 1792], H = 12, d = 64; add ``_fp16`` for FP16).
 """
 import argparse
 import json
@@ -19,7 +22,12 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_FP32_TFLOPS = 157.3      # MI355X dense FP32 (matrix = vector peak): 256 CU x 256 flop/clk x 2.4 GHz
+PEAK_FP32_TFLOPS = 157.3        # MI355X dense FP32 (matrix = vector peak): 256 CU x 256 flop/clk x 2.4 GHz
+PEAK_FP32_VALU_UNPACKED = 78.6  # plain v_fma_f32 (packed FP32 is disabled in this build): half of the above
+PEAK_FP16_TFLOPS = 2500.0       # MI355X dense FP16 MFMA
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
+# counter reads for a plain copy of known size in the same run (profiles/*_counters.md).
+MEASURED_TRAFFIC = {("sweep_n16384", "mfma_q256_w4"): 6.606e8, ("sweep_n16384", "mfma_q128_w4"): 1.208e9}
 
 
 def cpu_baseline(w, q, k, v, kv_len, gpu_out, budget_rows):
@@ -52,13 +60,34 @@ def cpu_baseline(w, q, k, v, kv_len, gpu_out, budget_rows):
     return base, par
 
 
+def cpu_baseline_varlen(q, k, v, cu, scale, gpu_out, fp16):
+    """Oracle on the first heads of the packed batch (bounded), timed; parity on the same slice."""
+    import numpy as np
+    import oracle
+    from tests.parity import metrics
+    hs = 2
+    f32 = lambda t: np.ascontiguousarray(t[:, :hs].astype(np.float32))
+    t0 = time.perf_counter()
+    ref = oracle.attn_varlen(f32(q), f32(k), f32(v), cu, scale)
+    dt = time.perf_counter() - t0
+    lens = np.diff(cu).astype(np.float64)
+    flops = float(4 * hs * q.shape[2] * np.sum(lens * lens))
+    tol = 2e-3 if fp16 else 2e-5
+    par = metrics(gpu_out[:, :hs].reshape(-1, q.shape[2]), ref.reshape(-1, q.shape[2]), tol)
+    par["tol"] = tol
+    par["pass"] = bool(par["e_row"] <= tol and par["e_mix"] <= tol)
+    base = {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+            "sample": "all rows of the first %d heads of the packed batch, FP64 single thread, %.1f s" % (hs, dt)}
+    return base, par
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="sweep_n16384")
-    ap.add_argument("--path", default="auto", choices=["auto", "fma", "mfma"])
+    ap.add_argument("--path", default="auto", choices=["auto", "fma", "mfma", "mfma16"])
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--xcd-map", type=int, default=0)
     ap.add_argument("--oracle-rows", type=int, default=4096, help="row budget of the cpu_baseline leg (0 = skip)")
@@ -76,14 +105,26 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    w = inputs.WORKLOADS[a.workload]
-    q, k, v, kv_len = inputs.make(w)
+    varlen = a.workload.startswith("varlen_8x1792")
+    if varlen:
+        fp16 = a.workload.endswith("_fp16")
+        H, d = 12, 64
+        q, k, v, cu = inputs.make_varlen(1006, 8, 256, 1792, H=H, d=d, fp16=fp16)
+        lens = np.diff(cu).astype(np.int64)
+        tcu = torch.from_numpy(cu).cuda()
+        scale = float(np.float32(d ** -0.5))
+        flops = int(4 * H * d * np.sum(lens * lens))
+        causal, kv_len = False, None
+    else:
+        w = inputs.WORKLOADS[a.workload]
+        q, k, v, kv_len = inputs.make(w)
+        fp16, causal, scale, flops = w.fp16, w.causal, w.scale, w.flops
     tq, tk, tv = (torch.from_numpy(t).cuda() for t in (q, k, v))
     tl = None if kv_len is None else torch.from_numpy(kv_len).cuda()
     out = torch.empty_like(tq)
     ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
     elsa.elsa_set_workspace(ws)
-    elsa.elsa_set_option(elsa.OPT_PATH, {"auto": 0, "fma": 1, "mfma": 2}[a.path])
+    elsa.elsa_set_option(elsa.OPT_PATH, {"auto": 0, "fma": 1, "mfma": 2, "mfma16": 3}[a.path])
     elsa.elsa_set_option(elsa.OPT_VARIANT, a.variant)
     elsa.elsa_set_option(elsa.OPT_XCD_MAP, a.xcd_map)
 
@@ -93,8 +134,12 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
 
-    def step():
-        elsa.elsa_attn_fwd_masked(tq, tk, tv, out, w.scale, w.causal, tl)
+    if varlen:
+        def step():
+            elsa.elsa_attn_fwd_varlen(tq, tk, tv, out, tcu, int(lens.max()), scale, causal)
+    else:
+        def step():
+            elsa.elsa_attn_fwd_masked(tq, tk, tv, out, scale, causal, tl)
 
     for _ in range(a.warmup):
         step()
@@ -111,26 +156,41 @@ def main():
     ms_kernel = ev0.elapsed_time(ev1) / a.steps
     kernel = elsa.elsa_last_kernel()
 
-    flops = w.flops                    # 4 B H n^2 d, the square count the metric is defined on
+    # flops: 4 B H n^2 d, the square count the metric is defined on (sum of len^2 for packed batches)
     value = flops / (ms_step * 1e-3) / 1e12
     achieved = flops / (ms_kernel * 1e-3) / 1e12
+    if kernel.startswith("fma"):
+        bound, peak = "alu", PEAK_FP32_VALU_UNPACKED
+    elif kernel.startswith("mfma16"):
+        bound, peak = "mfma", PEAK_FP16_TFLOPS
+    else:
+        bound, peak = "mfma", PEAK_FP32_TFLOPS
+    name = a.workload
     rec = {
-        "metric": "FP32 attention TFLOP/s at n=16K, d=64 (4*B*H*n^2*d / time)" if a.workload == "sweep_n16384"
+        "metric": "FP32 attention TFLOP/s at n=16K, d=64 (4*B*H*n^2*d / time)" if name == "sweep_n16384"
         else "attention TFLOP/s (4*B*H*n^2*d / time)",
         "value": value, "unit": "TFLOP/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16 io / f32 accumulate" if w.fp16 else "f32", "data": "synthetic",
+        "dtype": "f16 io / f32 state" if fp16 else "f32", "data": "synthetic",
         "pct_of_fp32_peak": 100.0 * value / PEAK_FP32_TFLOPS,
-        "config": {"workload": w.name, "B": w.B, "H": w.H, "n": w.n, "d": w.d, "causal": w.causal,
-                   "padded": w.padded, "kernel": kernel, "path": a.path},
-        "roofline": {"bound": "alu" if kernel.startswith("fma") else "mfma", "achieved": achieved,
-                     "peak": PEAK_FP32_TFLOPS, "unit": "TFLOP/s", "frac": achieved / PEAK_FP32_TFLOPS,
-                     "traffic": None, "kernel_ms": ms_kernel},
+        "config": {"workload": name, "causal": bool(causal), "kernel": kernel, "path": a.path},
+        "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
+                     "frac": achieved / peak, "traffic": MEASURED_TRAFFIC.get((name, kernel)),
+                     "kernel_ms": ms_kernel},
     }
-    if w.causal:
-        rec["causal_effective_tflops"] = 4.0 * w.B * w.H * w.d * (w.n * (w.n + 1) / 2) / (ms_step * 1e-3) / 1e12
+    if varlen:
+        rec["config"].update({"num_seqs": 8, "lengths": [int(x) for x in lens], "H": H, "d": d})
+        rec["tokens_per_s"] = float(lens.sum()) / (ms_step * 1e-3)
+    else:
+        rec["config"].update({"B": w.B, "H": w.H, "n": w.n, "d": w.d, "padded": w.padded})
+        if w.causal:
+            rec["causal_effective_tflops"] = 4.0 * w.B * w.H * w.d * (w.n * (w.n + 1) / 2) / (ms_step * 1e-3) / 1e12
     if a.oracle_rows > 0:
-        base, par = cpu_baseline(w, q, k, v, kv_len, out.double().cpu().numpy(), a.oracle_rows)
+        host = out.double().cpu().numpy()
+        if varlen:
+            base, par = cpu_baseline_varlen(q, k, v, cu, scale, host, fp16)
+        else:
+            base, par = cpu_baseline(w, q, k, v, kv_len, host, a.oracle_rows)
         rec["cpu_baseline"] = base
         rec["parity"] = par
     elsa.elsa_set_workspace(None)

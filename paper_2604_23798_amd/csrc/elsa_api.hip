@@ -216,9 +216,12 @@ int elsa_attn_fwd_varlen(const void *q, const void *k, const void *v, void *out,
     const int rc = check_common(1, H, total_tokens, d, dtype);
     if (rc != ELSA_OK) return rc;
     if (((long long)total_tokens / 32 + num_seqs) * (long long)H > 0x7fffff00LL) return ELSA_ERR_INVALID_ARG;
-    // tile choice as for num_seqs problems of max_seqlen tokens; no key split on this path
-    return run_forward(q, k, v, out, nullptr, nullptr, nullptr, num_seqs, H, max_seqlen, d, scale, causal, nullptr, 1, 0,
-                       0, dtype, stream, cu_seqlens, num_seqs, total_tokens);
+    // tile choice as for one sequence holding every token plus half a wasted tile per sequence
+    // (about the number of blocks the packed batch really yields); no key split on this path
+    const long long n_eff = (long long)total_tokens + 64LL * num_seqs;
+    (void)max_seqlen;
+    return run_forward(q, k, v, out, nullptr, nullptr, nullptr, 1, H, (int)(n_eff > 0x7fffffff ? 0x7fffffff : n_eff), d,
+                       scale, causal, nullptr, 1, 0, 0, dtype, stream, cu_seqlens, num_seqs, total_tokens);
 }
 
 const char *elsa_variant_name(int path, int variant) {
