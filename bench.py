@@ -81,6 +81,47 @@ def cpu_baseline_varlen(q, k, v, cu, scale, gpu_out, fp16):
     return base, par
 
 
+def scaling_fit(a):
+    """Per-head latency over n = 2^10..2^15 and the fit T(n) = a*L(n,B) + b*n^2 + c with B = 128
+    (the paper's empirical scaling validation; FP16 and FP32 I/O, H = 16, d = 64, no key split)."""
+    import math
+    import numpy as np
+    import torch
+    from paper_2604_23798_amd import elsa, inputs
+    H, d = 16, 64
+    res = {"metric": "per-head attention latency fit T(n) = a*L(n,128) + b*n^2 + c", "unit": "ms", "n_gpus": 1,
+           "H": H, "d": d, "steps": a.steps, "warmup": a.warmup, "fits": {}}
+    for fp16 in (True, False):
+        ns, ts = [], []
+        for lg in range(10, 16):
+            n = 1 << lg
+            w = inputs.Workload("fit", B=1, H=H, n=n, d=d, seed=1200 + lg, fp16=fp16)
+            q, k, v, _ = inputs.make(w)
+            tq, tk, tv = (torch.from_numpy(t).cuda() for t in (q, k, v))
+            out = torch.empty_like(tq)
+            for _ in range(a.warmup):
+                elsa.elsa_attn_fwd(tq, tk, tv, out, w.scale, False)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(a.steps):
+                elsa.elsa_attn_fwd(tq, tk, tv, out, w.scale, False)
+            e1.record()
+            torch.cuda.synchronize()
+            ns.append(n)
+            ts.append(e0.elapsed_time(e1) / a.steps / H)
+        L = [math.ceil(math.log2(128)) + 2 * math.ceil(math.log2(n / 128)) + 3 for n in ns]
+        A = np.array([[l, float(n) * n, 1.0] for l, n in zip(L, ns)])
+        coef, *_ = np.linalg.lstsq(A, np.array(ts), rcond=None)
+        pred = A @ coef
+        ss_res = float(np.sum((np.array(ts) - pred) ** 2))
+        ss_tot = float(np.sum((np.array(ts) - np.mean(ts)) ** 2))
+        res["fits"]["fp16" if fp16 else "fp32"] = {
+            "n": ns, "L": L, "ms_per_head": ts, "a": float(coef[0]), "b": float(coef[1]), "c": float(coef[2]),
+            "r2": 1.0 - ss_res / ss_tot}
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -91,6 +132,9 @@ def main():
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--xcd-map", type=int, default=0)
     ap.add_argument("--oracle-rows", type=int, default=4096, help="row budget of the cpu_baseline leg (0 = skip)")
+    ap.add_argument("--scaling-fit", action="store_true",
+                    help="instead of one workload: per-head latency for n = 2^10..2^15 (H=16, d=64) and the "
+                         "least-squares fit T(n) = a*L(n,128) + b*n^2 + c of the paper's scaling study")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -105,6 +149,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if a.scaling_fit:
+        print(json.dumps(scaling_fit(a)))
+        return
     varlen = a.workload.startswith("varlen_8x1792")
     if varlen:
         fp16 = a.workload.endswith("_fp16")

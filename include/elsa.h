@@ -61,6 +61,16 @@ int elsa_attn_fwd_masked(const void *q, const void *k, const void *v, void *out,
                          const int32_t *kv_len, int dtype, void *stream);
 
 /*
+ * As elsa_attn_fwd_masked, and additionally writes the log-normaliser of every row,
+ *   lse[b][h][i] = ln sum_j e^{s_ij} = m_i + ln S_i     (FP32, natural log, [B][H][n]),
+ * from which the attention probabilities of the drift metrics follow as
+ * P_ij = e^{s_ij - lse_i}.  A row with no visible key gets -inf.  lse must not be NULL.
+ */
+int elsa_attn_fwd_lse(const void *q, const void *k, const void *v, void *out, float *lse,
+                      int B, int H, int n, int d, float scale, int causal,
+                      const int32_t *kv_len, int dtype, void *stream);
+
+/*
  * Padding-free variable-length batches (the packed layout of the paper's
  * "padding-free variable-length" workload): Q, K, V, out are [total_tokens][H][d],
  * sequence s owns tokens cu_seqlens[s] .. cu_seqlens[s+1]-1 (device int32

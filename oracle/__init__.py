@@ -45,6 +45,7 @@ def _load():
         rows_sig = [fp, fp, fp, I, I, I, I, D, I, ip, lp, L, dp]
         lib.elsa_oracle_attn_rows.argtypes = rows_sig
         lib.elsa_oracle_fold_rows.argtypes = rows_sig
+        lib.elsa_oracle_lse_rows.argtypes = [fp, fp, I, I, I, I, D, I, ip, lp, L, dp]
         lib.elsa_oracle_partials_rows.argtypes = [fp, fp, fp, I, I, I, I, D, I, ip, I, lp, L, dp, dp, dp]
         mrg = [D, D, dp, D, D, dp, I, dp, dp, dp]
         lib.elsa_oracle_merge_case.argtypes = mrg
@@ -107,6 +108,17 @@ def fold_rows(q, k, v, scale, causal=False, kv_len=None, rows=None):
     out = np.empty((rows.size, d), dtype=np.float64)
     rc = _load().elsa_oracle_fold_rows(qp, kp, vp, B, H, n, d, float(scale), int(bool(causal)), klp,
                                        rp, rows.size, out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    assert rc == 0
+    return out
+
+
+def lse_rows(q, k, scale, causal=False, kv_len=None, rows=None):
+    """ln sum_j e^{s_ij} per row (float64 ``[len(rows)]``); ``-inf`` where no key is visible."""
+    keep, (qp, kp, _, B, H, n, d), klp, rp = _prep(q, k, k, kv_len, rows)
+    rows = keep[4]
+    out = np.empty(rows.size, dtype=np.float64)
+    rc = _load().elsa_oracle_lse_rows(qp, kp, B, H, n, d, float(scale), int(bool(causal)), klp, rp, rows.size,
+                                      out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
     assert rc == 0
     return out
 

@@ -92,6 +92,37 @@ int elsa_oracle_attn_rows(const float *q, const float *k, const float *v,
 }
 
 /*
+ * Log-normaliser of every sampled row: lse_i = ln sum_j e^{s_ij} = m + ln sum_j e^{s_ij - m}
+ * (the row sum s of Eq. 12 with its maximum put back); -inf for a row with no visible key.
+ * The attention probabilities of the drift metrics are P_ij = e^{s_ij - lse_i}.
+ */
+int elsa_oracle_lse_rows(const float *q, const float *k,
+                         int B, int H, int n, int d, double scale, int causal,
+                         const int32_t *kv_len,
+                         const int64_t *rows, int64_t nrows, double *lse)
+{
+    (void)B;
+    double *s = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    if (!s) return -1;
+    for (int64_t r = 0; r < nrows; ++r) {
+        int64_t row = rows[r];
+        int64_t i = row % n, bh = row / n, b = bh / H;
+        const float *qi = q + (size_t)row * d;
+        const float *kb = k + (size_t)bh * n * d;
+        int64_t L = visible_keys(i, n, causal, kv_len, b);
+        double m = -INFINITY, S = 0.0;
+        for (int64_t j = 0; j < L; ++j) {
+            s[j] = score(qi, kb + (size_t)j * d, d, scale);
+            if (s[j] > m) m = s[j];
+        }
+        for (int64_t j = 0; j < L; ++j) S += exp(s[j] - m);
+        lse[r] = (L > 0) ? m + log(S) : -INFINITY;
+    }
+    free(s);
+    return 0;
+}
+
+/*
  * Per-query sequential formulation (Alg. 1): start from the identity
  * (-inf, 0, 0); for each key either keep the maximum and add exp(s - m) (max
  * unchanged), or move the maximum to s, rescale the past by exp(m_old - s) and

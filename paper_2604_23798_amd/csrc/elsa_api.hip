@@ -55,7 +55,7 @@ int pick_variant(int path, long long BH, int n, int d, int splits) {
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
                 int B, int H, int n, int d, float scale, int causal, const int32_t *kv_len,
                 int num_splits, int emit, int m_natural, int dtype, void *stream,
-                const int32_t *cu_seqlens = nullptr, int num_seqs = 0, int total_tokens = 0) {
+                const int32_t *cu_seqlens = nullptr, int num_seqs = 0, int total_tokens = 0, float *lse = nullptr) {
     // auto: FP32 I/O -> FP32 MFMA; FP16 I/O -> FP16 MFMA (needs a non-zero scale)
     int path = g.opt[ELSA_OPT_PATH];
     if (path == 0) path = (dtype == ELSA_F16 && scale != 0.f) ? 3 : 2;
@@ -65,6 +65,7 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     if (tq <= 0) return ELSA_ERR_UNSUPPORTED;
     elsa::FwdParams p{};
     p.q = q; p.k = k; p.v = v; p.out = out;
+    p.lse = lse;
     p.part_m = pm; p.part_S = pS; p.part_W = pW;
     p.kv_len = kv_len;
     p.B = B; p.H = H; p.n = n;
@@ -140,7 +141,7 @@ int elsa_set_workspace(void *dev_ptr, size_t bytes) {
     return ELSA_OK;
 }
 
-int elsa_attn_fwd_masked(const void *q, const void *k, const void *v, void *out,
+static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out, float *lse,
                          int B, int H, int n, int d, float scale, int causal,
                          const int32_t *kv_len, int dtype, void *stream) {
     if (!q || !k || !v || !out) return ELSA_ERR_INVALID_ARG;
@@ -150,14 +151,27 @@ int elsa_attn_fwd_masked(const void *q, const void *k, const void *v, void *out,
     const int C = g.ws ? auto_splits(B, H, n, d) : 1;
     if (C == 1)
         return run_forward(q, k, v, out, nullptr, nullptr, nullptr, B, H, n, d, scale, causal, kv_len, 1, 0, 0, dtype,
-                           stream);
+                           stream, nullptr, 0, 0, lse);
     float *pm, *pS, *pW;
     carve(g.ws, B, H, n, d, C, &pm, &pS, &pW);
     // internal split: maxima stay in log2 units, so the second pass adds no rounding of m
     rc = run_forward(q, k, v, nullptr, pm, pS, pW, B, H, n, d, scale, causal, kv_len, C, 1, 0, dtype, stream);
     if (rc != ELSA_OK) return rc;
-    elsa::CombineParams cp{pm, pS, pW, out, (long long)B * H * n, n, C, 0, dtype == ELSA_F16};
+    elsa::CombineParams cp{pm, pS, pW, out, lse, (long long)B * H * n, n, C, 0, dtype == ELSA_F16};
     return elsa::launch_combine(cp, d, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
+}
+
+int elsa_attn_fwd_masked(const void *q, const void *k, const void *v, void *out,
+                         int B, int H, int n, int d, float scale, int causal,
+                         const int32_t *kv_len, int dtype, void *stream) {
+    return attn_fwd_impl(q, k, v, out, nullptr, B, H, n, d, scale, causal, kv_len, dtype, stream);
+}
+
+int elsa_attn_fwd_lse(const void *q, const void *k, const void *v, void *out, float *lse,
+                      int B, int H, int n, int d, float scale, int causal,
+                      const int32_t *kv_len, int dtype, void *stream) {
+    if (!lse) return ELSA_ERR_INVALID_ARG;
+    return attn_fwd_impl(q, k, v, out, lse, B, H, n, d, scale, causal, kv_len, dtype, stream);
 }
 
 int elsa_attn_fwd(const void *q, const void *k, const void *v, void *out,
@@ -184,7 +198,7 @@ int elsa_combine(const float *part_m, const float *part_S, const float *part_W, 
     int rc = check_common(B, H, n, d, dtype);
     if (rc != ELSA_OK) return rc;
     if (num_splits < 1 || num_splits > n || num_splits > kMaxSplits) return ELSA_ERR_INVALID_ARG;
-    elsa::CombineParams cp{part_m, part_S, part_W, out, (long long)B * H * n, n, num_splits, 1, dtype == ELSA_F16};
+    elsa::CombineParams cp{part_m, part_S, part_W, out, nullptr, (long long)B * H * n, n, num_splits, 1, dtype == ELSA_F16};
     return elsa::launch_combine(cp, d, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
 }
 

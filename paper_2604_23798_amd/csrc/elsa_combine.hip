@@ -35,6 +35,7 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
     }
     const float f = S > 0.f ? 1.f / S : 0.f;
     acc *= f;
+    if (p.lse && c4 == 0) p.lse[row] = lse_of(msafe * unit, S);
     if (p.f16_out) Io<_Float16>::store4(p.out, row * D + 4 * c4, acc);
     else Io<float>::store4(p.out, row * D + 4 * c4, acc);
 }

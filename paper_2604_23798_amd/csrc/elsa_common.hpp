@@ -22,6 +22,7 @@ constexpr int kNumXcd = 8;  // MI355X: 8 accelerator dies, blocks are dealt to t
 struct FwdParams {
     const void *q, *k, *v;
     void *out;                       // [B][H][n][d], used when num_splits == 1 && !emit_partials
+    float *lse;                      // optional [B][H][n]: ln sum_j e^{s_ij} (dense layout, single pass)
     float *part_m, *part_S, *part_W; // [BH][C][n], [BH][C][n], [BH][C][n][d]
     const int32_t *kv_len;           // device [B] or nullptr
     int B, H, n;
@@ -43,6 +44,7 @@ struct FwdParams {
 struct CombineParams {
     const float *part_m, *part_S, *part_W;
     void *out;
+    float *lse;                      // optional [rows]: ln of the merged normaliser
     long long rows;                  // B*H*n
     int n, num_splits;
     int m_natural;
@@ -50,6 +52,10 @@ struct CombineParams {
 };
 
 __device__ __forceinline__ float exp2_fast(float x) { return __builtin_amdgcn_exp2f(x); }
+// ln sum_j e^{s_j} from a state with the maximum in log2 units: (m + log2 S) ln 2; -inf for the identity
+__device__ __forceinline__ float lse_of(float m_log2, float S) {
+    return S > 0.f ? (m_log2 + __builtin_amdgcn_logf(S)) * kLn2 : -INFINITY;
+}
 
 // The two half-waves (lanes l and l ^ 32) trade one register with v_permlane32_swap:
 // afterwards r[0] holds the lower half's value and r[1] the upper half's value in

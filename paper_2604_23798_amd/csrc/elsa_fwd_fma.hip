@@ -139,6 +139,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
             Io<float>::store4(p.part_W, prow * D + 4 * c4, f32x4{W[4 * c4], W[4 * c4 + 1], W[4 * c4 + 2], W[4 * c4 + 3]});
     } else {
         const float f = S > 0.f ? 1.f / S : 0.f;
+        if (p.lse) p.lse[bh * (long long)n + row] = lse_of(m, S);
 #pragma unroll
         for (int c4 = 0; c4 < D / 4; ++c4)
             Io<T>::store4(p.out, head_off + (long long)row * ts + 4 * c4,

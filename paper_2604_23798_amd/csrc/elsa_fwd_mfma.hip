@@ -373,6 +373,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
         } else {
             f = stot[nq] > 0.f ? 1.f / stot[nq] : 0.f;
             obase = head_off + (long long)row * ts;
+            if (p.lse && h == 0) p.lse[bh * (long long)n + row] = lse_of(mrun[nq], stot[nq]);
         }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {

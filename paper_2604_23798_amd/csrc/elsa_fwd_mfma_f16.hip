@@ -307,6 +307,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
         } else {
             f = stot[nq] > 0.f ? 1.f / stot[nq] : 0.f;
             obase = head_off + (long long)row * ts;
+            if (p.lse && h == 0) p.lse[bh * (long long)n + row] = lse_of(mrun[nq], stot[nq]);
         }
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)

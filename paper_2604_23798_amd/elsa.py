@@ -17,7 +17,7 @@ F32, F16 = 0, 1
 OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP = 0, 1, 2, 3
 PATH_AUTO, PATH_FMA, PATH_MFMA, PATH_MFMA16 = 0, 1, 2, 3
 
-EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
+EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_lse", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
            "elsa_split_kv_workspace_bytes", "elsa_set_workspace", "elsa_set_option", "elsa_get_option",
            "elsa_variant_name", "elsa_last_kernel", "elsa_status_string", "elsa_debug_layout_probe")
 
@@ -29,6 +29,7 @@ _lib = ctypes.CDLL(LIB_PATH)
 _vp, _i, _f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
 _lib.elsa_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _i, _vp]
 _lib.elsa_attn_fwd_masked.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
+_lib.elsa_attn_fwd_lse.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
 _lib.elsa_attn_fwd_varlen.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _i, _vp]
 _lib.elsa_attn_fwd_split_kv.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _i, _vp]
 _lib.elsa_combine.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]
@@ -103,6 +104,16 @@ def elsa_attn_fwd_masked(q, k, v, out, scale, causal=False, kv_len=None, stream=
     _check(_lib.elsa_attn_fwd_masked(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, n, d, float(scale),
                                      int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
     return out
+
+
+def elsa_attn_fwd_lse(q, k, v, out, lse, scale, causal=False, kv_len=None, stream=None):
+    import torch
+    B, H, n, d = _shape(q, k, v)
+    assert out.is_contiguous() and out.shape == q.shape and out.dtype == q.dtype
+    assert lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, H, n)
+    _check(_lib.elsa_attn_fwd_lse(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, n, d, float(scale),
+                                  int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
+    return out, lse
 
 
 def elsa_attn_fwd_varlen(q, k, v, out, cu_seqlens, max_seqlen, scale, causal=False, stream=None):

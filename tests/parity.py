@@ -48,3 +48,30 @@ def assert_parity(out, ref, tol, what=""):
     print(msg)
     assert m["e_row"] <= tol and m["e_mix"] <= tol, msg
     return m
+
+
+def drift_metrics(P_hat, P_ref, Y_hat, Y_ref):
+    """The six drift metrics of the paper's numerical-equivalence section, per query row
+    (P: [R, n] attention probabilities, Y: [R, d] outputs), each summarised as
+    (median, 95th, 99th percentile) over rows: max |dP|, ||dP||_2/||P||_2, Jensen-Shannon
+    divergence, argmax disagreement (rate), max |dY|, ||dY||_2/||Y||_2."""
+    P_hat, P_ref = np.asarray(P_hat, np.float64), np.asarray(P_ref, np.float64)
+    Y_hat, Y_ref = np.asarray(Y_hat, np.float64), np.asarray(Y_ref, np.float64)
+    dP, dY = P_hat - P_ref, Y_hat - Y_ref
+
+    def kl(a, b):
+        with np.errstate(divide="ignore", invalid="ignore"):
+            t = np.where(a > 0, a * (np.log(a) - np.log(b)), 0.0)
+        return t.sum(axis=1)
+    M = 0.5 * (P_hat + P_ref)
+    js = 0.5 * kl(P_hat, M) + 0.5 * kl(P_ref, M)
+    rows = {
+        "dP_inf": np.abs(dP).max(axis=1),
+        "dP_l2_rel": np.linalg.norm(dP, axis=1) / np.linalg.norm(P_ref, axis=1),
+        "js": np.maximum(js, 0.0),
+        "dY_inf": np.abs(dY).max(axis=1),
+        "dY_l2_rel": np.linalg.norm(dY, axis=1) / np.linalg.norm(Y_ref, axis=1),
+    }
+    out = {k: tuple(float(np.percentile(v, p)) for p in (50, 95, 99)) for k, v in rows.items()}
+    out["arg_rate"] = float(np.mean(P_hat.argmax(axis=1) != P_ref.argmax(axis=1)))
+    return out

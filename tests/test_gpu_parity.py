@@ -305,6 +305,48 @@ def test_varlen_fp16_and_paper_recipe(d):
         assert_parity(out, ref, tolerance(1792, fp16), "varlen recipe d=%d fp16=%d" % (d, fp16))
 
 
+@pytest.mark.parametrize("path,variant,splits", [(MFMA, 1, 0), (MFMA, 3, 0), (FMA, 1, 0), (MFMA, 1, 3), (MFMA16, 1, 0)])
+def test_log_normaliser_and_drift_metrics(path, variant, splits):
+    """elsa_attn_fwd_lse: the row log-normaliser, and through it the paper's six drift metrics
+    (probabilities P_ij = e^{s_ij - lse_i}) on a short, a long-ish and a wide-score problem."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    from tests.parity import drift_metrics
+    fp16 = path == MFMA16
+    for (n, sigma, causal) in ((197, 1.0, False), (1500, 1.0, True), (700, 8.0, False)):
+        B, H, d = 1, 2, 64
+        q, k, v = _rand(B, H, n, d, 300 + n, sigma=sigma, fp16=fp16)
+        qf, kf, vf = _f32(q, k, v)
+        tq, tk, tv = G.to_dev(q), G.to_dev(k), G.to_dev(v)
+        out = torch.full_like(tq, float("nan"))
+        lse = torch.full((B, H, n), float("nan"), device="cuda")
+        ws = torch.empty(elsa.elsa_split_kv_workspace_bytes(B, H, n, d, max(splits, 1)), dtype=torch.uint8, device="cuda")
+        if splits:
+            elsa.elsa_set_workspace(ws)
+        try:
+            with G.Options(path=path, variant=variant, splits=splits):
+                elsa.elsa_attn_fwd_lse(tq, tk, tv, out, lse, 0.125, causal)
+            torch.cuda.synchronize()
+        finally:
+            elsa.elsa_set_workspace(None)
+        ref_lse = oracle.lse_rows(qf, kf, 0.125, causal=causal)
+        got_lse = lse.reshape(-1).double().cpu().numpy()
+        # |s| reaches ~300 on the wide problem: an FP32 score carries ~1e-4 of rounding there
+        assert np.all(np.abs(got_lse - ref_lse) <= (2e-3 if fp16 else 2e-5 * max(1.0, sigma ** 2))), \
+            float(np.abs(got_lse - ref_lse).max())
+        ref_y = oracle.attn_rows(qf, kf, vf, 0.125, causal=causal)
+        got_y = out.reshape(-1, d).double().cpu().numpy()
+        s = 0.125 * np.einsum("bhid,bhjd->bhij", qf.astype(np.float64), kf.astype(np.float64)).reshape(-1, n)
+        if causal:
+            s = np.where(np.tile(np.tril(np.ones((n, n), bool)), (B * H, 1)), s, -np.inf)
+        m = drift_metrics(np.exp(s - got_lse[:, None]), np.exp(s - ref_lse[:, None]), got_y, ref_y)
+        print("drift path%d n=%d sigma=%g:" % (path, n, sigma), m)
+        tol = tolerance(n, fp16) if sigma == 1.0 else (2e-3 if fp16 else 1e-4)
+        assert m["arg_rate"] == 0.0
+        assert m["dP_inf"][2] <= 10 * tol and m["dP_l2_rel"][2] <= 10 * tol and m["js"][2] <= tol
+        assert m["dY_l2_rel"][2] <= tol
+
+
 def test_deterministic_and_option_reporting():
     from paper_2604_23798_amd import elsa
     q, k, v = _rand(1, 4, 777, 64, 81)

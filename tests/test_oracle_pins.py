@@ -208,3 +208,21 @@ def test_varlen_reduces_to_dense_problems():
     _close(out[4], v2[4])                                    # the one-token sequence returns its value
     _close(out[5:], oracle.attn_varlen(q2[5:], k2[5:], v2[5:], [0, 9], 0.5))
     _close(out[:4], oracle.attn_varlen(q2[:4], k2[:4], v2[:4], [0, 4], 0.5))
+
+
+def test_lse_closed_forms_and_library():
+    q, k, v = _rand(2, 2, 40, 8, 71)
+    lse = oracle.lse_rows(q, k, 0.3).reshape(2, 2, 40)
+    s = torch.from_numpy(q).double() @ torch.from_numpy(k).double().transpose(-1, -2) * 0.3
+    _close(lse, torch.logsumexp(s, dim=-1).numpy(), 1e-12)
+    m = torch.ones(40, 40).triu(1).bool()
+    _close(oracle.lse_rows(q, k, 0.3, causal=True).reshape(2, 2, 40),
+           torch.logsumexp(s.masked_fill(m, float("-inf")), dim=-1).numpy(), 1e-12)
+    q0 = np.zeros_like(q)
+    _close(oracle.lse_rows(q0, k, 0.3), np.full(2 * 2 * 40, math.log(40.0)))      # uniform scores: ln n
+    _close(oracle.lse_rows(q, k, 0.3, causal=True).reshape(2, 2, 40)[..., 0],
+           0.3 * np.einsum("bhd,bhd->bh", q[:, :, 0].astype(np.float64), k[:, :, 0].astype(np.float64)))  # n = 1: s itself
+    assert np.all(np.isneginf(oracle.lse_rows(q, k, 0.3, kv_len=np.array([0, 40], np.int32)).reshape(2, 80)[0]))
+    # consistency with the state form: lse = m_c + ln S_c for a single chunk
+    pm, pS, _ = oracle.partials_rows(q, k, v, 0.3, 1)
+    _close(oracle.lse_rows(q, k, 0.3), pm[:, 0] + np.log(pS[:, 0]), 1e-12)
