@@ -7,7 +7,10 @@
  *     never allocates, frees or retains them (except the workspace registered
  *     with elsa_set_workspace, which it borrows until replaced).
  *   - Q, K, V, out are contiguous row-major [B][H][n][d] with d_v == d,
- *     self-attention (n queries, n keys).  d must be 64 or 128.
+ *     self-attention (n queries, n keys).  d must be 64 or 128.  The K (and V) slice of
+ *     one (batch, head) -- one sequence of a packed batch -- must span less than 2 GiB
+ *     (n*d*sizeof(element), or total_tokens*H*d*sizeof(element) for the packed layout);
+ *     larger problems return ELSA_ERR_UNSUPPORTED on the matrix-core paths.
  *   - dtype: ELSA_F32 = FP32 in/out; ELSA_F16 = IEEE FP16 in/out.  Scores, the
  *     running maximum m, the normaliser S and the weighted sum W are always FP32;
  *     on the default FP16 path the exponentials are rounded to FP16 (nearest even)

@@ -36,9 +36,11 @@ int variant_tq(int path, int variant, int d) {
          : path == 3 ? elsa::mfma16_variant_tq(variant, d) : elsa::mfma_variant_tq(variant, d);
 }
 
-// Tile configuration when the caller did not force one.  Measured on MI355X: the 256-row tile
-// (two query groups per wave) wins once it still yields two blocks per CU; below that the
-// 128-row tile; when even that leaves CUs idle, the configuration whose waves split the keys.
+// Tile configuration when the caller did not force one (FP32 MFMA ids in brackets).  Measured on
+// MI355X: the 128-row tile with 32-key LDS tiles [7] keeps three waves per SIMD resident and is
+// within 2 % of the fastest configuration at every size while using two score chains; d = 128
+// uses the 128-row tile [1]; when fewer than 192 such blocks exist, the configuration whose waves
+// split the key range [3].  The 256-row tiles [2, 4] are opt-in.
 int pick_variant(int path, long long BH, int n, int d, int splits) {
     if (g.opt[ELSA_OPT_VARIANT] >= 1 && g.opt[ELSA_OPT_VARIANT] <= variant_count(path)) return g.opt[ELSA_OPT_VARIANT];
     if (path == 1) {
@@ -48,8 +50,8 @@ int pick_variant(int path, long long BH, int n, int d, int splits) {
     const long long b256 = BH * ((n + 255) / 256) * splits;
     const long long b128 = BH * ((n + 127) / 128) * splits;
     if (path == 3) return (d == 64 && b256 >= 2 * kNumCu) ? 2 : (b128 >= (3 * kNumCu) / 4 ? 1 : 3);
-    if (d == 64 && b256 >= 2 * kNumCu) return 2;
-    return b128 >= (3 * kNumCu) / 4 ? 1 : 3;
+    if (b128 < (3 * kNumCu) / 4) return 3;
+    return d == 64 ? 7 : 1;
 }
 
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
@@ -60,6 +62,10 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     int path = g.opt[ELSA_OPT_PATH];
     if (path == 0) path = (dtype == ELSA_F16 && scale != 0.f) ? 3 : 2;
     if (path == 3 && (dtype != ELSA_F16 || scale == 0.f)) return ELSA_ERR_UNSUPPORTED;
+    // the K/V slice of one (sequence, head) is addressed through a 31-bit buffer range
+    const long long tok_stride = cu_seqlens ? (long long)H * d : d;
+    const long long longest = cu_seqlens ? total_tokens : n;
+    if (path != 1 && longest * tok_stride * (dtype == ELSA_F16 ? 2 : 4) >= 0x7fffffffLL) return ELSA_ERR_UNSUPPORTED;
     const int variant = pick_variant(path, (long long)B * H, n, d, num_splits);
     const int tq = variant_tq(path, variant, d);
     if (tq <= 0) return ELSA_ERR_UNSUPPORTED;
@@ -208,7 +214,7 @@ int elsa_set_option(int option, int value) {
     if (option == ELSA_OPT_PATH && value > 3) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_XCD_MAP && value > 2) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_SPLITS && value > kMaxSplits) return ELSA_ERR_INVALID_ARG;
-    if (option == ELSA_OPT_VARIANT && value > 16) return ELSA_ERR_INVALID_ARG;
+    if (option == ELSA_OPT_VARIANT && value > 32) return ELSA_ERR_INVALID_ARG;
     g.opt[option] = value;
     return ELSA_OK;
 }

@@ -139,6 +139,15 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
     return r;
 }
 
+// Raw buffer descriptors: loads past num_records bytes return zero, so a K/V tile that sticks out
+// of its chunk needs neither address arithmetic nor lane masking.
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *base, long long bytes) {
+    const int nrec = bytes > 0 ? (int)(bytes < 0x7fffffffLL ? bytes : 0x7fffffffLL) : 0;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(base), 0, nrec, 0x00020000);
+}
+
 template <typename T> struct Io;
 template <> struct Io<float> {
     static __device__ __forceinline__ f32x4 load4(const void *base, long long elem) {
@@ -146,6 +155,9 @@ template <> struct Io<float> {
     }
     static __device__ __forceinline__ void store4(void *base, long long elem, f32x4 x) {
         *reinterpret_cast<f32x4 *>(static_cast<float *>(base) + elem) = x;
+    }
+    static __device__ __forceinline__ f32x4 bload4(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+        return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
     }
 };
 template <> struct Io<_Float16> {
@@ -156,6 +168,10 @@ template <> struct Io<_Float16> {
     static __device__ __forceinline__ void store4(void *base, long long elem, f32x4 x) {
         f16x4 h = {(_Float16)x[0], (_Float16)x[1], (_Float16)x[2], (_Float16)x[3]};
         *reinterpret_cast<f16x4 *>(static_cast<_Float16 *>(base) + elem) = h;
+    }
+    static __device__ __forceinline__ f32x4 bload4(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+        const f16x4 h = __builtin_bit_cast(f16x4, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0));
+        return f32x4{(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
     }
 };
 

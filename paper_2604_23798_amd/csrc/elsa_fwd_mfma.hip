@@ -24,7 +24,7 @@ __device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
-template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int SCHED>
+template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int BUFL>
 __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p) {
     constexpr int NT = 64 * WQ * WK;
     constexpr int TQ = 32 * NQ * WQ;
@@ -83,11 +83,6 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 
     float mrun[NQ], srun[NQ];
     f32x16 oacc[NQ][MB];
-    f32x16 negm[(SCHED & 4) ? NQ : 1];      // FOLD only: -anchor in every register (0 while no key was seen)
-#pragma unroll
-    for (int nq = 0; nq < ((SCHED & 4) ? NQ : 1); ++nq)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) negm[nq][i] = 0.f;
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
         mrun[nq] = -INFINITY;
@@ -99,8 +94,30 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     }
 
     f32x4 kst[LPT], vst[LPT];
+    // BUF: tiles are fetched through buffer descriptors whose byte range ends with the last
+    // visible row of the chunk: rows beyond it read as zero, the per-thread offsets are constants
+    // and the tile's position is one scalar offset -- no vector address arithmetic per tile.
+    constexpr bool BUF = BUFL != 0;
+    const long long slice_bytes = kend > 0 ? ((long long)(kend - 1) * ts + D) * (long long)sizeof(T) : 0;
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(static_cast<const T *>(p.k) + head_off, BUF ? slice_bytes : 0);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(static_cast<const T *>(p.v) + head_off, BUF ? slice_bytes : 0);
+    int voff[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int e = tid + i * NT;
+        voff[i] = (int)(((long long)(e / QPR) * ts + 4 * (e % QPR)) * (long long)sizeof(T));
+    }
     auto gload = [&](int t) {
         const int kb0 = kbeg + t * TKB;
+        if constexpr (BUF) {
+            const int soff = (int)((long long)kb0 * ts * (long long)sizeof(T));
+#pragma unroll
+            for (int i = 0; i < LPT; ++i) {
+                kst[i] = Io<T>::bload4(krs, voff[i], soff);
+                vst[i] = Io<T>::bload4(vrs, voff[i], soff);
+            }
+            return;
+        }
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
             const int e = tid + i * NT;
@@ -157,10 +174,6 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                     for (int a = 0; a < NACC; ++a)
 #pragma unroll
                         for (int i = 0; i < 16; ++i) part[nq][a][i] = 0.f;
-                // FOLD: chain 0 starts from -anchor (held splat in 16 registers, as the C operand of
-                // the first MFMA), so the accumulator comes out as s - m and no subtraction follows
-                constexpr bool FOLD = (SCHED & 4) != 0;
-                if constexpr (SCHED & 1) __builtin_amdgcn_s_setprio(1);
                 // K fragments are fetched one column group ahead of the MFMAs that consume them
                 const float *krow = &Kb[(kl + j) * KROW + 4 * h];
                 f32x4 kf = *reinterpret_cast<const f32x4 *>(krow);
@@ -173,12 +186,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                     for (int tt = 0; tt < 4; ++tt)
 #pragma unroll
                         for (int nq = 0; nq < NQ; ++nq)
-                        {
-                            if (FOLD && cc == 0 && tt == 0)
-                                part[nq][0] = mfma32(kf[tt], qf[nq][4 * cc + tt], negm[nq]);
-                            else
-                                part[nq][cc / CPA] = mfma32(kf[tt], qf[nq][4 * cc + tt], part[nq][cc / CPA]);
-                        }
+                            part[nq][cc / CPA] = mfma32(kf[tt], qf[nq][4 * cc + tt], part[nq][cc / CPA]);
                     kf = kn;
                 }
                 // pin the order: two fragment reads in flight ahead of every group of MFMAs
@@ -189,7 +197,6 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                 }
                 __builtin_amdgcn_sched_group_barrier(0x008, 8 * NQ, 0);
-                if constexpr (SCHED & 1) __builtin_amdgcn_s_setprio(0);
 #pragma unroll
                 for (int nq = 0; nq < NQ; ++nq) {
                     if constexpr (NACC == 1) sacc[nq] = part[nq][0];
@@ -220,62 +227,31 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 #pragma unroll
                 for (int i = 1; i < 16; ++i) mt = fmaxf(mt, sacc[nq][i]);
                 mt = half_max(mt);                       // the other 16 keys of this query
-                if constexpr ((SCHED & 4) != 0) {
-                    // scores arrive relative to the anchor (0 while the row has seen no key)
-                    const bool seen = mrun[nq] > -INFINITY;
-                    const bool grow = seen ? (mt > 0.f) : (mt > -INFINITY);
-                    if (__builtin_amdgcn_ballot_w64(grow) != 0) {
-                        const float delta = grow ? mt : 0.f;
-                        const float alpha = seen ? exp2_fast(-delta) : 0.f;
-                        srun[nq] *= alpha;
+                const float mnew = fmaxf(mrun[nq], mt);
+                const float msafe = (mnew == -INFINITY) ? 0.f : mnew;   // identity (+) identity = identity
+                // the running state is rescaled only when some row of the wave moved its maximum
+                if (__builtin_amdgcn_ballot_w64(mnew > mrun[nq]) != 0) {
+                    const float alpha = exp2_fast(mrun[nq] - msafe);
+                    srun[nq] *= alpha;
 #pragma unroll
-                        for (int mb = 0; mb < MB; ++mb)
+                    for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
-                            for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
-                        if (grow) mrun[nq] = (seen ? mrun[nq] : 0.f) + delta;
-                        const float na = (mrun[nq] > -INFINITY) ? -mrun[nq] : 0.f;
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) {
-                            sacc[nq][i] -= delta;
-                            negm[nq][i] = na;
-                        }
-                    }
-                    float ps = 0.f;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float e = exp2_fast(sacc[nq][i]);
-                        sacc[nq][i] = e;
-                        ps += e;
-                    }
-                    srun[nq] += ps;
-                } else {
-                    const float mnew = fmaxf(mrun[nq], mt);
-                    const float msafe = (mnew == -INFINITY) ? 0.f : mnew;   // identity (+) identity = identity
-                    // the running state is rescaled only when some row of the wave moved its maximum
-                    if (__builtin_amdgcn_ballot_w64(mnew > mrun[nq]) != 0) {
-                        const float alpha = exp2_fast(mrun[nq] - msafe);
-                        srun[nq] *= alpha;
-#pragma unroll
-                        for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-                            for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
-                        mrun[nq] = mnew;
-                    }
-                    float ps = 0.f;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        const float e = exp2_fast(sacc[nq][i] - msafe);
-                        sacc[nq][i] = e;
-                        ps += e;
-                    }
-                    srun[nq] += ps;
+                        for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
+                    mrun[nq] = mnew;
                 }
+                float ps = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float e = exp2_fast(sacc[nq][i] - msafe);
+                    sacc[nq][i] = e;
+                    ps += e;
+                }
+                srun[nq] += ps;
             }
 
             // ---- (a4) W^T += V^T P^T.  Step i contracts keys 8g+t (lower half-wave) and
             // 8g+4+t (upper), which is where accumulator register i = 4g+t holds them.
             // Row r of block mb of W^T is value column MB*r + mb.
-            if constexpr (SCHED & 2) __builtin_amdgcn_s_setprio(1);
             {
                 typedef float vfrag __attribute__((ext_vector_type(MB)));
                 const float *vcol = &Vb[(kl + 4 * h) * VROW + MB * j];
@@ -299,7 +275,6 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                 }
                 __builtin_amdgcn_sched_group_barrier(0x008, 2 * MB * NQ, 0);
             }
-            if constexpr (SCHED & 2) __builtin_amdgcn_s_setprio(0);
         }
         if (t + 1 < ntiles) lstore(buf ^ 1);
         __syncthreads();
@@ -401,18 +376,20 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 }
 
 // ---- variants -------------------------------------------------------------------------------
-// id: 1 q128: 4 query waves, 2 score chains      2 q256: 4 query waves x 2 query groups
-//     3 xwave: the waves split the key range      4 q256w8: 8 query waves (4 per SIMD), 1 chain
-//     5 q128 with 1 score chain                   6 q128 with 4 score chains
-//     7 q128, anchor folded into the score MFMA   8 same with 1 score chain
+// id: 1 q128: 4 query waves, 64-key tiles            2 q256: 4 query waves x 2 query groups
+//     3 xwave: the waves split the key range          4 q256w8: 8 query waves (4 per SIMD in 128 regs)
+//     5 q128 with 1 score chain                       6 q128 with 4 score chains
+//     7 q128k32: 32-key tiles, 3 waves per SIMD       8 q128 with plain global loads (no descriptors)
+// All but 8 fetch tiles through buffer descriptors; all but 5/6 (and 4 at d = 64) use 2 score chains.
 
-static const char *kNames[kMfmaVariants] = {"mfma_q128_w4",   "mfma_q256_w4",   "mfma_xwave",     "mfma_q256_w8",
-                                            "mfma_q128_acc1", "mfma_q128_acc4", "mfma_q128_fold", "mfma_q128_fold1"};
+static const char *kNames[kMfmaVariants] = {"mfma_q128_w4",   "mfma_q256_w4",   "mfma_xwave",   "mfma_q256_w8",
+                                            "mfma_q128_acc1", "mfma_q128_acc4", "mfma_q128_k32", "mfma_q128_gld"};
 
 int mfma_variant_tq(int variant, int d) {
     switch (variant) {
         case 1: case 5: case 6: case 7: case 8: return 128;
-        case 2: case 4: return 256;
+        case 2: return 256;
+        case 4: return d == 64 ? 256 : 128;
         case 3: return d == 128 ? 64 : 32;      // d = 128: two query waves x two key waves
         default: return 0;
     }
@@ -421,13 +398,13 @@ const char *mfma_variant_name(int variant) {
     return (variant >= 1 && variant <= kMfmaVariants) ? kNames[variant - 1] : nullptr;
 }
 
-template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int SCHED>
+template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int BUFL>
 static int launch_one(const FwdParams &p, hipStream_t s) {
     constexpr int TKB = KS * WK;
     constexpr size_t kv_bytes = (size_t)2 * (TKB * (D + 4) + TKB * D) * sizeof(float);
     constexpr size_t xw_bytes = WK > 1 ? (size_t)(WK / 2) * WQ * NQ * (2 + D / 2) * 64 * sizeof(float) : 0;
     constexpr size_t smem = kv_bytes > xw_bytes ? kv_bytes : xw_bytes;
-    auto kern = fwd_mfma_kernel<D, T, NQ, WQ, WK, KS, WPE, NACC, SCHED>;
+    auto kern = fwd_mfma_kernel<D, T, NQ, WQ, WK, KS, WPE, NACC, BUFL>;
     static bool attr_done = false;          // per instantiation; idempotent, so a race is harmless
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
@@ -443,25 +420,29 @@ static int launch_one(const FwdParams &p, hipStream_t s) {
     return (int)hipGetLastError();
 }
 
+constexpr int Q256W8_NACC = 1;     // two chains do not fit 128 registers without spilling
+
 template <int D, typename T>
 static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
     // tile height per LDS buffer is 64 keys for d = 64 and 32 keys for d = 128 (same bytes)
     constexpr int KS = D == 64 ? 64 : 32;
     switch (variant) {
-        case 1: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 0>(p, s);
-        case 2: return launch_one<D, T, 2, 4, 1, KS, 2, 2, 0>(p, s);
+        case 1: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1>(p, s);
+        case 2: return launch_one<D, T, 2, 4, 1, KS, 2, 2, 1>(p, s);
         case 3:
-            if constexpr (D == 64) return launch_one<D, T, 1, 1, 4, 32, 2, 2, 0>(p, s);
-            else return launch_one<D, T, 1, 2, 2, 32, 2, 2, 0>(p, s);
+            if constexpr (D == 64) return launch_one<D, T, 1, 1, 4, 32, 2, 2, 1>(p, s);
+            else return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
         case 4:
-            // d = 64: 4 waves per SIMD in 128 registers.  d = 128: one 8-wave block per CU with 64-key
-            // tiles (133 KB of LDS), so a barrier falls every second step instead of every step.
-            if constexpr (D == 64) return launch_one<D, T, 1, 8, 1, KS, 4, 1, 0>(p, s);
-            else return launch_one<D, T, 1, 8, 1, 64, 2, 2, 0>(p, s);
-        case 5: return launch_one<D, T, 1, 4, 1, KS, 2, 1, 0>(p, s);
-        case 6: return launch_one<D, T, 1, 4, 1, KS, 2, 4, 0>(p, s);
-        case 7: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 4>(p, s);
-        case 8: return launch_one<D, T, 1, 4, 1, KS, 2, 1, 4>(p, s);
+            // d = 64: 8 waves, 4 per SIMD in 128 registers.  d = 128 has no such configuration
+            // (the state alone needs more registers): same as id 5.
+            if constexpr (D == 64) return launch_one<D, T, 1, 8, 1, KS, 4, Q256W8_NACC, 1>(p, s);
+            else return launch_one<D, T, 1, 4, 1, KS, 2, 1, 1>(p, s);
+        case 5: return launch_one<D, T, 1, 4, 1, KS, 2, 1, 1>(p, s);
+        case 6: return launch_one<D, T, 1, 4, 1, KS, 2, 4, 1>(p, s);
+        case 7:
+            if constexpr (D == 64) return launch_one<D, T, 1, 4, 1, 32, 3, 2, 1>(p, s);
+            else return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1>(p, s);
+        case 8: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 0>(p, s);
         default: return (int)hipErrorInvalidValue;
     }
 }

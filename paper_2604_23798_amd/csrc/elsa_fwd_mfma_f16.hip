@@ -100,22 +100,25 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
             for (int i = 0; i < 16; ++i) oacc[nq][mb][i] = 0.f;
     }
 
+    // Tiles are fetched through buffer descriptors whose byte range ends with the last visible row
+    // of the chunk: rows beyond it read as zero, the per-thread offsets are constants and the
+    // tile's position is one scalar offset (no vector address arithmetic, no lane masks).
     f16x8 kst[LPT], vst[LPT];
+    const long long slice_bytes = kend > 0 ? ((long long)(kend - 1) * ts + D) * 2 : 0;
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(kp + head_off, slice_bytes);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vp + head_off, slice_bytes);
+    int voff[LPT];
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+        const int e = tid + i * NT;
+        voff[i] = (int)(((long long)(e / CPR) * ts + 8 * (e % CPR)) * 2);
+    }
     auto gload = [&](int t) {
-        const int kb0 = kbeg + t * TKB;
+        const int soff = (int)((long long)(kbeg + t * TKB) * ts * 2);
 #pragma unroll
         for (int i = 0; i < LPT; ++i) {
-            const int e = tid + i * NT;
-            const int row = e / CPR, c8 = e % CPR;
-            const int key = kb0 + row;
-            f16x8 kx = {0, 0, 0, 0, 0, 0, 0, 0}, vx = {0, 0, 0, 0, 0, 0, 0, 0};
-            if (key < kend) {
-                const long long off = head_off + (long long)key * ts + 8 * c8;
-                kx = *reinterpret_cast<const f16x8 *>(kp + off);
-                vx = *reinterpret_cast<const f16x8 *>(vp + off);
-            }
-            kst[i] = kx;
-            vst[i] = vx;
+            kst[i] = __builtin_bit_cast(f16x8, __builtin_amdgcn_raw_buffer_load_b128(krs, voff[i], soff, 0));
+            vst[i] = __builtin_bit_cast(f16x8, __builtin_amdgcn_raw_buffer_load_b128(vrs, voff[i], soff, 0));
         }
     };
     auto lstore = [&](int buf) {
