@@ -27,7 +27,7 @@ PEAK_FP32_VALU_UNPACKED = 78.6  # plain v_fma_f32 (packed FP32 is disabled in th
 PEAK_FP16_TFLOPS = 2500.0       # MI355X dense FP16 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for a plain copy of known size in the same run (profiles/*_counters.md).
-MEASURED_TRAFFIC = {("sweep_n16384", "mfma_q256_w4"): 6.606e8, ("sweep_n16384", "mfma_q128_w4"): 1.208e9}
+MEASURED_TRAFFIC = {("sweep_n16384", "mfma_q128_k32"): 1.156e9, ("sweep_n16384", "mfma_q256_w4"): 6.606e8}
 
 
 def cpu_baseline(w, q, k, v, kv_len, gpu_out, budget_rows):
@@ -132,6 +132,9 @@ def main():
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--xcd-map", type=int, default=0)
     ap.add_argument("--oracle-rows", type=int, default=4096, help="row budget of the cpu_baseline leg (0 = skip)")
+    ap.add_argument("--pre-warm-ms", type=float, default=0.0,
+                    help="run untimed steps for this long before the W warm-up steps (short workloads otherwise "
+                         "run before the GPU clocks have ramped up)")
     ap.add_argument("--scaling-fit", action="store_true",
                     help="instead of one workload: per-head latency for n = 2^10..2^15 (H=16, d=64) and the "
                          "least-squares fit T(n) = a*L(n,128) + b*n^2 + c of the paper's scaling study")
@@ -188,6 +191,12 @@ def main():
         def step():
             elsa.elsa_attn_fwd_masked(tq, tk, tv, out, scale, causal, tl)
 
+    if a.pre_warm_ms > 0:
+        tw = time.perf_counter()
+        while (time.perf_counter() - tw) * 1e3 < a.pre_warm_ms:
+            for _ in range(20):
+                step()
+            torch.cuda.synchronize()
     for _ in range(a.warmup):
         step()
     torch.cuda.synchronize()
