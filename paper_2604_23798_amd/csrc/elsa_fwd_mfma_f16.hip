@@ -4,12 +4,13 @@
 // v_mfma_f32_32x32x16_f16 for both contractions: Q, K, V stay FP16 (exact inputs), every
 // score, the running maximum m, the normaliser S and the weighted sum W are FP32, and the
 // exponentials are rounded to FP16 (nearest-even) only as the B operand of the PV product.
-// 16-bit MFMA operands are contiguous along the contraction index, so
-//   * K is staged row-major (contraction over d),
-//   * V is staged TRANSPOSED (V^T[dv][key], contraction over keys): the transposition is done
-//     by the 2-byte LDS writes of the staging step,
-//   * the contraction index of PV is permuted so that the 8 exponentials a lane already holds
-//     in accumulator registers 8u..8u+7 are its B operand as they are.
+// 16-bit MFMA operands are contiguous along the contraction index.  K (contraction over d) is
+// staged row-major and read with 16-byte LDS reads.  V (contraction over keys) is staged row-major
+// too and its fragments are fetched with the transposing LDS read ds_read_b64_tr_b16: in every
+// group of 16 lanes, lane 4e+a supplies the address of four consecutive value columns of key e,
+// and lane i receives column i of keys 0..3 -- exactly the V^T fragment of 16 value columns x 4
+// keys.  The contraction index of PV is permuted so that the 8 exponentials a lane already holds
+// in accumulator registers 8u..8u+7 are its B operand as they are.
 // Scores stay in raw units (q.k); scale*log2(e) enters in the exponent, 2^(s*c - m*c), through
 // one FMA per score, so no rounding of Q is added.  Requires scale != 0 (the caller falls back
 // to the FP32-MFMA kernel otherwise).
@@ -29,9 +30,9 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
     constexpr int TQ = 32 * NQ * WQ;
     constexpr int TKB = KS * WK;             // keys per LDS tile
     constexpr int KROWB = D * 2 + 16;        // bytes per K row: 16-byte reads of 32 rows hit distinct banks
-    constexpr int VROWB = TKB * 2 + 8;       // bytes per V^T row (one value column, TKB keys)
+    constexpr int VROWB = D * 2 + 32;        // bytes per V row: the 4 rows x 32 bytes of a transposing read hit distinct banks
     constexpr int KBUFB = TKB * KROWB;
-    constexpr int VBUFB = D * VROWB;
+    constexpr int VBUFB = TKB * VROWB;
     constexpr int CPR = D / 8;               // 16-byte chunks per K/V row in HBM
     constexpr int LPT = TKB * CPR / NT;      // staged chunks per thread per tensor
     constexpr int MB = D / 32;               // 32-row blocks of W^T
@@ -127,9 +128,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
             const int e = tid + i * NT;
             const int row = e / CPR, c8 = e % CPR;
             *reinterpret_cast<f16x8 *>(Ks + buf * KBUFB + row * KROWB + 16 * c8) = kst[i];
-            unsigned char *vt = Vs + buf * VBUFB + (8 * c8) * VROWB + 2 * row;   // V^T[8*c8 + e8][row]
-#pragma unroll
-            for (int e8 = 0; e8 < 8; ++e8) *reinterpret_cast<_Float16 *>(vt + e8 * VROWB) = vst[i][e8];
+            *reinterpret_cast<f16x8 *>(Vs + buf * VBUFB + row * VROWB + 16 * c8) = vst[i];
         }
     };
 
@@ -219,16 +218,23 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
             }
 
             // ---- (a4) W^T += V^T P^T.  MFMA u contracts the 16 keys held in registers 8u..8u+7 of
-            // the two half-waves: element e of lane (.,h) is key 16u + 8*(e/4) + 4h + e%4.
+            // the two half-waves: element e of lane (.,h) is key 16u + 8*(e/4) + 4h + e%4.  The lane's
+            // source address for the transposing read: key 4h + (lane%16)/4 (+16u, +8 for the upper four
+            // elements), value columns 16*((lane/16)%2) + 4*(lane%4) .. +3 (+32 per row block).
+            const unsigned char *vsrc = Vb + (kl + 4 * h + ((lane & 15) >> 2)) * VROWB +
+                                        (16 * ((lane >> 4) & 1) + 4 * (lane & 3)) * 2;
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
 #pragma unroll
                 for (int mb = 0; mb < MB; ++mb) {
-                    const unsigned char *vrow = Vb + (32 * mb + j) * VROWB + 2 * (kl + 16 * u + 4 * h);
-                    typedef _Float16 f16x4v __attribute__((ext_vector_type(4)));
-                    const f16x4v lo = *reinterpret_cast<const f16x4v *>(vrow);
-                    const f16x4v hi = *reinterpret_cast<const f16x4v *>(vrow + 16);
-                    const f16x8 vf = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    typedef short s16x4 __attribute__((ext_vector_type(4)));
+                    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+                    const unsigned char *a0 = vsrc + 16 * u * VROWB + 64 * mb;
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0));
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0 + 8 * VROWB));
+                    typedef short s16x8 __attribute__((ext_vector_type(8)));
+                    const s16x8 both = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    const f16x8 vf = __builtin_bit_cast(f16x8, both);
 #pragma unroll
                     for (int nq = 0; nq < NQ; ++nq) oacc[nq][mb] = mfma16(vf, pb[nq][u], oacc[nq][mb]);
                 }
@@ -344,7 +350,7 @@ const char *mfma16_variant_name(int variant) {
 template <int D, int NQ, int WQ, int WK, int KS, int WPE>
 static int launch_one16(const FwdParams &p, hipStream_t s) {
     constexpr int TKB = KS * WK;
-    constexpr size_t kv_bytes = (size_t)2 * (TKB * (D * 2 + 16) + D * (TKB * 2 + 8));
+    constexpr size_t kv_bytes = (size_t)2 * (TKB * (D * 2 + 16) + TKB * (D * 2 + 32));
     constexpr size_t xw_bytes = WK > 1 ? (size_t)(WK / 2) * WQ * NQ * (2 + D / 2) * 64 * sizeof(float) : 0;
     constexpr size_t smem = kv_bytes > xw_bytes ? kv_bytes : xw_bytes;
     auto kern = fwd_mfma16_kernel<D, NQ, WQ, WK, KS, WPE>;
