@@ -377,10 +377,10 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 
 // ---- variants -------------------------------------------------------------------------------
 // id: 1 q128: 4 query waves, 64-key tiles            2 q256: 4 query waves x 2 query groups
-//     3 xwave: the waves split the key range          4 q256w8: 8 query waves (4 per SIMD in 128 regs)
+//     3 xwave: the waves split the key range          4 q256w8: 8 query waves, 32-key tiles (4 per SIMD)
 //     5 q128 with 1 score chain                       6 q128 with 4 score chains
 //     7 q128k32: 32-key tiles, 3 waves per SIMD       8 q128 with plain global loads (no descriptors)
-// All but 8 fetch tiles through buffer descriptors; all but 5/6 (and 4 at d = 64) use 2 score chains.
+// All but 8 fetch tiles through buffer descriptors; all but 5/6 use 2 score chains.
 
 static const char *kNames[kMfmaVariants] = {"mfma_q128_w4",   "mfma_q256_w4",   "mfma_xwave",   "mfma_q256_w8",
                                             "mfma_q128_acc1", "mfma_q128_acc4", "mfma_q128_k32", "mfma_q128_gld"};
@@ -420,8 +420,6 @@ static int launch_one(const FwdParams &p, hipStream_t s) {
     return (int)hipGetLastError();
 }
 
-constexpr int Q256W8_NACC = 1;     // two chains do not fit 128 registers without spilling
-
 template <int D, typename T>
 static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
     // tile height per LDS buffer is 64 keys for d = 64 and 32 keys for d = 128 (same bytes)
@@ -433,9 +431,9 @@ static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
             if constexpr (D == 64) return launch_one<D, T, 1, 1, 4, 32, 2, 2, 1>(p, s);
             else return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
         case 4:
-            // d = 64: 8 waves, 4 per SIMD in 128 registers.  d = 128 has no such configuration
-            // (the state alone needs more registers): same as id 5.
-            if constexpr (D == 64) return launch_one<D, T, 1, 8, 1, KS, 4, Q256W8_NACC, 1>(p, s);
+            // d = 64: 8 waves on 32-key tiles, 4 per SIMD in 128 registers.  d = 128 has no such
+            // configuration (the state alone needs more registers): same as id 5.
+            if constexpr (D == 64) return launch_one<D, T, 1, 8, 1, 32, 4, 2, 1>(p, s);
             else return launch_one<D, T, 1, 4, 1, KS, 2, 1, 1>(p, s);
         case 5: return launch_one<D, T, 1, 4, 1, KS, 2, 1, 1>(p, s);
         case 6: return launch_one<D, T, 1, 4, 1, KS, 2, 4, 1>(p, s);
