@@ -22,7 +22,7 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 int check_common(int B, int H, int n, int d, int dtype) {
     if (B <= 0 || H <= 0 || n <= 0) return ELSA_ERR_INVALID_ARG;
     if ((long long)B * H > 0x7fffffffLL / 64) return ELSA_ERR_INVALID_ARG;
-    if (d != 64 && d != 128) return ELSA_ERR_UNSUPPORTED;
+    if (d != 32 && d != 64 && d != 128) return ELSA_ERR_UNSUPPORTED;
     if (dtype != ELSA_F32 && dtype != ELSA_F16) return ELSA_ERR_UNSUPPORTED;
     return ELSA_OK;
 }
@@ -49,9 +49,9 @@ int pick_variant(int path, long long BH, int n, int d, int splits) {
     }
     const long long b256 = BH * ((n + 255) / 256) * splits;
     const long long b128 = BH * ((n + 127) / 128) * splits;
-    if (path == 3) return (d == 64 && b256 >= 2 * kNumCu) ? 2 : (b128 >= (3 * kNumCu) / 4 ? 1 : 3);
+    if (path == 3) return (d <= 64 && b256 >= 2 * kNumCu) ? 2 : (b128 >= (3 * kNumCu) / 4 ? 1 : 3);
     if (b128 < (3 * kNumCu) / 4) return 3;
-    return d == 64 ? 7 : 1;
+    return d <= 64 ? 7 : 1;
 }
 
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
@@ -134,7 +134,7 @@ int auto_splits(int B, int H, int n, int d) {
 extern "C" {
 
 size_t elsa_split_kv_workspace_bytes(int B, int H, int n, int d, int num_splits) {
-    if (B <= 0 || H <= 0 || n <= 0 || (d != 64 && d != 128) || num_splits < 1) return 0;
+    if (B <= 0 || H <= 0 || n <= 0 || (d != 32 && d != 64 && d != 128) || num_splits < 1) return 0;
     const size_t rows = (size_t)B * H * num_splits * n;
     return 2 * align256(rows * 4) + align256(rows * d * 4);
 }

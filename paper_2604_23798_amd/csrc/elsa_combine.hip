@@ -44,7 +44,8 @@ int launch_combine(const CombineParams &p, int d, hipStream_t s) {
     const long long threads = p.rows * (d / 4);
     const long long blocks = (threads + 255) / 256;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
-    if (d == 64) hipLaunchKernelGGL(combine_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    if (d == 32) hipLaunchKernelGGL(combine_kernel<32>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    else if (d == 64) hipLaunchKernelGGL(combine_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, s, p);
     else hipLaunchKernelGGL(combine_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, s, p);
     return (int)hipGetLastError();
 }

@@ -176,14 +176,15 @@ template <int D, typename T>
 static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
     switch (variant) {
         // d = 128 keeps 256 state registers per lane: one wave per SIMD
-        case 1: return launch_one<D, T, 4, 1, (D == 64 ? 2 : 1)>(p, s);
-        case 2: return launch_one<D, T, 1, 4, (D == 64 ? 2 : 1)>(p, s);
+        case 1: return launch_one<D, T, 4, 1, (D <= 64 ? 2 : 1)>(p, s);
+        case 2: return launch_one<D, T, 1, 4, (D <= 64 ? 2 : 1)>(p, s);
         default: return (int)hipErrorInvalidValue;
     }
 }
 
 int launch_fwd_fma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name) {
     if (name) *name = fma_variant_name(variant);
+    if (d == 32) return f16 ? launch_variant<32, _Float16>(p, variant, s) : launch_variant<32, float>(p, variant, s);
     if (d == 64) return f16 ? launch_variant<64, _Float16>(p, variant, s) : launch_variant<64, float>(p, variant, s);
     if (d == 128) return f16 ? launch_variant<128, _Float16>(p, variant, s) : launch_variant<128, float>(p, variant, s);
     return (int)hipErrorInvalidValue;

@@ -352,7 +352,13 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
         }
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
-            if constexpr (MB == 2) {
+            if constexpr (MB == 1) {
+                const f32x4 x = {oacc[nq][0][4 * g] * f, oacc[nq][0][4 * g + 1] * f, oacc[nq][0][4 * g + 2] * f,
+                                 oacc[nq][0][4 * g + 3] * f};
+                const int dv = 8 * g + 4 * h;
+                if (partial) Io<float>::store4(p.part_W, obase + dv, x);
+                else Io<T>::store4(p.out, obase + dv, x);
+            } else if constexpr (MB == 2) {
 #pragma unroll
                 for (int t2 = 0; t2 < 4; t2 += 2) {
                     const f32x4 x = {oacc[nq][0][4 * g + t2] * f, oacc[nq][1][4 * g + t2] * f,
@@ -388,8 +394,8 @@ static const char *kNames[kMfmaVariants] = {"mfma_q128_w4",   "mfma_q256_w4",   
 int mfma_variant_tq(int variant, int d) {
     switch (variant) {
         case 1: case 5: case 6: case 7: case 8: return 128;
-        case 2: return 256;
-        case 4: return d == 64 ? 256 : 128;
+        case 2: return d == 128 ? 128 : 256;
+        case 4: return d == 128 ? 128 : 256;
         case 3: return d == 128 ? 64 : 32;      // d = 128: two query waves x two key waves
         default: return 0;
     }
@@ -422,24 +428,27 @@ static int launch_one(const FwdParams &p, hipStream_t s) {
 
 template <int D, typename T>
 static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
-    // tile height per LDS buffer is 64 keys for d = 64 and 32 keys for d = 128 (same bytes)
-    constexpr int KS = D == 64 ? 64 : 32;
+    // keys per LDS buffer: 64 for d <= 64, 32 for d = 128 (same bytes)
+    constexpr int KS = D == 128 ? 32 : 64;
     switch (variant) {
         case 1: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1>(p, s);
-        case 2: return launch_one<D, T, 2, 4, 1, KS, 2, 2, 1>(p, s);
+        case 2:
+            if constexpr (D == 128) return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1>(p, s);   // no room for two query groups
+            else return launch_one<D, T, 2, 4, 1, KS, 2, 2, 1>(p, s);
         case 3:
-            if constexpr (D == 64) return launch_one<D, T, 1, 1, 4, 32, 2, 2, 1>(p, s);
-            else return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
+            if constexpr (D == 128) return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
+            else return launch_one<D, T, 1, 1, 4, 32, 2, 2, 1>(p, s);
         case 4:
             // d = 64: 8 waves on 32-key tiles, 4 per SIMD in 128 registers.  d = 128 has no such
             // configuration (the state alone needs more registers): same as id 5.
             if constexpr (D == 64) return launch_one<D, T, 1, 8, 1, 32, 4, 2, 1>(p, s);
+            else if constexpr (D == 32) return launch_one<D, T, 1, 8, 1, 64, 4, 2, 1>(p, s);
             else return launch_one<D, T, 1, 4, 1, KS, 2, 1, 1>(p, s);
         case 5: return launch_one<D, T, 1, 4, 1, KS, 2, 1, 1>(p, s);
         case 6: return launch_one<D, T, 1, 4, 1, KS, 2, 4, 1>(p, s);
         case 7:
-            if constexpr (D == 64) return launch_one<D, T, 1, 4, 1, 32, 3, 2, 1>(p, s);
-            else return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1>(p, s);
+            if constexpr (D == 128) return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1>(p, s);
+            else return launch_one<D, T, 1, 4, 1, 32, 3, 2, 1>(p, s);
         case 8: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 0>(p, s);
         default: return (int)hipErrorInvalidValue;
     }
@@ -447,6 +456,7 @@ static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
 
 int launch_fwd_mfma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name) {
     if (name) *name = mfma_variant_name(variant);
+    if (d == 32) return f16 ? launch_variant<32, _Float16>(p, variant, s) : launch_variant<32, float>(p, variant, s);
     if (d == 64) return f16 ? launch_variant<64, _Float16>(p, variant, s) : launch_variant<64, float>(p, variant, s);
     if (d == 128) return f16 ? launch_variant<128, _Float16>(p, variant, s) : launch_variant<128, float>(p, variant, s);
     return (int)hipErrorInvalidValue;

@@ -338,7 +338,7 @@ static const char *kNames16[kMfma16Variants] = {"mfma16_q128_w4", "mfma16_q256_w
 int mfma16_variant_tq(int variant, int d) {
     switch (variant) {
         case 1: return 128;
-        case 2: return 256;
+        case 2: return d == 128 ? 128 : 256;
         case 3: return d == 128 ? 64 : 32;
         default: return 0;
     }
@@ -373,16 +373,19 @@ template <int D>
 static int launch_variant16(const FwdParams &p, int variant, hipStream_t s) {
     switch (variant) {
         case 1: return launch_one16<D, 1, 4, 1, 64, 2>(p, s);
-        case 2: return launch_one16<D, 2, 4, 1, 64, 2>(p, s);
+        case 2:
+            if constexpr (D == 128) return launch_one16<D, 1, 4, 1, 64, 2>(p, s);   // two query groups would spill
+            else return launch_one16<D, 2, 4, 1, 64, 2>(p, s);
         case 3:
-            if constexpr (D == 64) return launch_one16<D, 1, 1, 4, 32, 2>(p, s);
-            else return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
+            if constexpr (D == 128) return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
+            else return launch_one16<D, 1, 1, 4, 32, 2>(p, s);
         default: return (int)hipErrorInvalidValue;
     }
 }
 
 int launch_fwd_mfma16(const FwdParams &p, int d, int variant, hipStream_t s, const char **name) {
     if (name) *name = mfma16_variant_name(variant);
+    if (d == 32) return launch_variant16<32>(p, variant, s);
     if (d == 64) return launch_variant16<64>(p, variant, s);
     if (d == 128) return launch_variant16<128>(p, variant, s);
     return (int)hipErrorInvalidValue;

@@ -134,6 +134,10 @@ WORKLOADS = {
                              v_dist="uniform", note="LLaMA-13B shaped causal long context"),
     "llama13b_32k_fp16": Workload("llama13b_32k_fp16", B=1, H=40, n=32768, d=128, seed=1004, causal=True,
                                   v_dist="uniform", fp16=True, note="same, FP16 I/O"),
+    "swin_w7": Workload("swin_w7", B=512, H=3, n=49, d=32, seed=1007,
+                        note="window attention: Swin-T stage 1 at 224 px, 7x7 windows, 64 windows x batch 8"),
+    "swin_w14": Workload("swin_w14", B=128, H=3, n=196, d=32, seed=1008,
+                         note="window attention with 14x14 windows (196 tokens, the largest window size the paper uses)"),
     "hires_vit_64k": Workload("hires_vit_64k", B=1, H=16, n=65536, d=64, seed=1005, qk_sigma=8.0,
                               note="1024x1024 image, 4x4 patches; wide score range"),
 }

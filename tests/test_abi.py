@@ -53,6 +53,7 @@ def test_workspace_bytes():
     a = lambda x: (x + 255) // 256 * 256
     assert elsa.elsa_split_kv_workspace_bytes(B, H, n, d, C) == 2 * a(rows * 4) + a(rows * d * 4)
     assert elsa.elsa_split_kv_workspace_bytes(B, H, n, 48, C) == 0
+    assert elsa.elsa_split_kv_workspace_bytes(B, H, n, 32, C) == 2 * a(rows * 4) + a(rows * 32 * 4)
     assert elsa.elsa_split_kv_workspace_bytes(B, H, 0, d, C) == 0
 
 
@@ -67,12 +68,12 @@ def test_bad_arguments_are_rejected_before_any_launch():
                                        kw.get("dtype", 0), None)
     assert f(q=None) == INV and f(out=None) == INV
     assert f(B=0) == INV and f(H=-1) == INV and f(n=0) == INV
-    assert f(d=48) == UNS and f(dtype=2) == UNS
+    assert f(d=48) == UNS and f(d=256) == UNS and f(dtype=2) == UNS
     assert f(scale=float("nan")) == INV and f(scale=float("inf")) == INV
     s = lambda C, **kw: lib.elsa_attn_fwd_split_kv(p, p, p, kw.get("pm", p), p, p, 1, 1, 8, 64, 0.125, 0, None, C, 0, None)
     assert s(0) == INV and s(9) == INV and s(2, pm=None) == INV
     c = lambda C, **kw: lib.elsa_combine(p, p, p, kw.get("out", p), 1, 1, 8, kw.get("d", 64), C, 0, None)
-    assert c(0) == INV and c(9) == INV and c(2, out=None) == INV and c(2, d=32) == UNS
+    assert c(0) == INV and c(9) == INV and c(2, out=None) == INV and c(2, d=48) == UNS
     assert lib.elsa_set_workspace(p, 0) == INV and lib.elsa_set_workspace(None, 16) == INV
     assert lib.elsa_set_workspace(ctypes.c_void_p(8), 1024) == 3
     assert lib.elsa_set_workspace(None, 0) == 0

@@ -60,6 +60,14 @@ def test_hires_vit_64k_wide_scores():
     assert m["max_abs"] < 1e-3
 
 
+@pytest.mark.parametrize("name", ["swin_w7", "swin_w14"])
+def test_window_attention_shapes(name):
+    """Many small independent windows (d = 32): batched tiny problems, every row checked."""
+    w = inputs.WORKLOADS[name]
+    _check(w, per_head=w.n)
+    _check(w.with_(fp16=True, name=name + "_fp16"), per_head=w.n)
+
+
 def test_small_workloads_with_workspace_split():
     """The two short workloads again with a lent workspace, so the library splits the key range."""
     import torch

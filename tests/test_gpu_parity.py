@@ -59,7 +59,7 @@ def test_mfma_layout_and_half_wave_exchange():
 
 
 @pytest.mark.parametrize("path,variant", ALL_KERNELS)
-@pytest.mark.parametrize("shape", [(1, 2, 197, 64), (2, 2, 330, 64), (1, 2, 300, 128)])
+@pytest.mark.parametrize("shape", [(1, 2, 197, 64), (2, 2, 330, 64), (1, 2, 300, 128), (2, 3, 200, 32)])
 @pytest.mark.parametrize("causal", [False, True])
 def test_small_problems_every_kernel(path, variant, shape, causal):
     B, H, n, d = shape
@@ -72,7 +72,7 @@ def test_small_problems_every_kernel(path, variant, shape, causal):
 
 
 @pytest.mark.parametrize("path,variant", [(MFMA, 1), (MFMA, 3), (FMA, 1), (MFMA16, 1), (MFMA16, 2), (MFMA16, 3)])
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_fp16_io(path, variant, d):
     B, H, n = 1, 3, 450
     q, k, v = _rand(B, H, n, d, 7, fp16=True)
@@ -185,7 +185,7 @@ def test_split_kv_states_and_combine(path, variant, C, causal):
     assert_parity(out.reshape(-1, d).double().cpu().numpy(), ref, tol, "combine C=%d causal=%d" % (C, causal))
 
 
-@pytest.mark.parametrize("d,fp16_out", [(64, False), (128, False), (64, True)])
+@pytest.mark.parametrize("d,fp16_out", [(64, False), (128, False), (64, True), (32, False)])
 def test_combine_alone_on_oracle_states(d, fp16_out):
     """elsa_combine fed with block states written by the oracle (incl. identities)."""
     import torch
@@ -294,7 +294,7 @@ def test_varlen_packed_sequences(path, variant):
     assert np.array_equal(a, b)
 
 
-@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("d", [32, 64, 128])
 def test_varlen_fp16_and_paper_recipe(d):
     # 8 sequences with lengths uniform on [256, 1792] (the padding-free workload), default kernels
     for fp16 in (False, True):
