@@ -54,6 +54,9 @@ int pick_variant(int path, long long BH, int n, int d, int splits) {
     return d <= 64 ? 7 : 1;
 }
 
+// The LDS-free one-wave-per-tile kernel serves dense single-pass calls only.
+bool small_kernel_ok(const int32_t *cu_seqlens, int splits, int emit) { return !cu_seqlens && splits == 1 && !emit; }
+
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
                 int B, int H, int n, int d, float scale, int causal, const int32_t *kv_len,
                 int num_splits, int emit, int m_natural, int dtype, void *stream,
@@ -66,7 +69,13 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     const long long tok_stride = cu_seqlens ? (long long)H * d : d;
     const long long longest = cu_seqlens ? total_tokens : n;
     if (path != 1 && longest * tok_stride * (dtype == ELSA_F16 ? 2 : 4) >= 0x7fffffffLL) return ELSA_ERR_UNSUPPORTED;
-    const int variant = pick_variant(path, (long long)B * H, n, d, num_splits);
+    int variant = pick_variant(path, (long long)B * H, n, d, num_splits);
+    if (path == 2) {
+        const bool ok = small_kernel_ok(cu_seqlens, num_splits, emit);
+        if (g.opt[ELSA_OPT_VARIANT] == 0 && ok && n <= 128 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu)
+            variant = 10;                        // thousands of tiny problems (window attention)
+        if ((variant == 9 || variant == 10) && !ok) variant = d <= 64 ? 7 : 1;
+    }
     const int tq = variant_tq(path, variant, d);
     if (tq <= 0) return ELSA_ERR_UNSUPPORTED;
     elsa::FwdParams p{};

@@ -387,9 +387,11 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 //     5 q128 with 1 score chain                       6 q128 with 4 score chains
 //     7 q128k32: 32-key tiles, 3 waves per SIMD       8 q128 with plain global loads (no descriptors)
 // All but 8 fetch tiles through buffer descriptors; all but 5/6 use 2 score chains.
+//     9/10 small: one wave per 64 / 32 query rows, operands straight from memory (elsa_fwd_small.hip)
 
-static const char *kNames[kMfmaVariants] = {"mfma_q128_w4",   "mfma_q256_w4",   "mfma_xwave",   "mfma_q256_w8",
-                                            "mfma_q128_acc1", "mfma_q128_acc4", "mfma_q128_k32", "mfma_q128_gld"};
+static const char *kNames[kMfmaVariants] = {"mfma_q128_w4",   "mfma_q256_w4",   "mfma_xwave",    "mfma_q256_w8",
+                                            "mfma_q128_acc1", "mfma_q128_acc4", "mfma_q128_k32", "mfma_q128_gld",
+                                            "mfma_small_q64", "mfma_small_q32"};
 
 int mfma_variant_tq(int variant, int d) {
     switch (variant) {
@@ -397,6 +399,8 @@ int mfma_variant_tq(int variant, int d) {
         case 2: return d == 128 ? 128 : 256;
         case 4: return d == 128 ? 128 : 256;
         case 3: return d == 128 ? 64 : 32;      // d = 128: two query waves x two key waves
+        case 9: return 64;                      // one wave per 64 (32) query rows, no LDS
+        case 10: return 32;
         default: return 0;
     }
 }
@@ -456,6 +460,7 @@ static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
 
 int launch_fwd_mfma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name) {
     if (name) *name = mfma_variant_name(variant);
+    if (variant == 9 || variant == 10) return launch_fwd_mfma_small(p, d, f16, variant == 9 ? 2 : 1, s);
     if (d == 32) return f16 ? launch_variant<32, _Float16>(p, variant, s) : launch_variant<32, float>(p, variant, s);
     if (d == 64) return f16 ? launch_variant<64, _Float16>(p, variant, s) : launch_variant<64, float>(p, variant, s);
     if (d == 128) return f16 ? launch_variant<128, _Float16>(p, variant, s) : launch_variant<128, float>(p, variant, s);
