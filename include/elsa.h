@@ -81,6 +81,8 @@ int elsa_attn_fwd_lse(const void *q, const void *k, const void *v, void *out, fl
  * only within itself; Eq. 1 per sequence.  No layout conversion and no padding
  * work: query tiles are cut per sequence.  max_seqlen (>= every length) only
  * guides the tile choice.  1 <= num_seqs <= 4096.  Empty sequences are allowed.
+ * Offsets are clamped to [0, total_tokens] on the device; tokens not covered by any
+ * sequence are left untouched in out.
  */
 int elsa_attn_fwd_varlen(const void *q, const void *k, const void *v, void *out,
                          const int32_t *cu_seqlens, int num_seqs, int total_tokens, int max_seqlen,

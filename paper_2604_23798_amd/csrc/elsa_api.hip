@@ -94,6 +94,7 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     p.tq = tq;
     p.cu_seqlens = cu_seqlens;
     p.num_seqs = num_seqs;
+    p.total_tokens = total_tokens;
     // every sequence wastes at most one partly filled tile
     p.var_tiles = cu_seqlens ? (int)(((long long)total_tokens + tq - 1) / tq + num_seqs) : 0;
     p.xcd_map = g.opt[ELSA_OPT_XCD_MAP];

@@ -39,6 +39,7 @@ struct FwdParams {
     const int32_t *cu_seqlens;       // device [num_seqs + 1], token offsets of the sequences
     int num_seqs;
     int var_tiles;                   // upper bound of query tiles over all sequences
+    int total_tokens;                // offsets in cu_seqlens are clamped to [0, total_tokens]
 };
 
 struct CombineParams {
@@ -96,9 +97,11 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
         const long long w = blockIdx.x;
         const int hd = (int)(w % p.H);
         const int t = (int)(w / p.H);
-        int s = 0, before = 0, len = 0, tiles = 0;
+        // offsets are clamped so that a malformed list cannot send an access outside the tensors
+        int s = 0, before = 0, len = 0, tiles = 0, beg = 0;
         for (; s < p.num_seqs; ++s) {
-            len = p.cu_seqlens[s + 1] - p.cu_seqlens[s];
+            beg = min(max(p.cu_seqlens[s], 0), p.total_tokens);
+            len = min(max(p.cu_seqlens[s + 1], beg), p.total_tokens) - beg;
             tiles = len > 0 ? (len + p.tq - 1) / p.tq : 0;
             if (t < before + tiles) break;
             before += tiles;
@@ -110,7 +113,7 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
         r.qt = t - before;
         if (p.causal) r.qt = tiles - 1 - r.qt;
         r.ts = (long long)p.H * D;
-        r.base = r.valid ? (long long)p.cu_seqlens[s] * r.ts + (long long)hd * D : 0;
+        r.base = r.valid ? (long long)beg * r.ts + (long long)hd * D : 0;
         return r;
     }
     const long long BH = (long long)p.B * p.H;

@@ -70,6 +70,7 @@ def test_bad_arguments_are_rejected_before_any_launch():
     assert f(B=0) == INV and f(H=-1) == INV and f(n=0) == INV
     assert f(d=48) == UNS and f(d=256) == UNS and f(dtype=2) == UNS
     assert f(scale=float("nan")) == INV and f(scale=float("inf")) == INV
+    assert f(n=1 << 24, d=128) == UNS          # one K slice of 8 GiB: beyond the 2 GiB buffer range
     s = lambda C, **kw: lib.elsa_attn_fwd_split_kv(p, p, p, kw.get("pm", p), p, p, 1, 1, 8, 64, 0.125, 0, None, C, 0, None)
     assert s(0) == INV and s(9) == INV and s(2, pm=None) == INV
     c = lambda C, **kw: lib.elsa_combine(p, p, p, kw.get("out", p), 1, 1, 8, kw.get("d", 64), C, 0, None)
