@@ -14,7 +14,9 @@
  * n = 2 sigmoid mixture, q = 0 column mean), a library float64 softmax used as
  * a black box, agreement of the definition with the sequential fold and with
  * arbitrary merge trees, the monoid laws, shift invariance, one-hot dominance,
- * causal-prefix equivalence, key-permutation invariance.  The paper prints no
+ * causal-prefix equivalence, key-permutation invariance; the rectangular (n_q != n_k) routine
+ * against the library softmax with a rectangular mask, against the square routine on the tail
+ * rows of a longer problem, and a hand-computed single-query case.  The paper prints no
  * worked softmax example, so exact output values beyond those closed forms are
  * pinned by these independent formulations only.
  *
@@ -287,6 +289,60 @@ int elsa_oracle_combine_rows(const double *part_m, const double *part_S, const d
         for (int t = 0; t < d; ++t) out[(size_t)r * d + t] = (S > 0.0) ? Wa[t] / S : 0.0;
     }
     free(Wa);
+    return 0;
+}
+
+/*
+ * Rectangular attention: n_q queries against n_k keys per (batch, head) -- cross-attention,
+ * chunked prefill, and single-query decoding against a cache.  Eq. 1 does not tie the number of
+ * queries to the number of keys; the row formula is the same.  q, out: [B][H][n_q][d];
+ * k, v: [B][H][n_k][d]; a row is r = (b*H + h)*n_q + i.
+ * Reading for the causal mask (the paper states it for n_q = n_k only): the LAST query is
+ * aligned with the LAST key, i.e. key j is visible to query i iff j <= i + (n_k - n_q); queries
+ * with no visible key (possible when n_k < n_q) output zeros and lse = -inf.
+ * out: [nrows][d]; lse: [nrows] or NULL.
+ */
+int elsa_oracle_cross_rows(const float *q, const float *k, const float *v,
+                           int B, int H, int nq, int nk, int d, double scale, int causal,
+                           const int32_t *kv_len,
+                           const int64_t *rows, int64_t nrows, double *out, double *lse)
+{
+    (void)B;
+    double *s = (double *)malloc(sizeof(double) * (size_t)(nk > 0 ? nk : 1));
+    if (!s) return -1;
+    for (int64_t r = 0; r < nrows; ++r) {
+        int64_t row = rows[r];
+        int64_t i = row % nq, bh = row / nq, b = bh / H;
+        const float *qi = q + (size_t)row * d;
+        const float *kb = k + (size_t)bh * nk * d;
+        const float *vb = v + (size_t)bh * nk * d;
+        double *o = out + (size_t)r * d;
+        int64_t L = kv_len ? (int64_t)kv_len[b] : nk;
+        if (L > nk) L = nk;
+        if (causal) {
+            int64_t last = i + ((int64_t)nk - (int64_t)nq);     /* last visible key */
+            if (last + 1 < L) L = last + 1;
+        }
+        if (L < 0) L = 0;
+        for (int t = 0; t < d; ++t) o[t] = 0.0;
+        if (lse) lse[r] = -INFINITY;
+        if (L == 0) continue;
+        double m = -INFINITY;
+        for (int64_t j = 0; j < L; ++j) {
+            s[j] = score(qi, kb + (size_t)j * d, d, scale);
+            if (s[j] > m) m = s[j];
+        }
+        double S = 0.0;
+        for (int64_t j = 0; j < L; ++j) {
+            double e = exp(s[j] - m);
+            S += e;
+            const float *vj = vb + (size_t)j * d;
+            for (int t = 0; t < d; ++t) o[t] += e * (double)vj[t];
+        }
+        for (int t = 0; t < d; ++t) o[t] /= S;
+        if (lse) lse[r] = m + log(S);
+    }
+    free(s);
     return 0;
 }
 

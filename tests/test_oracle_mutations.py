@@ -68,6 +68,24 @@ def battery():
         for merge in (oracle.merge_case, oracle.merge_unsum):
             m, S, W = merge(x, y)
             assert abs(m - math.log(2.0)) < 1e-15 and abs(S - 3.5) < 1e-14 and abs(W[0]) < 1e-14
+    # rectangular attention against the library softmax, both aspect ratios, causal and padded
+    for nq, nk in ((5, 23), (23, 5)):
+        qq = inputs.normal(9, 0, 0, 2 * 2 * nq * 8).reshape(2, 2, nq, 8)
+        kk = inputs.normal(9, 1, 0, 2 * 2 * nk * 8).reshape(2, 2, nk, 8)
+        vv = inputs.normal(9, 2, 0, 2 * 2 * nk * 8).reshape(2, 2, nk, 8)
+        a, b_, c = (torch.from_numpy(x).double() for x in (qq, kk, vv))
+        sx = (a @ b_.transpose(-1, -2)) * 0.4
+        o, l = oracle.cross_rows(qq, kk, vv, 0.4)
+        _close(o, (torch.softmax(sx, -1) @ c).numpy().reshape(-1, 8))
+        _close(l, torch.logsumexp(sx, -1).numpy().reshape(-1))
+        i, j = torch.arange(nq)[:, None], torch.arange(nk)[None, :]
+        sm = sx.masked_fill(j > i + (nk - nq), float("-inf"))
+        o, _ = oracle.cross_rows(qq, kk, vv, 0.4, causal=True)
+        _close(o, (torch.nan_to_num(torch.softmax(sm, -1), nan=0.0) @ c).numpy().reshape(-1, 8))
+        kl = np.array([nk, 3], np.int32)
+        sp = sx.masked_fill((j >= torch.from_numpy(kl).long()[:, None, None, None]), float("-inf"))
+        o, _ = oracle.cross_rows(qq, kk, vv, 0.4, kv_len=kl)
+        _close(o, (torch.softmax(sp, -1) @ c).numpy().reshape(-1, 8))
     lad = oracle.ladder_f32_fold_rows(q, k, v, 0.3).astype(np.float64)
     ref = oracle.attn_rows(q, k, v, 0.3)
     assert np.max(np.linalg.norm(lad - ref, axis=1) / np.linalg.norm(ref, axis=1)) < 1e-5
@@ -89,6 +107,11 @@ MUTATIONS = [
     ("combine without normalisation", "out[(size_t)r * d + t] = (S > 0.0) ? Wa[t] / S : 0.0;", "out[(size_t)r * d + t] = Wa[t];"),
     ("log-normaliser without its maximum", "lse[r] = (L > 0) ? m + log(S) : -INFINITY;", "lse[r] = (L > 0) ? log(S) : -INFINITY;"),
     ("transposed operand in the score", "acc += (double)qi[t] * (double)kj[t];", "acc += (double)qi[t] * (double)kj[d - 1 - t];"),
+    ("rectangular: diagonal aligned with the first key", "int64_t last = i + ((int64_t)nk - (int64_t)nq);", "int64_t last = i;"),
+    ("rectangular: diagonal shifted the wrong way", "int64_t last = i + ((int64_t)nk - (int64_t)nq);", "int64_t last = i + ((int64_t)nq - (int64_t)nk);"),
+    ("rectangular: keys strided by the query count", "const float *kb = k + (size_t)bh * nk * d;", "const float *kb = k + (size_t)bh * nq * d;"),
+    ("rectangular: padding ignored", "int64_t L = kv_len ? (int64_t)kv_len[b] : nk;", "int64_t L = nk;"),
+    ("rectangular: log-normaliser without its maximum", "if (lse) lse[r] = m + log(S);", "if (lse) lse[r] = log(S);"),
     ("single-precision ladder: past not rescaled", "S = S * beta + 1.0f;", "S = S + 1.0f;"),
 ]
 

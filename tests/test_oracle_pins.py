@@ -226,3 +226,79 @@ def test_lse_closed_forms_and_library():
     # consistency with the state form: lse = m_c + ln S_c for a single chunk
     pm, pS, _ = oracle.partials_rows(q, k, v, 0.3, 1)
     _close(oracle.lse_rows(q, k, 0.3), pm[:, 0] + np.log(pS[:, 0]), 1e-12)
+
+
+# ---- rectangular attention (n_q != n_k): cross-attention, chunked prefill, decoding -----------
+def _rect(B, H, nq, nk, d, seed):
+    q = inputs.normal(seed, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
+    k = inputs.normal(seed, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
+    v = inputs.normal(seed, 2, 0, B * H * nk * d).reshape(B, H, nk, d)
+    return q, k, v
+
+
+def test_cross_single_query_two_keys_by_hand():
+    q = np.array([[[[2.0, 1.0]]]], np.float32)
+    k = np.array([[[[1.0, 0.0], [0.0, 3.0]]]], np.float32)
+    v = np.array([[[[4.0, -2.0], [-6.0, 10.0]]]], np.float32)
+    s1, s2 = 0.5 * 2.0, 0.5 * 3.0
+    w1 = 1.0 / (1.0 + math.exp(s2 - s1))
+    out, lse = oracle.cross_rows(q, k, v, 0.5)
+    _close(out[0], [w1 * 4.0 + (1 - w1) * -6.0, w1 * -2.0 + (1 - w1) * 10.0])
+    _close(lse[0], math.log(math.exp(s1) + math.exp(s2)))
+    # causal with one query and two keys: the query is the LAST position, so it sees both keys
+    out_c, _ = oracle.cross_rows(q, k, v, 0.5, causal=True)
+    _close(out_c, out)
+
+
+@pytest.mark.parametrize("nq,nk", [(5, 23), (23, 5), (1, 40), (17, 17)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_cross_against_library_softmax(nq, nk, causal):
+    B, H, d = 2, 3, 8
+    q, k, v = _rect(B, H, nq, nk, d, 31 + nq)
+    tq, tk, tv = (torch.from_numpy(t).double() for t in (q, k, v))
+    s = (tq @ tk.transpose(-1, -2)) * 0.4
+    if causal:
+        i = torch.arange(nq)[:, None]
+        j = torch.arange(nk)[None, :]
+        s = s.masked_fill(j > i + (nk - nq), float("-inf"))
+    p = torch.softmax(s, -1)
+    p = torch.nan_to_num(p, nan=0.0)                     # rows with no visible key
+    out, lse = oracle.cross_rows(q, k, v, 0.4, causal=causal)
+    _close(out, (p @ tv).numpy().reshape(-1, d))
+    ref_lse = torch.logsumexp(s, -1).numpy().reshape(-1)
+    vis = np.isfinite(ref_lse)
+    _close(lse[vis], ref_lse[vis])
+    assert np.all(np.isneginf(lse[~vis])) and np.all(out[~vis] == 0)
+    if causal and nk < nq:
+        assert (~vis).reshape(B * H, nq)[:, : nq - nk].all() and vis.reshape(B * H, nq)[:, nq - nk:].all()
+
+
+def test_cross_square_case_is_the_square_routine():
+    q, k, v = _rand(2, 2, 29, 8, 41)
+    kv_len = np.array([29, 9], np.int32)
+    for causal in (False, True):
+        out, lse = oracle.cross_rows(q, k, v, 0.3, causal=causal, kv_len=kv_len)
+        _close(out, oracle.attn_rows(q, k, v, 0.3, causal=causal, kv_len=kv_len))
+        _close(lse, oracle.lse_rows(q, k, 0.3, causal=causal, kv_len=kv_len))
+
+
+def test_cross_tail_queries_of_a_causal_problem():
+    """Chunked prefill / decoding: the last n_q queries of a causal square problem, given alone."""
+    B, H, n, d = 1, 2, 45, 8
+    q, k, v = _rand(B, H, n, d, 43)
+    full = oracle.attn_rows(q, k, v, 0.25, causal=True).reshape(B, H, n, d)
+    for nq in (1, 7, 32):
+        out, _ = oracle.cross_rows(q[:, :, n - nq:], k, v, 0.25, causal=True)
+        _close(out.reshape(B, H, nq, d), full[:, :, n - nq:])
+
+
+def test_cross_key_padding_and_row_subset():
+    B, H, nq, nk, d = 2, 2, 6, 19, 4
+    q, k, v = _rect(B, H, nq, nk, d, 47)
+    kv_len = np.array([19, 4], np.int32)
+    out, _ = oracle.cross_rows(q, k, v, 0.7, kv_len=kv_len)
+    trunc, _ = oracle.cross_rows(q[1:], k[1:, :, :4], v[1:, :, :4], 0.7)
+    _close(out.reshape(B, H * nq, d)[1], trunc)
+    rows = np.array([3, 23, 0], np.int64)
+    sub, _ = oracle.cross_rows(q, k, v, 0.7, kv_len=kv_len, rows=rows)
+    _close(sub, out[rows])
