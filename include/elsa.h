@@ -74,6 +74,22 @@ int elsa_attn_fwd_lse(const void *q, const void *k, const void *v, void *out, fl
                       const int32_t *kv_len, int dtype, void *stream);
 
 /*
+ * Rectangular attention: n_q queries against n_k keys per (batch, head) -- cross-attention,
+ * chunked prefill, and decoding a few new positions against a cache.  Eq. 1 does not tie the
+ * number of queries to the number of keys; every row is the same reduction over its visible keys.
+ *   q, out: [B][H][n_q][d];  k, v: [B][H][n_k][d];  lse: FP32 [B][H][n_q] or NULL (not written).
+ * causal != 0 aligns the LAST query with the LAST key: key j is visible to query i iff
+ * j <= i + (n_k - n_q); a query with no visible key (n_k < n_q) gets zeros and lse = -inf.
+ * kv_len (device int32 [B], or NULL) bounds the visible keys of a batch entry from above.
+ * With a registered workspace and few query tiles the key range is split internally (up to 64
+ * chunks when n_q * 8 <= n_k) and combined, which is what fills the GPU when decoding.
+ * Errors as elsa_attn_fwd; additionally ELSA_ERR_INVALID_ARG for n_k <= 0.
+ */
+int elsa_attn_fwd_cross(const void *q, const void *k, const void *v, void *out, float *lse,
+                        int B, int H, int n_q, int n_k, int d, float scale, int causal,
+                        const int32_t *kv_len, int dtype, void *stream);
+
+/*
  * Padding-free variable-length batches (the packed layout of the paper's
  * "padding-free variable-length" workload): Q, K, V, out are [total_tokens][H][d],
  * sequence s owns tokens cu_seqlens[s] .. cu_seqlens[s+1]-1 (device int32

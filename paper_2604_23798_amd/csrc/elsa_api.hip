@@ -55,23 +55,27 @@ int pick_variant(int path, long long BH, int n, int d, int splits) {
 }
 
 // The LDS-free one-wave-per-tile kernel serves dense single-pass calls only.
-bool small_kernel_ok(const int32_t *cu_seqlens, int splits, int emit) { return !cu_seqlens && splits == 1 && !emit; }
+bool small_kernel_ok(const int32_t *cu_seqlens, int splits, int emit, int n, int nk) {
+    return !cu_seqlens && splits == 1 && !emit && n == nk;
+}
 
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
                 int B, int H, int n, int d, float scale, int causal, const int32_t *kv_len,
                 int num_splits, int emit, int m_natural, int dtype, void *stream,
-                const int32_t *cu_seqlens = nullptr, int num_seqs = 0, int total_tokens = 0, float *lse = nullptr) {
+                const int32_t *cu_seqlens = nullptr, int num_seqs = 0, int total_tokens = 0, float *lse = nullptr,
+                int nk = 0) {
+    if (nk <= 0) nk = n;                         // self-attention: as many keys as queries
     // auto: FP32 I/O -> FP32 MFMA; FP16 I/O -> FP16 MFMA (needs a non-zero scale)
     int path = g.opt[ELSA_OPT_PATH];
     if (path == 0) path = (dtype == ELSA_F16 && scale != 0.f) ? 3 : 2;
     if (path == 3 && (dtype != ELSA_F16 || scale == 0.f)) return ELSA_ERR_UNSUPPORTED;
     // the K/V slice of one (sequence, head) is addressed through a 31-bit buffer range
     const long long tok_stride = cu_seqlens ? (long long)H * d : d;
-    const long long longest = cu_seqlens ? total_tokens : n;
+    const long long longest = cu_seqlens ? total_tokens : (nk > n ? nk : n);
     if (path != 1 && longest * tok_stride * (dtype == ELSA_F16 ? 2 : 4) >= 0x7fffffffLL) return ELSA_ERR_UNSUPPORTED;
     int variant = pick_variant(path, (long long)B * H, n, d, num_splits);
     if (path == 2) {
-        const bool ok = small_kernel_ok(cu_seqlens, num_splits, emit);
+        const bool ok = small_kernel_ok(cu_seqlens, num_splits, emit, n, nk);
         if (g.opt[ELSA_OPT_VARIANT] == 0 && ok && n <= 128 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu)
             variant = 10;                        // thousands of tiny problems (window attention)
         if ((variant == 9 || variant == 10) && !ok) variant = d <= 64 ? 7 : 1;
@@ -83,11 +87,11 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     p.lse = lse;
     p.part_m = pm; p.part_S = pS; p.part_W = pW;
     p.kv_len = kv_len;
-    p.B = B; p.H = H; p.n = n;
+    p.B = B; p.H = H; p.n = n; p.nk = nk;
     p.qscale = scale * elsa::kLog2e;
     p.causal = causal ? 1 : 0;
     p.num_splits = num_splits;
-    p.chunk = (n + num_splits - 1) / num_splits;
+    p.chunk = (nk + num_splits - 1) / num_splits;
     p.emit_partials = emit;
     p.m_natural = m_natural;
     p.q_tiles = (n + tq - 1) / tq;
@@ -121,19 +125,21 @@ void carve(void *ws, int B, int H, int n, int d, int C, float **pm, float **pS, 
 
 // Number of key chunks for elsa_attn_fwd when a workspace is lent: enough 128-row blocks for
 // two per CU, chunks no shorter than 256 keys, at most 8, and only if the workspace holds them.
-int auto_splits(int B, int H, int n, int d) {
+int auto_splits(int B, int H, int n, int nk, int d) {
     int C = g.opt[ELSA_OPT_SPLITS];
     if (C <= 0) {
         const long long blocks = (long long)B * H * ((n + 127) / 128);
         C = 1;
         if (blocks < 2 * kNumCu) {
             C = (int)((2 * kNumCu + blocks - 1) / blocks);
-            const int cap = n / 256 > 1 ? n / 256 : 1;
+            const int cap = nk / 256 > 1 ? nk / 256 : 1;
             if (C > cap) C = cap;
-            if (C > 8) C = 8;
+            // few queries against many keys (decoding): the key range is the only parallelism
+            const int most = n * 8 <= nk ? 64 : 8;
+            if (C > most) C = most;
         }
     }
-    if (C > n) C = n;
+    if (C > nk) C = nk;
     if (C > kMaxSplits) C = kMaxSplits;
     while (C > 1 && elsa_split_kv_workspace_bytes(B, H, n, d, C) > g.ws_bytes) --C;
     return C < 1 ? 1 : C;
@@ -159,19 +165,21 @@ int elsa_set_workspace(void *dev_ptr, size_t bytes) {
 
 static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out, float *lse,
                          int B, int H, int n, int d, float scale, int causal,
-                         const int32_t *kv_len, int dtype, void *stream) {
+                         const int32_t *kv_len, int dtype, void *stream, int nk = 0) {
     if (!q || !k || !v || !out) return ELSA_ERR_INVALID_ARG;
     if (!std::isfinite(scale)) return ELSA_ERR_INVALID_ARG;
+    if (nk <= 0) nk = n;
     int rc = check_common(B, H, n, d, dtype);
     if (rc != ELSA_OK) return rc;
-    const int C = g.ws ? auto_splits(B, H, n, d) : 1;
+    const int C = g.ws ? auto_splits(B, H, n, nk, d) : 1;
     if (C == 1)
         return run_forward(q, k, v, out, nullptr, nullptr, nullptr, B, H, n, d, scale, causal, kv_len, 1, 0, 0, dtype,
-                           stream, nullptr, 0, 0, lse);
+                           stream, nullptr, 0, 0, lse, nk);
     float *pm, *pS, *pW;
     carve(g.ws, B, H, n, d, C, &pm, &pS, &pW);
     // internal split: maxima stay in log2 units, so the second pass adds no rounding of m
-    rc = run_forward(q, k, v, nullptr, pm, pS, pW, B, H, n, d, scale, causal, kv_len, C, 1, 0, dtype, stream);
+    rc = run_forward(q, k, v, nullptr, pm, pS, pW, B, H, n, d, scale, causal, kv_len, C, 1, 0, dtype, stream,
+                     nullptr, 0, 0, nullptr, nk);
     if (rc != ELSA_OK) return rc;
     elsa::CombineParams cp{pm, pS, pW, out, lse, (long long)B * H * n, n, C, 0, dtype == ELSA_F16};
     return elsa::launch_combine(cp, d, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
@@ -188,6 +196,13 @@ int elsa_attn_fwd_lse(const void *q, const void *k, const void *v, void *out, fl
                       const int32_t *kv_len, int dtype, void *stream) {
     if (!lse) return ELSA_ERR_INVALID_ARG;
     return attn_fwd_impl(q, k, v, out, lse, B, H, n, d, scale, causal, kv_len, dtype, stream);
+}
+
+int elsa_attn_fwd_cross(const void *q, const void *k, const void *v, void *out, float *lse,
+                        int B, int H, int n_q, int n_k, int d, float scale, int causal,
+                        const int32_t *kv_len, int dtype, void *stream) {
+    if (n_k <= 0) return ELSA_ERR_INVALID_ARG;
+    return attn_fwd_impl(q, k, v, out, lse, B, H, n_q, d, scale, causal, kv_len, dtype, stream, n_k);
 }
 
 int elsa_attn_fwd(const void *q, const void *k, const void *v, void *out,

@@ -25,11 +25,12 @@ struct FwdParams {
     float *lse;                      // optional [B][H][n]: ln sum_j e^{s_ij} (dense layout, single pass)
     float *part_m, *part_S, *part_W; // [BH][C][n], [BH][C][n], [BH][C][n][d]
     const int32_t *kv_len;           // device [B] or nullptr
-    int B, H, n;
+    int B, H, n;                     // n: queries per (batch, head)
+    int nk;                          // keys per (batch, head); nk == n for self-attention
     float qscale;
     int causal;
     int num_splits;                  // C >= 1
-    int chunk;                       // ceil(n / C) keys per split
+    int chunk;                       // ceil(nk / C) keys per split
     int emit_partials;               // 1: write (m,S,W) states instead of out
     int m_natural;                   // 1: part_m in natural-log units, 0: log2 units (internal)
     int xcd_map;                     // block -> work item order, see decode_work
@@ -84,8 +85,11 @@ struct Work {
     int qt, c;
     long long bh;
     bool valid;
-    int n;             // keys (= queries) of the sequence this block works on
-    long long base;    // element offset of token 0 of this (sequence, head)
+    int n;             // queries of the sequence this block works on
+    int nk;            // its keys
+    int coff;          // causal mask: key j is visible to query i iff j <= i + coff  (coff = nk - n)
+    long long base;    // element offset of query 0 of this (sequence, head) in Q and out
+    long long kbase;   // element offset of key 0 in K and V
     long long ts;      // elements between consecutive tokens
 };
 template <int D>
@@ -110,10 +114,13 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
         r.c = 0;
         r.bh = (long long)s * p.H + hd;
         r.n = r.valid ? len : 0;
+        r.nk = r.n;
+        r.coff = 0;
         r.qt = t - before;
         if (p.causal) r.qt = tiles - 1 - r.qt;
         r.ts = (long long)p.H * D;
         r.base = r.valid ? (long long)beg * r.ts + (long long)hd * D : 0;
+        r.kbase = r.base;
         return r;
     }
     const long long BH = (long long)p.B * p.H;
@@ -137,8 +144,11 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
     }
     if (p.causal) r.qt = p.q_tiles - 1 - r.qt;   // longest rows first
     r.n = p.n;
+    r.nk = p.nk;
+    r.coff = p.nk - p.n;
     r.ts = D;
     r.base = r.bh * (long long)p.n * D;
+    r.kbase = r.bh * (long long)p.nk * D;
     return r;
 }
 

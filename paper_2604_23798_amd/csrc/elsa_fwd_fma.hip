@@ -28,12 +28,13 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
     const long long bh = wi.bh;
     const int n = wi.n;
     const long long ts = wi.ts;          // elements between consecutive tokens
-    int L = n;
-    if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), n);
+    const int coff = wi.coff;            // causal: key j visible to row i iff j <= i + coff
+    int L = wi.nk;
+    if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), wi.nk);
     const int q0 = qt * TQ;
     const int kbeg = c * p.chunk;
     int kend = min(kbeg + p.chunk, L);
-    if (p.causal) kend = min(kend, q0 + TQ);
+    if (p.causal) kend = min(kend, q0 + TQ + coff);
 
     // this wave's slice of the block's key range
     const int span = kend > kbeg ? kend - kbeg : 0;
@@ -41,11 +42,11 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
     const int wbeg = kbeg + wk * per;
     int wend = min(wbeg + per, kend);
     const int wrow0 = q0 + wq * 64;
-    if (p.causal) wend = min(wend, wrow0 + 64);
+    if (p.causal) wend = min(wend, wrow0 + 64 + coff);
 
     const long long head_off = wi.base;
     const int row = wrow0 + lane;
-    const int lim = p.causal ? min(wend, row + 1) : wend;      // keys >= lim are invisible to this row
+    const int lim = p.causal ? min(wend, row + 1 + coff) : wend;      // keys >= lim are invisible to this row
 
     float qr[D];
 #pragma unroll
@@ -61,14 +62,14 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
 #pragma unroll
     for (int t = 0; t < D; ++t) W[t] = 0.f;
 
-    const T *__restrict__ kp = static_cast<const T *>(p.k) + head_off;
-    const T *__restrict__ vp = static_cast<const T *>(p.v) + head_off;
+    const T *__restrict__ kp = static_cast<const T *>(p.k) + wi.kbase;
+    const T *__restrict__ vp = static_cast<const T *>(p.v) + wi.kbase;
 
     for (int j0 = wbeg; j0 < wend; j0 += G) {
         float s[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const int key = min(j0 + g, n - 1);                // clamp: never read past the tensor
+            const int key = min(j0 + g, wi.nk - 1);                // clamp: never read past the tensor
             const T *__restrict__ kj = kp + (long long)key * ts;
             float acc = 0.f;
 #pragma unroll
@@ -93,7 +94,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
         for (int t = 0; t < D; ++t) W[t] *= alpha;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const int key = min(j0 + g, n - 1);
+            const int key = min(j0 + g, wi.nk - 1);
             const T *__restrict__ vj = vp + (long long)key * ts;
 #pragma unroll
             for (int t = 0; t < D; ++t) W[t] = fmaf(e[g], ld_uniform(vj, t), W[t]);

@@ -55,15 +55,17 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     const long long bh = wi.bh;
     const int n = wi.n;
     const long long ts = wi.ts;          // elements between consecutive tokens
-    int L = n;
-    if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), n);
+    const int coff = wi.coff;            // causal: key j visible to row i iff j <= i + coff
+    int L = wi.nk;
+    if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), wi.nk);
     const int q0 = qt * TQ;
     const int kbeg = c * p.chunk;
     int kend = min(kbeg + p.chunk, L);
-    if (p.causal) kend = min(kend, q0 + TQ);
+    if (p.causal) kend = min(kend, q0 + TQ + coff);
     const int ntiles = kend > kbeg ? (kend - kbeg + TKB - 1) / TKB : 0;
 
-    const long long head_off = wi.base;
+    const long long head_off = wi.base;   // Q and out
+    const long long kv_off = wi.kbase;     // K and V
     const int wrow0 = q0 + wq * NQ * 32;    // first query row of this wave
 
     // ---- Q fragments (B operand).  MFMA step s = 4*cc + t contracts columns
@@ -99,8 +101,8 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     // and the tile's position is one scalar offset -- no vector address arithmetic per tile.
     constexpr bool BUF = BUFL != 0;
     const long long slice_bytes = kend > 0 ? ((long long)(kend - 1) * ts + D) * (long long)sizeof(T) : 0;
-    const __amdgpu_buffer_rsrc_t krs = make_rsrc(static_cast<const T *>(p.k) + head_off, BUF ? slice_bytes : 0);
-    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(static_cast<const T *>(p.v) + head_off, BUF ? slice_bytes : 0);
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(static_cast<const T *>(p.k) + kv_off, BUF ? slice_bytes : 0);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(static_cast<const T *>(p.v) + kv_off, BUF ? slice_bytes : 0);
     int voff[LPT];
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
@@ -125,7 +127,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
             const int key = kb0 + row;
             f32x4 kx = {0.f, 0.f, 0.f, 0.f}, vx = {0.f, 0.f, 0.f, 0.f};
             if (key < kend) {               // rows past the chunk are zero (and masked below)
-                const long long off = head_off + (long long)key * ts + 4 * c4;
+                const long long off = kv_off + (long long)key * ts + 4 * c4;
                 kx = Io<T>::load4(p.k, off);
                 vx = Io<T>::load4(p.v, off);
             }
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
         __syncthreads();
     }
     // first key that no lane of this wave can see
-    const int wave_lim = p.causal ? min(kend, wrow0 + NQ * 32) : kend;
+    const int wave_lim = p.causal ? min(kend, wrow0 + NQ * 32 + coff) : kend;
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1;
         if (t + 1 < ntiles) gload(t + 1);
@@ -206,12 +208,12 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
             }
 
             // ---- (a2) masks: only on steps that straddle the chunk end or the diagonal
-            const bool need_mask = (kg + 32 > kend) || (p.causal && kg + 31 > wrow0);
+            const bool need_mask = (kg + 32 > kend) || (p.causal && kg + 31 > wrow0 + coff);
             if (need_mask) {
 #pragma unroll
                 for (int nq = 0; nq < NQ; ++nq) {
                     const int row = wrow0 + nq * 32 + j;
-                    const int lim = p.causal ? min(kend, row + 1) : kend;
+                    const int lim = p.causal ? min(kend, row + 1 + coff) : kend;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int key = kg + 8 * (i >> 2) + 4 * h + (i & 3);

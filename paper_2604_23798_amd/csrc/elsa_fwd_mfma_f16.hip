@@ -56,15 +56,17 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
     const long long bh = wi.bh;
     const int n = wi.n;
     const long long ts = wi.ts;          // elements between consecutive tokens
-    int L = n;
-    if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), n);
+    const int coff = wi.coff;            // causal: key j visible to row i iff j <= i + coff
+    int L = wi.nk;
+    if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), wi.nk);
     const int q0 = qt * TQ;
     const int kbeg = c * p.chunk;
     int kend = min(kbeg + p.chunk, L);
-    if (p.causal) kend = min(kend, q0 + TQ);
+    if (p.causal) kend = min(kend, q0 + TQ + coff);
     const int ntiles = kend > kbeg ? (kend - kbeg + TKB - 1) / TKB : 0;
 
-    const long long head_off = wi.base;
+    const long long head_off = wi.base;   // Q and out
+    const long long kv_off = wi.kbase;     // K and V
     const int wrow0 = q0 + wq * NQ * 32;
     const _Float16 *qp = static_cast<const _Float16 *>(p.q);
     const _Float16 *kp = static_cast<const _Float16 *>(p.k);
@@ -106,8 +108,8 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
     // tile's position is one scalar offset (no vector address arithmetic, no lane masks).
     f16x8 kst[LPT], vst[LPT];
     const long long slice_bytes = kend > 0 ? ((long long)(kend - 1) * ts + D) * 2 : 0;
-    const __amdgpu_buffer_rsrc_t krs = make_rsrc(kp + head_off, slice_bytes);
-    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vp + head_off, slice_bytes);
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(kp + kv_off, slice_bytes);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(vp + kv_off, slice_bytes);
     int voff[LPT];
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
@@ -137,7 +139,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
         lstore(0);
         __syncthreads();
     }
-    const int wave_lim = p.causal ? min(kend, wrow0 + NQ * 32) : kend;
+    const int wave_lim = p.causal ? min(kend, wrow0 + NQ * 32 + coff) : kend;
     for (int t = 0; t < ntiles; ++t) {
         const int buf = t & 1;
         if (t + 1 < ntiles) gload(t + 1);
@@ -164,12 +166,12 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
             }
 
             // ---- (a2) masks
-            const bool need_mask = (kg + 32 > kend) || (p.causal && kg + 31 > wrow0);
+            const bool need_mask = (kg + 32 > kend) || (p.causal && kg + 31 > wrow0 + coff);
             if (need_mask) {
 #pragma unroll
                 for (int nq = 0; nq < NQ; ++nq) {
                     const int row = wrow0 + nq * 32 + j;
-                    const int lim = p.causal ? min(kend, row + 1) : kend;
+                    const int lim = p.causal ? min(kend, row + 1 + coff) : kend;
 #pragma unroll
                     for (int i = 0; i < 16; ++i) {
                         const int key = kg + 8 * (i >> 2) + 4 * h + (i & 3);

@@ -17,7 +17,7 @@ F32, F16 = 0, 1
 OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP = 0, 1, 2, 3
 PATH_AUTO, PATH_FMA, PATH_MFMA, PATH_MFMA16 = 0, 1, 2, 3
 
-EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_lse", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
+EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_lse", "elsa_attn_fwd_cross", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
            "elsa_split_kv_workspace_bytes", "elsa_set_workspace", "elsa_set_option", "elsa_get_option",
            "elsa_variant_name", "elsa_last_kernel", "elsa_status_string", "elsa_debug_layout_probe")
 
@@ -30,6 +30,7 @@ _vp, _i, _f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
 _lib.elsa_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _i, _vp]
 _lib.elsa_attn_fwd_masked.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
 _lib.elsa_attn_fwd_lse.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
+_lib.elsa_attn_fwd_cross.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
 _lib.elsa_attn_fwd_varlen.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _i, _vp]
 _lib.elsa_attn_fwd_split_kv.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _i, _vp]
 _lib.elsa_combine.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]
@@ -114,6 +115,24 @@ def elsa_attn_fwd_lse(q, k, v, out, lse, scale, causal=False, kv_len=None, strea
     _check(_lib.elsa_attn_fwd_lse(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, n, d, float(scale),
                                   int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
     return out, lse
+
+
+def elsa_attn_fwd_cross(q, k, v, out, scale, causal=False, kv_len=None, lse=None, stream=None):
+    """q, out: [B, H, n_q, d]; k, v: [B, H, n_k, d]; lse (optional): float32 [B, H, n_q]."""
+    import torch
+    assert q.is_cuda and q.dim() == 4 and k.dim() == 4 and k.shape == v.shape
+    assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and out.is_contiguous()
+    assert q.dtype == k.dtype == v.dtype == out.dtype and out.shape == q.shape
+    B, H, nq, d = q.shape
+    nk = k.shape[2]
+    assert tuple(k.shape) == (B, H, nk, d)
+    if kv_len is not None:
+        assert kv_len.is_cuda and kv_len.dtype == torch.int32 and tuple(kv_len.shape) == (B,)
+    if lse is not None:
+        assert lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, H, nq)
+    _check(_lib.elsa_attn_fwd_cross(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, nq, nk, d, float(scale),
+                                    int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
+    return out
 
 
 def elsa_attn_fwd_varlen(q, k, v, out, cu_seqlens, max_seqlen, scale, causal=False, stream=None):

@@ -84,3 +84,16 @@ def fwd_varlen(q, k, v, cu, max_seqlen, scale, causal=False):
     elsa.elsa_attn_fwd_varlen(tq, tk, tv, out, tcu, max_seqlen, scale, causal)
     torch.cuda.synchronize()
     return out.double().cpu().numpy()
+
+
+def fwd_cross(q, k, v, scale, causal=False, kv_len=None, want_lse=False):
+    """elsa_attn_fwd_cross on numpy inputs (q [B,H,nq,d]; k, v [B,H,nk,d]) -> float64 [R, d] (, lse [R])."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    tq, tk, tv, tl = to_dev(q), to_dev(k), to_dev(v), to_dev(kv_len)
+    out = torch.full_like(tq, float("nan"))
+    lse = torch.full(tq.shape[:3], float("nan"), device="cuda") if want_lse else None
+    elsa.elsa_attn_fwd_cross(tq, tk, tv, out, scale, causal, tl, lse)
+    torch.cuda.synchronize()
+    o = out.reshape(-1, q.shape[-1]).double().cpu().numpy()
+    return (o, lse.reshape(-1).double().cpu().numpy()) if want_lse else o

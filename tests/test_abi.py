@@ -83,3 +83,7 @@ def test_bad_arguments_are_rejected_before_any_launch():
                                                kw.get("mx", 40), 2, kw.get("d", 64), 0.125, 0, 0, None)
     assert vl(cu=None) == INV and vl(ns=0) == INV and vl(ns=5000) == INV and vl(T=0) == INV
     assert vl(mx=0) == INV and vl(mx=65) == INV and vl(d=96) == UNS
+    x = lambda **kw: lib.elsa_attn_fwd_cross(kw.get("q", p), p, p, p, None, 1, 1, kw.get("nq", 4), kw.get("nk", 8),
+                                             kw.get("d", 64), 0.125, 0, None, 0, None)
+    assert x(q=None) == INV and x(nq=0) == INV and x(nk=0) == INV and x(nk=-3) == INV and x(d=96) == UNS
+    assert x(nq=1, nk=1 << 24, d=128) == UNS   # the key slice, not the query count, sets the limit

@@ -1,0 +1,122 @@
+"""GPU parity of rectangular attention (n_q != n_k: cross-attention, chunked prefill, decoding)
+through the C ABI, against the FP64 oracle, for every kernel family and both I/O types."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_23798_amd import inputs
+from tests import gpu_util as G
+from tests.parity import assert_parity, tolerance
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not G.have_gpu():
+        pytest.skip("no GPU")
+    from paper_2604_23798_amd import elsa  # noqa: F401
+
+
+def _rect(B, H, nq, nk, d, seed, fp16=False, sigma=1.0):
+    q = inputs.normal(seed, 0, 0, B * H * nq * d, sigma).reshape(B, H, nq, d)
+    k = inputs.normal(seed, 1, 0, B * H * nk * d, sigma).reshape(B, H, nk, d)
+    v = inputs.normal(seed, 2, 0, B * H * nk * d).reshape(B, H, nk, d)
+    if fp16:
+        q, k, v = (t.astype(np.float16) for t in (q, k, v))
+    return q, k, v
+
+
+def _ref(q, k, v, scale, **kw):
+    f32 = lambda t: t.astype(np.float32)
+    return oracle.cross_rows(f32(q), f32(k), f32(v), scale, **kw)
+
+
+SHAPES = [(1, 777), (5, 300), (37, 2000), (200, 64), (129, 131), (64, 1100), (300, 333)]
+KERNELS = [(2, v) for v in range(1, 9)] + [(1, 1), (1, 2)]
+
+
+@pytest.mark.parametrize("path,variant", KERNELS)
+@pytest.mark.parametrize("causal", [False, True])
+def test_fp32_kernels_on_rectangular_problems(path, variant, causal):
+    for (nq, nk) in SHAPES:
+        for d in (64, 128) if (nq + nk) % 2 else (64,):
+            q, k, v = _rect(2, 3, nq, nk, d, 100 + nq)
+            ref, _ = _ref(q, k, v, d ** -0.5, causal=causal)
+            with G.Options(path=path, variant=variant):
+                out = G.fwd_cross(q, k, v, d ** -0.5, causal=causal)
+            assert_parity(out, ref, tolerance(max(nq, nk), False), "cross p%d v%d %dx%d d%d c%d" % (path, variant, nq, nk, d, causal))
+
+
+@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("causal", [False, True])
+def test_fp16_matrix_core_kernels_on_rectangular_problems(variant, causal):
+    for (nq, nk) in SHAPES:
+        for d in (32, 64, 128):
+            q, k, v = _rect(1, 4, nq, nk, d, 200 + nk, fp16=True)
+            ref, _ = _ref(q, k, v, d ** -0.5, causal=causal)
+            with G.Options(path=3, variant=variant):
+                out = G.fwd_cross(q, k, v, d ** -0.5, causal=causal)
+            assert_parity(out, ref, tolerance(max(nq, nk), True), "cross f16 v%d %dx%d d%d c%d" % (variant, nq, nk, d, causal))
+
+
+@pytest.mark.parametrize("fp16", [False, True])
+def test_default_configuration_with_padding_and_lse(fp16):
+    B, H, nq, nk, d = 3, 2, 70, 500, 32
+    q, k, v = _rect(B, H, nq, nk, d, 301, fp16=fp16)
+    kv_len = np.array([500, 33, 0], np.int32)
+    for causal in (False, True):
+        ref, ref_lse = _ref(q, k, v, 0.2, causal=causal, kv_len=kv_len)
+        out, lse = G.fwd_cross(q, k, v, 0.2, causal=causal, kv_len=kv_len, want_lse=True)
+        assert_parity(out, ref, tolerance(nk, fp16), "cross padded")
+        vis = np.isfinite(ref_lse)
+        assert np.all(np.isneginf(lse[~vis])) and np.all(out[~vis] == 0)
+        assert np.max(np.abs(lse[vis] - ref_lse[vis])) < (5e-3 if fp16 else 2e-5)
+
+
+def test_more_queries_than_keys_under_the_causal_mask():
+    """n_k < n_q: the first n_q - n_k queries see no key -> zeros, lse = -inf (identity state)."""
+    B, H, nq, nk, d = 1, 2, 150, 40, 64
+    q, k, v = _rect(B, H, nq, nk, d, 302)
+    ref, ref_lse = _ref(q, k, v, 0.125, causal=True)
+    for opts in (dict(), dict(path=2, variant=3), dict(path=1, variant=1)):
+        with G.Options(**opts):
+            out, lse = G.fwd_cross(q, k, v, 0.125, causal=True, want_lse=True)
+        assert_parity(out, ref, tolerance(nq, False), "nk<nq")
+        blind = np.isneginf(ref_lse)
+        assert blind.reshape(B * H, nq)[:, : nq - nk].all() and np.all(out[blind] == 0) and np.all(np.isneginf(lse[blind]))
+
+
+@pytest.mark.parametrize("fp16", [False, True])
+@pytest.mark.parametrize("nq", [1, 4, 48])
+def test_decoding_with_a_lent_workspace_splits_the_key_range(nq, fp16):
+    """Few queries against a long cache: with a workspace the library cuts the keys into chunks,
+    emits one state per chunk and merges them (Prop. 1); the result is that of the single pass."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    B, H, nk, d = 2, 4, 9000, 128
+    q, k, v = _rect(B, H, nq, nk, d, 303 + nq, fp16=fp16)
+    kv_len = np.array([9000, 4097], np.int32)
+    ref, ref_lse = _ref(q, k, v, d ** -0.5, causal=True, kv_len=kv_len)
+    single = G.fwd_cross(q, k, v, d ** -0.5, causal=True, kv_len=kv_len)
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    elsa.elsa_set_workspace(ws)
+    try:
+        out, lse = G.fwd_cross(q, k, v, d ** -0.5, causal=True, kv_len=kv_len, want_lse=True)
+        with G.Options(splits=7):
+            forced = G.fwd_cross(q, k, v, d ** -0.5, causal=True, kv_len=kv_len)
+    finally:
+        elsa.elsa_set_workspace(None)
+    tol = tolerance(nk, fp16)
+    assert_parity(single, ref, tol, "decode single pass")
+    assert_parity(out, ref, tol, "decode split")
+    assert_parity(forced, ref, tol, "decode 7 chunks")
+    assert np.max(np.abs(lse - ref_lse)) < (5e-3 if fp16 else 2e-5)
+
+
+def test_square_call_through_the_rectangular_entry_point_is_bitwise_the_square_entry_point():
+    w = inputs.WORKLOADS["vit_b16_224"]
+    q, k, v, _ = inputs.make(w)
+    a = G.fwd(q, k, v, w.scale, causal=True)
+    b = G.fwd_cross(q, k, v, w.scale, causal=True)
+    assert np.array_equal(a, b)
