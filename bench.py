@@ -9,7 +9,7 @@ the one the headline metric is quoted on: the long-sequence sweep at n = 16384, 
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--path auto|fma|mfma|mfma16]
 
-``--workload`` takes any name of ``paper_2604_23798_amd.inputs.WORKLOADS`` or ``varlen_8x1792``
+``--workload`` takes any name of ``paper_2604_23798_amd.inputs.WORKLOADS``, ``decode_32k[_fp16]`` or ``varlen_8x1792``
 (8 packed sequences with lengths uniform on [256, 1792], H = 12, d = 64; add ``_fp16`` for FP16).
 """
 import argparse
@@ -156,7 +156,20 @@ def main():
         print(json.dumps(scaling_fit(a)))
         return
     varlen = a.workload.startswith("varlen_8x1792")
-    if varlen:
+    decode = a.workload.startswith("decode_32k")
+    if decode:
+        # one new position per sequence against a 32K-token cache, LLaMA-13B head shape
+        fp16 = a.workload.endswith("_fp16")
+        B, H, d, nq, nk = 2, 40, 128, 1, 32768
+        q = inputs.normal(1007, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
+        k = inputs.normal(1007, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
+        v = inputs.normal(1007, 2, 0, B * H * nk * d).reshape(B, H, nk, d)
+        if fp16:
+            q, k, v = (t.astype(np.float16) for t in (q, k, v))
+        scale = float(np.float32(d ** -0.5))
+        flops = 4 * B * H * nq * nk * d
+        causal, kv_len = True, None
+    elif varlen:
         fp16 = a.workload.endswith("_fp16")
         H, d = 12, 64
         q, k, v, cu = inputs.make_varlen(1006, 8, 256, 1792, H=H, d=d, fp16=fp16)
@@ -184,7 +197,10 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
 
-    if varlen:
+    if decode:
+        def step():
+            elsa.elsa_attn_fwd_cross(tq, tk, tv, out, scale, causal, tl)
+    elif varlen:
         def step():
             elsa.elsa_attn_fwd_varlen(tq, tk, tv, out, tcu, int(lens.max()), scale, causal)
     else:
@@ -234,7 +250,18 @@ def main():
                      "frac": achieved / peak, "traffic": MEASURED_TRAFFIC.get((name, kernel)),
                      "kernel_ms": ms_kernel},
     }
-    if varlen:
+    if decode:
+        # every K and V element is read once: the kernel is bound by HBM, not by the matrix cores
+        kv_bytes = 2.0 * B * H * nk * d * (2 if fp16 else 4)
+        rec["metric"] = "decode attention: K/V cache bytes consumed per second"
+        rec["value"], rec["unit"] = kv_bytes / (ms_step * 1e-3) / 1e9, "GB/s"
+        rec["roofline"] = {"bound": "hbm", "achieved": kv_bytes / (ms_kernel * 1e-3) / 1e9, "peak": 8000.0,
+                           "unit": "GB/s", "frac": kv_bytes / (ms_kernel * 1e-3) / 1e9 / 8000.0, "traffic": None,
+                           "kernel_ms": ms_kernel}
+        rec["config"].update({"B": B, "H": H, "n_q": nq, "n_k": nk, "d": d})
+        rec["tokens_per_s"] = B * nq / (ms_step * 1e-3)
+        del rec["pct_of_fp32_peak"]
+    elif varlen:
         rec["config"].update({"num_seqs": 8, "lengths": [int(x) for x in lens], "H": H, "d": d})
         rec["tokens_per_s"] = float(lens.sum()) / (ms_step * 1e-3)
     else:
@@ -243,7 +270,18 @@ def main():
             rec["causal_effective_tflops"] = 4.0 * w.B * w.H * w.d * (w.n * (w.n + 1) / 2) / (ms_step * 1e-3) / 1e12
     if a.oracle_rows > 0:
         host = out.double().cpu().numpy()
-        if varlen:
+        if decode:
+            import oracle
+            t0 = time.perf_counter()
+            f32 = lambda x: x.astype(np.float32)
+            rows = np.arange(0, B * H, 5, dtype=np.int64)          # one (batch, head) in five
+            ref, _ = oracle.cross_rows(f32(q), f32(k), f32(v), scale, causal=True, rows=rows)
+            dt = time.perf_counter() - t0
+            err = np.linalg.norm(host.reshape(-1, d)[rows] - ref, axis=1) / np.linalg.norm(ref, axis=1)
+            base = {"value": rows.size * 2.0 * nk * d * (2 if fp16 else 4) / dt / 1e9, "unit": "GB/s", "cores": 1,
+                    "kind": "oracle", "sample": "%d of %d (batch, head) rows, all %d keys" % (rows.size, B * H, nk)}
+            par = {"rows": int(rows.size), "e_row": float(err.max())}
+        elif varlen:
             base, par = cpu_baseline_varlen(q, k, v, cu, scale, host, fp16)
         else:
             base, par = cpu_baseline(w, q, k, v, kv_len, host, a.oracle_rows)

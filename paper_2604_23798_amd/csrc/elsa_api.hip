@@ -69,11 +69,21 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     int path = g.opt[ELSA_OPT_PATH];
     if (path == 0) path = (dtype == ELSA_F16 && scale != 0.f) ? 3 : 2;
     if (path == 3 && (dtype != ELSA_F16 || scale == 0.f)) return ELSA_ERR_UNSUPPORTED;
+    // one to four queries per (batch, head): the vector kernel that streams K and V once
+    int decode_variant = 0;
+    if (g.opt[ELSA_OPT_PATH] == 0 && g.opt[ELSA_OPT_VARIANT] == 0 && !cu_seqlens && n <= 4) {
+        path = 1;
+        decode_variant = n == 1 ? 3 : 4;
+    }
+    if (path == 1 && (g.opt[ELSA_OPT_VARIANT] == 3 || g.opt[ELSA_OPT_VARIANT] == 4)) {
+        if (cu_seqlens) return ELSA_ERR_UNSUPPORTED;
+        decode_variant = g.opt[ELSA_OPT_VARIANT];
+    }
     // the K/V slice of one (sequence, head) is addressed through a 31-bit buffer range
     const long long tok_stride = cu_seqlens ? (long long)H * d : d;
     const long long longest = cu_seqlens ? total_tokens : (nk > n ? nk : n);
-    if (path != 1 && longest * tok_stride * (dtype == ELSA_F16 ? 2 : 4) >= 0x7fffffffLL) return ELSA_ERR_UNSUPPORTED;
-    int variant = pick_variant(path, (long long)B * H, n, d, num_splits);
+    if ((path != 1 || decode_variant) && longest * tok_stride * (dtype == ELSA_F16 ? 2 : 4) >= 0x7fffffffLL) return ELSA_ERR_UNSUPPORTED;
+    int variant = decode_variant ? decode_variant : pick_variant(path, (long long)B * H, n, d, num_splits);
     if (path == 2) {
         const bool ok = small_kernel_ok(cu_seqlens, num_splits, emit, n, nk);
         if (g.opt[ELSA_OPT_VARIANT] == 0 && ok && n <= 128 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu)

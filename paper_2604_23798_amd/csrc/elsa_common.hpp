@@ -193,6 +193,7 @@ int launch_fwd_mfma(const FwdParams &p, int d, int f16, int variant, hipStream_t
 int launch_fwd_fma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name);
 int launch_fwd_mfma16(const FwdParams &p, int d, int variant, hipStream_t s, const char **name);
 int launch_fwd_mfma_small(const FwdParams &p, int d, int f16, int nq, hipStream_t s);
+int launch_fwd_decode(const FwdParams &p, int d, int f16, int nq, hipStream_t s);
 int launch_combine(const CombineParams &p, int d, hipStream_t s);
 int launch_probe(float *out, hipStream_t s);
 int mfma_variant_tq(int variant, int d);   // queries per block of a variant (0 if unknown)
@@ -202,7 +203,7 @@ const char *mfma16_variant_name(int variant);
 const char *mfma_variant_name(int variant);
 const char *fma_variant_name(int variant);
 constexpr int kMfmaVariants = 10;
-constexpr int kFmaVariants = 2;
+constexpr int kFmaVariants = 4;
 constexpr int kMfma16Variants = 3;
 
 }  // namespace elsa

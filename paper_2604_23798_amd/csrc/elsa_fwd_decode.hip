@@ -1,0 +1,233 @@
+// ELSA forward for a handful of queries against a long key range (decoding against a cache,
+// speculative steps): FP32 vector arithmetic, bound by the HBM reads of K and V.
+//
+// With one to four queries a 32-column matrix-core tile would spend 1/32 .. 1/8 of its work on
+// real rows, so this kernel forms the scores on the vector ALU instead.  A key row of d elements
+// is spread over LPR = d/8 lanes (8 columns each), so one wave instruction reads 64/LPR whole
+// consecutive rows, fully coalesced; a lane multiplies its 8 columns into the query, the LPR
+// lanes of a key add their partial sums with DPP row operations (no LDS), and every lane folds
+// the (key, score) pair into its OWN monoid state (m, S, W[8 columns]) with the merge operator of
+// Eq. 3.  Lanes, waves and -- through the chunk states of Prop. 1 -- blocks cover disjoint key
+// subsets; the states of one block meet in LDS at the end, those of different blocks in the
+// combine kernel.
+#include "elsa_common.hpp"
+
+namespace elsa {
+
+namespace {
+
+template <int CTRL> __device__ __forceinline__ float dpp_get(float x) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
+// sum over the LPR (4, 8 or 16) consecutive lanes of a key; every lane of the group gets the sum
+template <int LPR> __device__ __forceinline__ float group_sum(float x) {
+    x += dpp_get<0xB1>(x);                          // quad_perm [1,0,3,2]
+    x += dpp_get<0x4E>(x);                          // quad_perm [2,3,0,1]: quads are uniform now
+    if constexpr (LPR >= 8) x += dpp_get<0x141>(x);  // row_half_mirror: the other quad of each 8
+    if constexpr (LPR >= 16) x += dpp_get<0x140>(x); // row_mirror: the other 8 of each 16
+    return x;
+}
+
+template <typename T> struct Row8;   // 8 consecutive elements of a row, widened to float
+template <> struct Row8<float> {
+    static __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, int voff, int soff, float *o) {
+        const f32x4 a = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
+        const f32x4 b = __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff + 16, soff, 0));
+#pragma unroll
+        for (int t = 0; t < 4; ++t) { o[t] = a[t]; o[4 + t] = b[t]; }
+    }
+};
+template <> struct Row8<_Float16> {
+    static __device__ __forceinline__ void load(__amdgpu_buffer_rsrc_t r, int voff, int soff, float *o) {
+        const f16x8 a = __builtin_bit_cast(f16x8, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
+#pragma unroll
+        for (int t = 0; t < 8; ++t) o[t] = (float)a[t];
+    }
+};
+
+}  // namespace
+
+template <int D, typename T, int NQ>
+__global__ __launch_bounds__(256) void fwd_decode_kernel(FwdParams p) {
+    constexpr int LPR = D / 8;           // lanes per key row
+    constexpr int KPI = 64 / LPR;        // keys per wave instruction
+    constexpr int U = 4;                 // key groups in flight per wave
+    constexpr int ES = (int)sizeof(T);
+    constexpr int NS = 10;               // floats of state per (lane, query): m, S, W[8]
+    __shared__ float st[4 * 64 * NQ * NS];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cs = lane % LPR, ksub = lane / LPR;
+
+    const Work wi = decode_work<D>(p);   // dense layout only (checked by the launcher)
+    if (!wi.valid) return;               // uniform over the block
+    const int c = wi.c;
+    const long long bh = wi.bh;
+    const int n = wi.n;
+    const int coff = wi.coff;
+    int L = wi.nk;
+    if (p.kv_len) L = min(max(p.kv_len[bh / p.H], 0), wi.nk);
+    const int q0 = wi.qt * NQ;
+    const int kbeg = c * p.chunk;
+    int kend = min(kbeg + p.chunk, L);
+    if (p.causal) kend = min(kend, q0 + NQ + coff);
+
+    float qr[NQ][8];
+    int lim[NQ];                         // first key the query cannot see
+#pragma unroll
+    for (int iq = 0; iq < NQ; ++iq) {
+        const int row = q0 + iq;
+        f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = a;
+        if (row < n) {
+            a = Io<T>::load4(p.q, wi.base + (long long)row * D + 8 * cs);
+            b = Io<T>::load4(p.q, wi.base + (long long)row * D + 8 * cs + 4);
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) { qr[iq][t] = a[t] * p.qscale; qr[iq][4 + t] = b[t] * p.qscale; }
+        lim[iq] = p.causal ? min(kend, row + 1 + coff) : kend;
+    }
+    int lim_min = lim[0];
+#pragma unroll
+    for (int iq = 1; iq < NQ; ++iq) lim_min = min(lim_min, lim[iq]);
+
+    float m[NQ], S[NQ], W[NQ][8];
+#pragma unroll
+    for (int iq = 0; iq < NQ; ++iq) {
+        m[iq] = -INFINITY;
+        S[iq] = 0.f;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) W[iq][t] = 0.f;
+    }
+
+    // rows at or beyond kend read as zero and are masked
+    const long long slice_bytes = kend > 0 ? (long long)kend * D * ES : 0;
+    const __amdgpu_buffer_rsrc_t krs = make_rsrc(static_cast<const T *>(p.k) + wi.kbase, slice_bytes);
+    const __amdgpu_buffer_rsrc_t vrs = make_rsrc(static_cast<const T *>(p.v) + wi.kbase, slice_bytes);
+    const int voff = (ksub * D + 8 * cs) * ES;
+
+    // the four waves take turns on runs of U key groups, so that the block reads one contiguous
+    // stream of 4*U*KPI rows per round
+    const int ngroups = kend > kbeg ? (kend - kbeg + KPI - 1) / KPI : 0;
+    for (int g0 = wave * U; g0 < ngroups; g0 += 4 * U) {
+        float kf[U][8], vf[U][8];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            // groups past the chunk start at or beyond kend: every lane reads zeros there
+            const int key0 = min(kbeg + (g0 + u) * KPI, kend);
+            const int soff = key0 * D * ES;
+            Row8<T>::load(krs, voff, soff, kf[u]);
+            Row8<T>::load(vrs, voff, soff, vf[u]);
+        }
+        const bool need_mask = kbeg + (g0 + U) * KPI > lim_min;
+#pragma unroll
+        for (int iq = 0; iq < NQ; ++iq) {
+            float s[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float acc = qr[iq][0] * kf[u][0];
+#pragma unroll
+                for (int t = 1; t < 8; ++t) acc = fmaf(qr[iq][t], kf[u][t], acc);
+                s[u] = group_sum<LPR>(acc);
+            }
+            if (need_mask) {
+#pragma unroll
+                for (int u = 0; u < U; ++u)
+                    if (kbeg + (g0 + u) * KPI + ksub >= lim[iq]) s[u] = -INFINITY;
+            }
+            float mt = s[0];
+#pragma unroll
+            for (int u = 1; u < U; ++u) mt = fmaxf(mt, s[u]);
+            const float mnew = fmaxf(m[iq], mt);
+            const float msafe = (mnew == -INFINITY) ? 0.f : mnew;   // identity (+) identity = identity
+            const float alpha = exp2_fast(m[iq] - msafe);
+            m[iq] = mnew;
+            float e[U], ps = 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                e[u] = exp2_fast(s[u] - msafe);
+                ps += e[u];
+            }
+            S[iq] = S[iq] * alpha + ps;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                float w = W[iq][t] * alpha;
+#pragma unroll
+                for (int u = 0; u < U; ++u) w = fmaf(e[u], vf[u][t], w);
+                W[iq][t] = w;
+            }
+        }
+    }
+
+    // ---- the 4 * KPI lane states that share a column slice meet in LDS
+#pragma unroll
+    for (int iq = 0; iq < NQ; ++iq) {
+        float *dst = &st[((wave * 64 + lane) * NQ + iq) * NS];
+        dst[0] = m[iq];
+        dst[1] = S[iq];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) dst[2 + t] = W[iq][t];
+    }
+    __syncthreads();
+    if (tid >= LPR * NQ) return;
+    const int iq = tid / LPR, cs2 = tid % LPR;
+    const int row = q0 + iq;
+    if (row >= n) return;
+    float ma = -INFINITY, Sa = 0.f, Wa[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) Wa[t] = 0.f;
+    for (int w = 0; w < 4; ++w)
+        for (int ks = 0; ks < KPI; ++ks) {
+            const float *src = &st[((w * 64 + ks * LPR + cs2) * NQ + iq) * NS];
+            const float mb = src[0], Sb = src[1];
+            const float mnew = fmaxf(ma, mb);
+            const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+            const float fa = exp2_fast(ma - msafe), fb = exp2_fast(mb - msafe);
+            ma = mnew;
+            Sa = Sa * fa + Sb * fb;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) Wa[t] = Wa[t] * fa + src[2 + t] * fb;
+        }
+    if (p.emit_partials) {
+        const long long prow = (bh * p.num_splits + c) * (long long)n + row;
+        if (cs2 == 0) {
+            p.part_m[prow] = p.m_natural ? ma * kLn2 : ma;
+            p.part_S[prow] = Sa;
+        }
+        Io<float>::store4(p.part_W, prow * D + 8 * cs2, f32x4{Wa[0], Wa[1], Wa[2], Wa[3]});
+        Io<float>::store4(p.part_W, prow * D + 8 * cs2 + 4, f32x4{Wa[4], Wa[5], Wa[6], Wa[7]});
+    } else {
+        const float f = Sa > 0.f ? 1.f / Sa : 0.f;
+        if (p.lse && cs2 == 0) p.lse[bh * (long long)n + row] = lse_of(ma, Sa);
+        const long long o = wi.base + (long long)row * D + 8 * cs2;
+        Io<T>::store4(p.out, o, f32x4{Wa[0] * f, Wa[1] * f, Wa[2] * f, Wa[3] * f});
+        Io<T>::store4(p.out, o + 4, f32x4{Wa[4] * f, Wa[5] * f, Wa[6] * f, Wa[7] * f});
+    }
+}
+
+template <int D, typename T, int NQ>
+static int launch_decode_one(const FwdParams &p, hipStream_t s) {
+    const long long total = (long long)p.q_tiles * p.B * p.H * p.num_splits;
+    long long blocks = total;
+    if (p.xcd_map == 2) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((fwd_decode_kernel<D, T, NQ>), dim3((unsigned)blocks), dim3(256), 0, s, p);
+    return (int)hipGetLastError();
+}
+
+template <int D, typename T>
+static int launch_decode_d(const FwdParams &p, int nq, hipStream_t s) {
+    return nq == 1 ? launch_decode_one<D, T, 1>(p, s) : launch_decode_one<D, T, 4>(p, s);
+}
+
+// nq = 1 or 4 queries per block (p.tq must say the same).  Dense layout only.
+int launch_fwd_decode(const FwdParams &p, int d, int f16, int nq, hipStream_t s) {
+    if (p.cu_seqlens || (nq != 1 && nq != 4) || p.tq != nq) return (int)hipErrorInvalidValue;
+    if (d == 32) return f16 ? launch_decode_d<32, _Float16>(p, nq, s) : launch_decode_d<32, float>(p, nq, s);
+    if (d == 64) return f16 ? launch_decode_d<64, _Float16>(p, nq, s) : launch_decode_d<64, float>(p, nq, s);
+    if (d == 128) return f16 ? launch_decode_d<128, _Float16>(p, nq, s) : launch_decode_d<128, float>(p, nq, s);
+    return (int)hipErrorInvalidValue;
+}
+
+}  // namespace elsa

@@ -120,3 +120,55 @@ def test_square_call_through_the_rectangular_entry_point_is_bitwise_the_square_e
     a = G.fwd(q, k, v, w.scale, causal=True)
     b = G.fwd_cross(q, k, v, w.scale, causal=True)
     assert np.array_equal(a, b)
+
+
+# ---- the vector kernel for one to four queries (decoding) --------------------------------------
+@pytest.mark.parametrize("fp16", [False, True])
+@pytest.mark.parametrize("d", [32, 64, 128])
+def test_decode_kernel_shapes_masks_and_chunks(d, fp16):
+    import torch
+    from paper_2604_23798_amd import elsa
+    ws = torch.empty(32 << 20, dtype=torch.uint8, device="cuda")
+    for nq, nk in [(1, 1), (1, 5), (2, 64), (1, 777), (3, 1000), (4, 4100), (7, 130), (4, 3)]:
+        B, H = 2, 3
+        q, k, v = _rect(B, H, nq, nk, d, 400 + nq + nk, fp16=fp16)
+        kv_len = np.array([nk, max(0, nk // 3)], np.int32)
+        for causal in (False, True):
+            for kl in (None, kv_len):
+                ref, ref_lse = _ref(q, k, v, d ** -0.5, causal=causal, kv_len=kl)
+                vis = np.isfinite(ref_lse)
+                for variant in (3, 4):
+                    for splits in (0, 3):
+                        if splits > nk:
+                            continue
+                        elsa.elsa_set_workspace(ws if splits else None)
+                        try:
+                            with G.Options(path=1, variant=variant, splits=splits):
+                                out, lse = G.fwd_cross(q, k, v, d ** -0.5, causal=causal, kv_len=kl, want_lse=True)
+                                assert elsa.elsa_last_kernel() == ("fma_decode_q1" if variant == 3 else "fma_decode_q4")
+                        finally:
+                            elsa.elsa_set_workspace(None)
+                        what = "decode v%d %dx%d d%d c%d pad%d s%d" % (variant, nq, nk, d, causal, kl is not None, splits)
+                        assert_parity(out, ref, tolerance(nk, fp16), what)
+                        assert np.all(out[~vis] == 0) and np.all(np.isneginf(lse[~vis])), what
+                        assert np.max(np.abs(lse[vis] - ref_lse[vis]), initial=0.0) < (5e-3 if fp16 else 2e-5), what
+
+
+@pytest.mark.parametrize("nq,name", [(1, "fma_decode_q1"), (3, "fma_decode_q4"), (4, "fma_decode_q4"), (5, None)])
+def test_decode_kernel_is_the_default_for_up_to_four_queries(nq, name):
+    from paper_2604_23798_amd import elsa
+    q, k, v = _rect(1, 8, nq, 2048, 64, 500 + nq)
+    ref, _ = _ref(q, k, v, 0.125, causal=True)
+    out = G.fwd_cross(q, k, v, 0.125, causal=True)
+    assert_parity(out, ref, tolerance(2048, False), "default decode nq=%d" % nq)
+    last = elsa.elsa_last_kernel()
+    assert last == name if name else not last.startswith("fma_decode")
+
+
+def test_decode_kernel_wide_scores():
+    """Scores spread over hundreds of units (sigma = 8 inputs): the lane states must merge without overflow."""
+    q, k, v = _rect(1, 4, 1, 6000, 64, 600, sigma=8.0)
+    ref, _ = _ref(q, k, v, 0.125)
+    out = G.fwd_cross(q, k, v, 0.125)
+    assert np.all(np.isfinite(out))
+    assert_parity(out, ref, tolerance(6000, False), "decode wide")
