@@ -41,8 +41,10 @@ int variant_tq(int path, int variant, int d) {
 // within 2 % of the fastest configuration at every size while using two score chains; d = 128
 // uses the 128-row tile [1]; when fewer than 192 such blocks exist, the configuration whose waves
 // split the key range [3].  The 256-row tiles [2, 4] are opt-in.
-int pick_variant(int path, long long BH, int n, int d, int splits) {
+int pick_variant(int path, long long BH, int n, int nk, int d, int splits) {
     if (g.opt[ELSA_OPT_VARIANT] >= 1 && g.opt[ELSA_OPT_VARIANT] <= variant_count(path)) return g.opt[ELSA_OPT_VARIANT];
+    // one query tile against a long key range: the waves of a block split the keys, not the queries
+    if (path != 1 && (long long)n * 8 <= nk && n <= variant_tq(path, 3, d)) return 3;
     if (path == 1) {
         const long long blocks = BH * ((n + 255) / 256) * splits;
         return blocks >= kNumCu ? 1 : 2;
@@ -83,7 +85,7 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     const long long tok_stride = cu_seqlens ? (long long)H * d : d;
     const long long longest = cu_seqlens ? total_tokens : (nk > n ? nk : n);
     if ((path != 1 || decode_variant) && longest * tok_stride * (dtype == ELSA_F16 ? 2 : 4) >= 0x7fffffffLL) return ELSA_ERR_UNSUPPORTED;
-    int variant = decode_variant ? decode_variant : pick_variant(path, (long long)B * H, n, d, num_splits);
+    int variant = decode_variant ? decode_variant : pick_variant(path, (long long)B * H, n, nk, d, num_splits);
     if (path == 2) {
         const bool ok = small_kernel_ok(cu_seqlens, num_splits, emit, n, nk);
         if (g.opt[ELSA_OPT_VARIANT] == 0 && ok && n <= 128 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu)
@@ -134,18 +136,22 @@ void carve(void *ws, int B, int H, int n, int d, int C, float **pm, float **pS, 
 }
 
 // Number of key chunks for elsa_attn_fwd when a workspace is lent: enough 128-row blocks for
-// two per CU, chunks no shorter than 256 keys, at most 8, and only if the workspace holds them.
+// two per CU, chunks no shorter than 256 keys, at most 8 (64 when decoding), and only if the
+// workspace holds them.
 int auto_splits(int B, int H, int n, int nk, int d) {
     int C = g.opt[ELSA_OPT_SPLITS];
     if (C <= 0) {
         const long long blocks = (long long)B * H * ((n + 127) / 128);
         C = 1;
-        if (blocks < 2 * kNumCu) {
-            C = (int)((2 * kNumCu + blocks - 1) / blocks);
+        // few queries against many keys (decoding): the key range is the only parallelism; about
+        // five blocks per CU measured best there (two suffice when query tiles share the work)
+        const bool few_q = (long long)n * 8 <= nk;
+        const int want = few_q ? 5 * kNumCu : 2 * kNumCu;
+        if (blocks < want) {
+            C = (int)((want + blocks - 1) / blocks);
             const int cap = nk / 256 > 1 ? nk / 256 : 1;
             if (C > cap) C = cap;
-            // few queries against many keys (decoding): the key range is the only parallelism
-            const int most = n * 8 <= nk ? 64 : 8;
+            const int most = few_q ? 64 : 8;
             if (C > most) C = most;
         }
     }
