@@ -27,7 +27,8 @@ PEAK_FP32_VALU_UNPACKED = 78.6  # plain v_fma_f32 (packed FP32 is disabled in th
 PEAK_FP16_TFLOPS = 2500.0       # MI355X dense FP16 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for a plain copy of known size in the same run (profiles/*_counters.md).
-MEASURED_TRAFFIC = {("sweep_n16384", "mfma_q128_k32"): 1.156e9, ("sweep_n16384", "mfma_q256_w4"): 6.606e8}
+MEASURED_TRAFFIC = {("sweep_n16384", "mfma_q128_k32"): 1.156e9, ("sweep_n16384", "mfma_q256_w4"): 6.606e8,
+                    ("decode_32k", "fma_decode_q1"): 2.824e9}
 
 
 def cpu_baseline(w, q, k, v, kv_len, gpu_out, budget_rows):
@@ -135,6 +136,8 @@ def main():
     ap.add_argument("--pre-warm-ms", type=float, default=0.0,
                     help="run untimed steps for this long before the W warm-up steps (short workloads otherwise "
                          "run before the GPU clocks have ramped up)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph and time replays (launch-bound workloads)")
     ap.add_argument("--scaling-fit", action="store_true",
                     help="instead of one workload: per-head latency for n = 2^10..2^15 (H=16, d=64) and the "
                          "least-squares fit T(n) = a*L(n,128) + b*n^2 + c of the paper's scaling study")
@@ -207,6 +210,19 @@ def main():
         def step():
             elsa.elsa_attn_fwd_masked(tq, tk, tv, out, scale, causal, tl)
 
+    if a.graph:
+        eager_step = step
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            eager_step()                       # first launch outside the capture
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            eager_step()
+        step = graph.replay
+
     if a.pre_warm_ms > 0:
         tw = time.perf_counter()
         while (time.perf_counter() - tw) * 1e3 < a.pre_warm_ms:
@@ -245,7 +261,7 @@ def main():
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 io / f32 state" if fp16 else "f32", "data": "synthetic",
         "pct_of_fp32_peak": 100.0 * value / PEAK_FP32_TFLOPS,
-        "config": {"workload": name, "causal": bool(causal), "kernel": kernel, "path": a.path},
+        "config": {"workload": name, "causal": bool(causal), "kernel": kernel, "path": a.path, "graph": bool(a.graph)},
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": MEASURED_TRAFFIC.get((name, kernel)),
                      "kernel_ms": ms_kernel},
@@ -256,7 +272,8 @@ def main():
         rec["metric"] = "decode attention: K/V cache bytes consumed per second"
         rec["value"], rec["unit"] = kv_bytes / (ms_step * 1e-3) / 1e9, "GB/s"
         rec["roofline"] = {"bound": "hbm", "achieved": kv_bytes / (ms_kernel * 1e-3) / 1e9, "peak": 8000.0,
-                           "unit": "GB/s", "frac": kv_bytes / (ms_kernel * 1e-3) / 1e9 / 8000.0, "traffic": None,
+                           "unit": "GB/s", "frac": kv_bytes / (ms_kernel * 1e-3) / 1e9 / 8000.0,
+                           "traffic": MEASURED_TRAFFIC.get((name, kernel)),
                            "kernel_ms": ms_kernel}
         rec["config"].update({"B": B, "H": H, "n_q": nq, "n_k": nk, "d": d})
         rec["tokens_per_s"] = B * nq / (ms_step * 1e-3)

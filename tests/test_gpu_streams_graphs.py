@@ -1,0 +1,87 @@
+"""The entry points neither allocate nor synchronise, so they can run on any stream and be
+captured into a HIP graph.  Every replay is checked against the eager result, with eager work and
+synchronisations of the program between the replays."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_23798_amd import inputs
+from tests import gpu_util as G
+from tests.parity import assert_parity, tolerance
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not G.have_gpu():
+        pytest.skip("no GPU")
+    from paper_2604_23798_amd import elsa  # noqa: F401
+
+
+def test_side_stream_matches_default_stream():
+    import torch
+    from paper_2604_23798_amd import elsa
+    w = inputs.WORKLOADS["vit_b16_224"]
+    q, k, v, _ = inputs.make(w)
+    tq, tk, tv = G.to_dev(q), G.to_dev(k), G.to_dev(v)
+    a = torch.empty_like(tq)
+    elsa.elsa_attn_fwd(tq, tk, tv, a, w.scale, True)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()              # default priority
+    b = torch.full_like(tq, float("nan"))
+    with torch.cuda.stream(side):
+        elsa.elsa_attn_fwd(tq, tk, tv, b, w.scale, True)
+    side.synchronize()
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("case", ["single_pass", "split_and_combine", "decode"])
+def test_graph_capture_and_replays(case):
+    import torch
+    from paper_2604_23798_amd import elsa
+    if case == "decode":
+        B, H, nq, nk, d = 2, 4, 1, 5000, 64
+        q = inputs.normal(77, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
+        k = inputs.normal(77, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
+        v = inputs.normal(77, 2, 0, B * H * nk * d).reshape(B, H, nk, d)
+        scale, n = 0.125, nk
+        ref, _ = oracle.cross_rows(q, k, v, scale, causal=True)
+        call = lambda tq, tk, tv, out: elsa.elsa_attn_fwd_cross(tq, tk, tv, out, scale, True)
+    else:
+        w = inputs.sweep(1024)
+        q, k, v, _ = inputs.make(w)
+        scale, n = w.scale, w.n
+        rows = inputs.sample_rows(w, per_head=8)
+        ref = oracle.attn_rows(q, k, v, scale, rows=rows)
+        call = lambda tq, tk, tv, out: elsa.elsa_attn_fwd(tq, tk, tv, out, scale, False)
+    tq, tk, tv = G.to_dev(q), G.to_dev(k), G.to_dev(v)
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda") if case != "single_pass" else None
+    elsa.elsa_set_workspace(ws)
+    try:
+        eager = torch.empty_like(tq)
+        call(tq, tk, tv, eager)
+        torch.cuda.synchronize()
+        out = torch.full_like(tq, float("nan"))
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            call(tq, tk, tv, out)               # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            call(tq, tk, tv, out)
+        for rep in range(4):
+            out.fill_(float("nan"))
+            scratch = torch.randn(1 << 16, device="cuda").sum().item()   # eager work + a sync in between
+            assert np.isfinite(scratch)
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(out, eager), "replay %d differs from the eager result" % rep
+    finally:
+        elsa.elsa_set_workspace(None)
+    got = out.reshape(-1, q.shape[-1]).double().cpu().numpy()
+    if case != "decode":
+        got = got[rows]
+    assert_parity(got, ref, tolerance(n, False), "graph " + case)
