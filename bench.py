@@ -132,7 +132,7 @@ def main():
     ap.add_argument("--path", default="auto", choices=["auto", "fma", "mfma", "mfma16"])
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--xcd-map", type=int, default=0)
-    ap.add_argument("--oracle-rows", type=int, default=4096, help="row budget of the cpu_baseline leg (0 = skip)")
+    ap.add_argument("--oracle-rows", type=int, default=16384, help="row budget of the cpu_baseline leg (0 = skip)")
     ap.add_argument("--pre-warm-ms", type=float, default=0.0,
                     help="run untimed steps for this long before the W warm-up steps (short workloads otherwise "
                          "run before the GPU clocks have ramped up)")
@@ -243,6 +243,17 @@ def main():
     ms_step = wall * 1e3 / a.steps
     ms_kernel = ev0.elapsed_time(ev1) / a.steps
     kernel = elsa.elsa_last_kernel()
+    # per-launch spread, from a second pass with one event pair per step (not part of the figure above)
+    n_lat = max(a.steps, 20)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_lat + 1)]
+    evs[0].record()
+    for i in range(n_lat):
+        step()
+        evs[i + 1].record()
+    torch.cuda.synchronize()
+    lat = np.sort(np.array([evs[i].elapsed_time(evs[i + 1]) for i in range(n_lat)]))
+    latency = {"median": float(np.median(lat)), "p10": float(lat[int(0.1 * (n_lat - 1))]),
+               "p90": float(lat[int(0.9 * (n_lat - 1))]), "launches": n_lat}
 
     # flops: 4 B H n^2 d, the square count the metric is defined on (sum of len^2 for packed batches)
     value = flops / (ms_step * 1e-3) / 1e12
@@ -265,6 +276,7 @@ def main():
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": MEASURED_TRAFFIC.get((name, kernel)),
                      "kernel_ms": ms_kernel},
+        "latency_ms": latency,
     }
     if decode:
         # every K and V element is read once: the kernel is bound by HBM, not by the matrix cores
@@ -283,6 +295,8 @@ def main():
         rec["tokens_per_s"] = float(lens.sum()) / (ms_step * 1e-3)
     else:
         rec["config"].update({"B": w.B, "H": w.H, "n": w.n, "d": w.d, "padded": w.padded})
+        if kv_len is not None:         # the nominal figure counts padded keys; this one only the visible ones
+            rec["visible_keys_tflops"] = 4.0 * w.H * w.n * w.d * float(np.minimum(kv_len, w.n).sum()) / (ms_step * 1e-3) / 1e12
         if w.causal:
             rec["causal_effective_tflops"] = 4.0 * w.B * w.H * w.d * (w.n * (w.n + 1) / 2) / (ms_step * 1e-3) / 1e12
     if a.oracle_rows > 0:

@@ -136,7 +136,7 @@ void carve(void *ws, int B, int H, int n, int d, int C, float **pm, float **pS, 
 }
 
 // Number of key chunks for elsa_attn_fwd when a workspace is lent: enough 128-row blocks for
-// two per CU, chunks no shorter than 256 keys, at most 8 (64 when decoding), and only if the
+// one per CU, chunks no shorter than 256 keys, at most 8 (64 when decoding), and only if the
 // workspace holds them.
 int auto_splits(int B, int H, int n, int nk, int d) {
     int C = g.opt[ELSA_OPT_SPLITS];
@@ -144,11 +144,14 @@ int auto_splits(int B, int H, int n, int nk, int d) {
         const long long blocks = (long long)B * H * ((n + 127) / 128);
         C = 1;
         // few queries against many keys (decoding): the key range is the only parallelism; about
-        // five blocks per CU measured best there (two suffice when query tiles share the work)
+        // five blocks per CU measured best there.  Otherwise one block per CU: every further cut
+        // adds prologue, state traffic and combine work without adding matrix-core throughput
+        // (measured at n = 1024, H = 16: 2 chunks 47.5 us, 4 chunks 51 us, none 77 us).
         const bool few_q = (long long)n * 8 <= nk;
-        const int want = few_q ? 5 * kNumCu : 2 * kNumCu;
-        if (blocks < want) {
+        const int want = few_q ? 5 * kNumCu : kNumCu;
+        if (blocks <= want) {
             C = (int)((want + blocks - 1) / blocks);
+            if (C < 2) C = 2;                    // exactly one block per CU still gains from two chunks
             const int cap = nk / 256 > 1 ? nk / 256 : 1;
             if (C > cap) C = cap;
             const int most = few_q ? 64 : 8;
