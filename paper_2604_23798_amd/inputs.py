@@ -138,6 +138,12 @@ WORKLOADS = {
                         note="window attention: Swin-T stage 1 at 224 px, 7x7 windows, 64 windows x batch 8"),
     "swin_w14": Workload("swin_w14", B=128, H=3, n=196, d=32, seed=1008,
                          note="window attention with 14x14 windows (196 tokens, the largest window size the paper uses)"),
+    "swin_w8": Workload("swin_w8", B=392, H=3, n=64, d=32, seed=1009,
+                        note="window attention, 8x8 windows (W8): 49 windows x batch 8"),
+    "swin_w16": Workload("swin_w16", B=128, H=3, n=256, d=32, seed=1010,
+                         note="window attention, 16x16 windows (W16): 16 windows x batch 8"),
+    "frames_416k": Workload("frames_416k", B=1, H=1, n=416400, d=64, seed=1011,
+                            note="one head at the longest token count the paper mentions (multi-frame input, 416,400 tokens)"),
     "hires_vit_64k": Workload("hires_vit_64k", B=1, H=16, n=65536, d=64, seed=1005, qk_sigma=8.0,
                               note="1024x1024 image, 4x4 patches; wide score range"),
 }

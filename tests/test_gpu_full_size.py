@@ -60,12 +60,26 @@ def test_hires_vit_64k_wide_scores():
     assert m["max_abs"] < 1e-3
 
 
-@pytest.mark.parametrize("name", ["swin_w7", "swin_w14"])
+@pytest.mark.parametrize("name", ["swin_w7", "swin_w8", "swin_w14", "swin_w16"])
 def test_window_attention_shapes(name):
     """Many small independent windows (d = 32): batched tiny problems, every row checked."""
     w = inputs.WORKLOADS[name]
     _check(w, per_head=w.n)
     _check(w.with_(fp16=True, name=name + "_fp16"), per_head=w.n)
+
+
+@pytest.mark.parametrize("fp16", [False, True])
+def test_one_head_at_416400_tokens(fp16):
+    """Far beyond the stated sizes (n is no multiple of any tile): same tolerance as at 64K."""
+    w = inputs.WORKLOADS["frames_416k"]
+    if fp16:
+        w = w.with_(fp16=True, name="frames_416k_fp16")
+    q, k, v, kv_len = inputs.make(w)
+    rows = inputs.sample_rows(w, per_head=64)
+    f32 = lambda t: t.astype(np.float32)
+    ref = oracle.attn_rows(f32(q), f32(k), f32(v), w.scale, rows=rows)
+    out = G.fwd(q, k, v, w.scale, rows=rows)
+    assert_parity(out, ref, 2e-3 if fp16 else 1e-4, w.name)
 
 
 def test_small_workloads_with_workspace_split():
