@@ -7,10 +7,11 @@
  *     never allocates, frees or retains them (except the workspace registered
  *     with elsa_set_workspace, which it borrows until replaced).
  *   - Q, K, V, out are contiguous row-major [B][H][n][d] with d_v == d,
- *     self-attention (n queries, n keys).  d must be 32, 64 or 128.  The K (and V) slice of
- *     one (batch, head) -- one sequence of a packed batch -- must span less than 2 GiB
- *     (n*d*sizeof(element), or total_tokens*H*d*sizeof(element) for the packed layout);
- *     larger problems return ELSA_ERR_UNSUPPORTED on the matrix-core paths.
+ *     self-attention (n queries, n keys) except for elsa_attn_fwd_cross.  d must be 32, 64 or
+ *     128.  The K (and V) slice of one (batch, head) -- one sequence of a packed batch -- must
+ *     span less than 2 GiB (n*d*sizeof(element), or total_tokens*H*d*sizeof(element) for the
+ *     packed layout); larger problems return ELSA_ERR_UNSUPPORTED on every path that fetches
+ *     through buffer descriptors (all but the FP32 FMA tiles of ELSA_OPT_PATH = 1).
  *   - dtype: ELSA_F32 = FP32 in/out; ELSA_F16 = IEEE FP16 in/out.  Scores, the
  *     running maximum m, the normaliser S and the weighted sum W are always FP32;
  *     on the default FP16 path the exponentials are rounded to FP16 (nearest even)
@@ -141,7 +142,8 @@ int elsa_set_workspace(void *dev_ptr, size_t bytes);
 
 /*
  * Measurement / tuning knobs (process-wide, not thread-safe).  Defaults are 0.
- *   ELSA_OPT_PATH     0 = auto (FP32 I/O: FP32 MFMA; FP16 I/O: FP16 MFMA with FP32 state),
+ *   ELSA_OPT_PATH     0 = auto (FP32 I/O: FP32 MFMA; FP16 I/O: FP16 MFMA with FP32 state; one to
+ *                     four queries per (batch, head): the FP32 vector kernel that streams K and V),
  *                     1 = FP32 FMA (vector ALU), 2 = FP32 MFMA (FP16 inputs widened to FP32),
  *                     3 = FP16 MFMA (FP16 I/O and scale != 0 only, else ELSA_ERR_UNSUPPORTED)
  *   ELSA_OPT_VARIANT  0 = auto, otherwise a tile configuration id (see elsa_variant_name)
