@@ -136,6 +136,9 @@ def main():
     ap.add_argument("--pre-warm-ms", type=float, default=0.0,
                     help="run untimed steps for this long before the W warm-up steps (short workloads otherwise "
                          "run before the GPU clocks have ramped up)")
+    ap.add_argument("--stream-chunks", type=int, default=0,
+                    help="memory-lean mode: feed K and V in this many equal chunks through elsa_attn_stream_step "
+                         "(eta = 1/chunks) and finish; dense workloads only")
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph and time replays (launch-bound workloads)")
     ap.add_argument("--scaling-fit", action="store_true",
@@ -200,7 +203,19 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
 
-    if decode:
+    if a.stream_chunks > 0:
+        assert not decode and not varlen and kv_len is None and w.n % a.stream_chunks == 0
+        nc = w.n // a.stream_chunks
+        kcs = [tk[:, :, i * nc:(i + 1) * nc].contiguous() for i in range(a.stream_chunks)]
+        vcs = [tv[:, :, i * nc:(i + 1) * nc].contiguous() for i in range(a.stream_chunks)]
+        state = torch.empty(elsa.elsa_stream_state_bytes(w.B, w.H, w.n, w.d), dtype=torch.uint8, device="cuda")
+
+        def step():
+            for i in range(a.stream_chunks):
+                elsa.elsa_attn_stream_step(tq, kcs[i], vcs[i], state, scale, first=(i == 0), causal=causal,
+                                           causal_shift=-i * nc)
+            elsa.elsa_attn_stream_finish(state, out)
+    elif decode:
         def step():
             elsa.elsa_attn_fwd_cross(tq, tk, tv, out, scale, causal, tl)
     elif varlen:
@@ -272,7 +287,8 @@ def main():
         "ms_per_step": ms_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16 io / f32 state" if fp16 else "f32", "data": "synthetic",
         "pct_of_fp32_peak": 100.0 * value / PEAK_FP32_TFLOPS,
-        "config": {"workload": name, "causal": bool(causal), "kernel": kernel, "path": a.path, "graph": bool(a.graph)},
+        "config": {"workload": name, "causal": bool(causal), "kernel": kernel, "path": a.path, "graph": bool(a.graph),
+                   "stream_chunks": a.stream_chunks},
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": MEASURED_TRAFFIC.get((name, kernel)),
                      "kernel_ms": ms_kernel},

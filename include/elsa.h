@@ -128,6 +128,39 @@ int elsa_attn_fwd_split_kv(const void *q, const void *k, const void *v,
 int elsa_combine(const float *part_m, const float *part_S, const float *part_W, void *out,
                  int B, int H, int n, int d, int num_splits, int dtype, void *stream);
 
+/*
+ * Streaming (memory-lean) evaluation: the keys and values arrive chunk by chunk -- a fraction of
+ * the sequence at a time, e.g. staged from host memory -- and never need to be resident together.
+ * The running state u = (m, S, W) of every query row lives in a caller-owned buffer; each step
+ * forms the state of the new chunk and replaces u by u (+) u_chunk (Eq. 3; Prop. 1 with the
+ * chunks as blocks; the identity-started sequential use of the monoid of Alg. 1, one block per
+ * step).  elsa_attn_stream_finish writes y = W/S (Alg. 1, last line).
+ *   state    device buffer of elsa_stream_state_bytes(B, H, n_q, d) bytes, 256-byte aligned:
+ *            m [B][H][n_q] | S [B][H][n_q] | W [B][H][n_q][d], FP32, each part 256-byte aligned;
+ *            m is the running maximum of scale*<q,k> in LOG2 units (times log2 e), so that
+ *            re-merging adds no rounding to it.  Opaque apart from that; scale, d, dtype and the
+ *            shape must stay the same over the steps of one evaluation.
+ *   q        [B][H][n_q][d];  k_chunk, v_chunk: [B][H][n_chunk][d] (this step's keys only).
+ *   first    != 0: the state is overwritten (no need to initialise it); 0: merged into.
+ *   causal   != 0: key j OF THIS CHUNK is visible to query i iff j <= i + causal_shift.  For a
+ *            chunk that starts at global key k0 of n_k keys in all, with the last query aligned
+ *            to the last key, causal_shift = (n_k - n_q) - k0.  Rows that see no key of the
+ *            chunk keep their state.
+ *   kv_len   device int32 [B] or NULL: visible keys of this chunk per batch entry.
+ * One launch per step, no key split: meant for n_q large enough to fill the GPU or for chunks
+ * that arrive slower than they are consumed.  Steps of one evaluation must be ordered on the
+ * stream (they read and write the state).  Errors as elsa_attn_fwd; a misaligned state returns
+ * ELSA_ERR_WORKSPACE.
+ */
+size_t elsa_stream_state_bytes(int B, int H, int n_q, int d);
+int elsa_attn_stream_step(const void *q, const void *k_chunk, const void *v_chunk, void *state,
+                          int B, int H, int n_q, int n_chunk, int d, float scale,
+                          int causal, int causal_shift, const int32_t *kv_len, int first,
+                          int dtype, void *stream);
+/* out [B][H][n_q][d] = W/S of the state; lse (FP32 [B][H][n_q], or NULL) = ln of the normaliser. */
+int elsa_attn_stream_finish(const void *state, void *out, float *lse, int B, int H, int n_q, int d,
+                            int dtype, void *stream);
+
 /* Bytes of FP32 workspace that hold part_m, part_S and part_W for these sizes
  * (0 for invalid sizes).  Layout: part_m | part_S | part_W, each 256-byte aligned. */
 size_t elsa_split_kv_workspace_bytes(int B, int H, int n, int d, int num_splits);

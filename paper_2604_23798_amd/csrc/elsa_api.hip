@@ -61,12 +61,24 @@ bool small_kernel_ok(const int32_t *cu_seqlens, int splits, int emit, int n, int
     return !cu_seqlens && splits == 1 && !emit && n == nk;
 }
 
+// Optional parts of a forward launch.
+struct Extra {
+    const int32_t *cu_seqlens = nullptr;         // packed layout
+    int num_seqs = 0, total_tokens = 0;
+    float *lse = nullptr;
+    int nk = 0;                                  // keys per (batch, head); 0 = as many as queries
+    int accumulate = 0;                          // merge the emitted state into the stored one
+    bool has_coff = false;                       // causal diagonal given explicitly (streamed chunks)
+    int coff = 0;
+};
+
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
                 int B, int H, int n, int d, float scale, int causal, const int32_t *kv_len,
-                int num_splits, int emit, int m_natural, int dtype, void *stream,
-                const int32_t *cu_seqlens = nullptr, int num_seqs = 0, int total_tokens = 0, float *lse = nullptr,
-                int nk = 0) {
-    if (nk <= 0) nk = n;                         // self-attention: as many keys as queries
+                int num_splits, int emit, int m_natural, int dtype, void *stream, const Extra &x = Extra()) {
+    const int32_t *cu_seqlens = x.cu_seqlens;
+    const int num_seqs = x.num_seqs, total_tokens = x.total_tokens;
+    float *lse = x.lse;
+    const int nk = x.nk > 0 ? x.nk : n;          // self-attention: as many keys as queries
     // auto: FP32 I/O -> FP32 MFMA; FP16 I/O -> FP16 MFMA (needs a non-zero scale)
     int path = g.opt[ELSA_OPT_PATH];
     if (path == 0) path = (dtype == ELSA_F16 && scale != 0.f) ? 3 : 2;
@@ -105,6 +117,8 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     p.num_splits = num_splits;
     p.chunk = (nk + num_splits - 1) / num_splits;
     p.emit_partials = emit;
+    p.accumulate = x.accumulate;
+    p.coff = x.has_coff ? x.coff : nk - n;       // last query aligned with the last key
     p.m_natural = m_natural;
     p.q_tiles = (n + tq - 1) / tq;
     p.tq = tq;
@@ -191,14 +205,17 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     int rc = check_common(B, H, n, d, dtype);
     if (rc != ELSA_OK) return rc;
     const int C = g.ws ? auto_splits(B, H, n, nk, d) : 1;
-    if (C == 1)
+    Extra x;
+    x.nk = nk;
+    if (C == 1) {
+        x.lse = lse;
         return run_forward(q, k, v, out, nullptr, nullptr, nullptr, B, H, n, d, scale, causal, kv_len, 1, 0, 0, dtype,
-                           stream, nullptr, 0, 0, lse, nk);
+                           stream, x);
+    }
     float *pm, *pS, *pW;
     carve(g.ws, B, H, n, d, C, &pm, &pS, &pW);
     // internal split: maxima stay in log2 units, so the second pass adds no rounding of m
-    rc = run_forward(q, k, v, nullptr, pm, pS, pW, B, H, n, d, scale, causal, kv_len, C, 1, 0, dtype, stream,
-                     nullptr, 0, 0, nullptr, nk);
+    rc = run_forward(q, k, v, nullptr, pm, pS, pW, B, H, n, d, scale, causal, kv_len, C, 1, 0, dtype, stream, x);
     if (rc != ELSA_OK) return rc;
     elsa::CombineParams cp{pm, pS, pW, out, lse, (long long)B * H * n, n, C, 0, dtype == ELSA_F16};
     return elsa::launch_combine(cp, d, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
@@ -252,6 +269,41 @@ int elsa_combine(const float *part_m, const float *part_S, const float *part_W, 
     return elsa::launch_combine(cp, d, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
 }
 
+size_t elsa_stream_state_bytes(int B, int H, int n_q, int d) { return elsa_split_kv_workspace_bytes(B, H, n_q, d, 1); }
+
+int elsa_attn_stream_step(const void *q, const void *k_chunk, const void *v_chunk, void *state,
+                          int B, int H, int n_q, int n_chunk, int d, float scale,
+                          int causal, int causal_shift, const int32_t *kv_len, int first,
+                          int dtype, void *stream) {
+    if (!q || !k_chunk || !v_chunk || !state) return ELSA_ERR_INVALID_ARG;
+    if (!std::isfinite(scale) || n_chunk <= 0) return ELSA_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(state) & 255) return ELSA_ERR_WORKSPACE;
+    const int rc = check_common(B, H, n_q, d, dtype);
+    if (rc != ELSA_OK) return rc;
+    float *pm, *pS, *pW;
+    carve(state, B, H, n_q, d, 1, &pm, &pS, &pW);
+    Extra x;
+    x.nk = n_chunk;
+    x.accumulate = first ? 0 : 1;
+    x.has_coff = true;
+    x.coff = causal_shift;
+    // one chunk per call, maxima kept in log2 units so that re-merging adds no rounding of m
+    return run_forward(q, k_chunk, v_chunk, nullptr, pm, pS, pW, B, H, n_q, d, scale, causal, kv_len, 1, 1, 0, dtype,
+                       stream, x);
+}
+
+int elsa_attn_stream_finish(const void *state, void *out, float *lse, int B, int H, int n_q, int d, int dtype,
+                            void *stream) {
+    if (!state || !out) return ELSA_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(state) & 255) return ELSA_ERR_WORKSPACE;
+    const int rc = check_common(B, H, n_q, d, dtype);
+    if (rc != ELSA_OK) return rc;
+    float *pm, *pS, *pW;
+    carve(const_cast<void *>(state), B, H, n_q, d, 1, &pm, &pS, &pW);
+    elsa::CombineParams cp{pm, pS, pW, out, lse, (long long)B * H * n_q, n_q, 1, 0, dtype == ELSA_F16};
+    return elsa::launch_combine(cp, d, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
+}
+
 int elsa_set_option(int option, int value) {
     if (option < 0 || option > 3) return ELSA_ERR_UNSUPPORTED;
     if (value < 0) return ELSA_ERR_INVALID_ARG;
@@ -284,8 +336,12 @@ int elsa_attn_fwd_varlen(const void *q, const void *k, const void *v, void *out,
     // (about the number of blocks the packed batch really yields); no key split on this path
     const long long n_eff = (long long)total_tokens + 64LL * num_seqs;
     (void)max_seqlen;
+    Extra x;
+    x.cu_seqlens = cu_seqlens;
+    x.num_seqs = num_seqs;
+    x.total_tokens = total_tokens;
     return run_forward(q, k, v, out, nullptr, nullptr, nullptr, 1, H, (int)(n_eff > 0x7fffffff ? 0x7fffffff : n_eff), d,
-                       scale, causal, nullptr, 1, 0, 0, dtype, stream, cu_seqlens, num_seqs, total_tokens);
+                       scale, causal, nullptr, 1, 0, 0, dtype, stream, x);
 }
 
 const char *elsa_variant_name(int path, int variant) {

@@ -32,6 +32,9 @@ struct FwdParams {
     int num_splits;                  // C >= 1
     int chunk;                       // ceil(nk / C) keys per split
     int emit_partials;               // 1: write (m,S,W) states instead of out
+    int accumulate;                  // 1 (with emit_partials, num_splits == 1, log2-unit m): merge the new state
+                                     //    into the one already stored at part_m/S/W (streamed key chunks)
+    int coff;                        // dense layout, causal: key j is visible to query i iff j <= i + coff
     int m_natural;                   // 1: part_m in natural-log units, 0: log2 units (internal)
     int xcd_map;                     // block -> work item order, see decode_work
     int q_tiles;                     // ceil(n / T_q) for the launched configuration
@@ -71,6 +74,16 @@ __device__ __forceinline__ float half_sum(float x) {
     unsigned u = __float_as_uint(x);
     auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Factors of a (+) b (Eq. 3) for maxima in log2 units: a is scaled by fa, b by fb, the merged
+// maximum is returned.  Two identities give (0, 0) and -inf.
+__device__ __forceinline__ float merge_factors(float ma, float mb, float &fa, float &fb) {
+    const float mnew = fmaxf(ma, mb);
+    const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+    fa = exp2_fast(ma - msafe);
+    fb = exp2_fast(mb - msafe);
+    return mnew;
 }
 
 // Work item (query tile, key chunk, head) of this block.  Blocks are dealt round-robin to the
@@ -145,7 +158,7 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
     if (p.causal) r.qt = p.q_tiles - 1 - r.qt;   // longest rows first
     r.n = p.n;
     r.nk = p.nk;
-    r.coff = p.nk - p.n;
+    r.coff = p.coff;
     r.ts = D;
     r.base = r.bh * (long long)p.n * D;
     r.kbase = r.bh * (long long)p.nk * D;

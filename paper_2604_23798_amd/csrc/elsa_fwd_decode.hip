@@ -191,12 +191,21 @@ __global__ __launch_bounds__(256) void fwd_decode_kernel(FwdParams p) {
         }
     if (p.emit_partials) {
         const long long prow = (bh * p.num_splits + c) * (long long)n + row;
+        f32x4 x0 = {Wa[0], Wa[1], Wa[2], Wa[3]}, x1 = {Wa[4], Wa[5], Wa[6], Wa[7]};
+        if (p.accumulate) {                      // stored (+) new, Eq. 3; the LPR threads of a row all read first
+            const float ms = p.part_m[prow], Ss = p.part_S[prow];
+            float fn, fold;
+            ma = merge_factors(ma, ms, fn, fold);
+            Sa = Sa * fn + Ss * fold;
+            x0 = x0 * fn + Io<float>::load4(p.part_W, prow * D + 8 * cs2) * fold;
+            x1 = x1 * fn + Io<float>::load4(p.part_W, prow * D + 8 * cs2 + 4) * fold;
+        }
         if (cs2 == 0) {
             p.part_m[prow] = p.m_natural ? ma * kLn2 : ma;
             p.part_S[prow] = Sa;
         }
-        Io<float>::store4(p.part_W, prow * D + 8 * cs2, f32x4{Wa[0], Wa[1], Wa[2], Wa[3]});
-        Io<float>::store4(p.part_W, prow * D + 8 * cs2 + 4, f32x4{Wa[4], Wa[5], Wa[6], Wa[7]});
+        Io<float>::store4(p.part_W, prow * D + 8 * cs2, x0);
+        Io<float>::store4(p.part_W, prow * D + 8 * cs2 + 4, x1);
     } else {
         const float f = Sa > 0.f ? 1.f / Sa : 0.f;
         if (p.lse && cs2 == 0) p.lse[bh * (long long)n + row] = lse_of(ma, Sa);

@@ -133,11 +133,20 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
     if (row >= n) return;
     if (p.emit_partials) {
         const long long prow = (bh * p.num_splits + c) * (long long)n + row;
+        float fn = 1.f, fold = 0.f;
+        if (p.accumulate) {                      // stored (+) new, Eq. 3
+            const float ms = p.part_m[prow], Ss = p.part_S[prow];
+            m = merge_factors(m, ms, fn, fold);
+            S = S * fn + Ss * fold;
+        }
         p.part_m[prow] = p.m_natural ? m * kLn2 : m;
         p.part_S[prow] = S;
 #pragma unroll
-        for (int c4 = 0; c4 < D / 4; ++c4)
-            Io<float>::store4(p.part_W, prow * D + 4 * c4, f32x4{W[4 * c4], W[4 * c4 + 1], W[4 * c4 + 2], W[4 * c4 + 3]});
+        for (int c4 = 0; c4 < D / 4; ++c4) {
+            f32x4 x = f32x4{W[4 * c4], W[4 * c4 + 1], W[4 * c4 + 2], W[4 * c4 + 3]} * fn;
+            if (p.accumulate) x += Io<float>::load4(p.part_W, prow * D + 4 * c4) * fold;
+            Io<float>::store4(p.part_W, prow * D + 4 * c4, x);
+        }
     } else {
         const float f = S > 0.f ? 1.f / S : 0.f;
         if (p.lse) p.lse[bh * (long long)n + row] = lse_of(m, S);

@@ -338,13 +338,19 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     for (int nq = 0; nq < NQ; ++nq) {
         const int row = wrow0 + nq * 32 + j;
         if (row >= n) continue;
-        float f = 1.f;
+        float f = 1.f, fold = 0.f;               // out/state = new * f + stored state * fold
         long long obase;
         if (partial) {
             const long long prow = (bh * p.num_splits + c) * (long long)n + row;
+            float mo = mrun[nq], So = stot[nq];
+            if (p.accumulate) {                  // stored (+) new, Eq. 3; every lane of the row reads, lane h = 0 writes
+                const float ms = p.part_m[prow], Ss = p.part_S[prow];
+                mo = merge_factors(mrun[nq], ms, f, fold);
+                So = stot[nq] * f + Ss * fold;
+            }
             if (h == 0) {
-                p.part_m[prow] = p.m_natural ? mrun[nq] * kLn2 : mrun[nq];
-                p.part_S[prow] = stot[nq];
+                p.part_m[prow] = p.m_natural ? mo * kLn2 : mo;
+                p.part_S[prow] = So;
             }
             obase = prow * D;
         } else {
@@ -352,31 +358,33 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
             obase = head_off + (long long)row * ts;
             if (p.lse && h == 0) p.lse[bh * (long long)n + row] = lse_of(mrun[nq], stot[nq]);
         }
+        auto emit = [&](long long at, f32x4 x) {
+            if (partial) {
+                if (p.accumulate) x += Io<float>::load4(p.part_W, at) * fold;
+                Io<float>::store4(p.part_W, at, x);
+            } else {
+                Io<T>::store4(p.out, at, x);
+            }
+        };
 #pragma unroll
         for (int g = 0; g < 4; ++g) {
             if constexpr (MB == 1) {
                 const f32x4 x = {oacc[nq][0][4 * g] * f, oacc[nq][0][4 * g + 1] * f, oacc[nq][0][4 * g + 2] * f,
                                  oacc[nq][0][4 * g + 3] * f};
-                const int dv = 8 * g + 4 * h;
-                if (partial) Io<float>::store4(p.part_W, obase + dv, x);
-                else Io<T>::store4(p.out, obase + dv, x);
+                emit(obase + 8 * g + 4 * h, x);
             } else if constexpr (MB == 2) {
 #pragma unroll
                 for (int t2 = 0; t2 < 4; t2 += 2) {
                     const f32x4 x = {oacc[nq][0][4 * g + t2] * f, oacc[nq][1][4 * g + t2] * f,
                                      oacc[nq][0][4 * g + t2 + 1] * f, oacc[nq][1][4 * g + t2 + 1] * f};
-                    const int dv = 2 * (8 * g + 4 * h + t2);
-                    if (partial) Io<float>::store4(p.part_W, obase + dv, x);
-                    else Io<T>::store4(p.out, obase + dv, x);
+                    emit(obase + 2 * (8 * g + 4 * h + t2), x);
                 }
             } else {
 #pragma unroll
                 for (int t = 0; t < 4; ++t) {
                     const f32x4 x = {oacc[nq][0][4 * g + t] * f, oacc[nq][1][4 * g + t] * f,
                                      oacc[nq][2][4 * g + t] * f, oacc[nq][3][4 * g + t] * f};
-                    const int dv = 4 * (8 * g + 4 * h + t);
-                    if (partial) Io<float>::store4(p.part_W, obase + dv, x);
-                    else Io<T>::store4(p.out, obase + dv, x);
+                    emit(obase + 4 * (8 * g + 4 * h + t), x);
                 }
             }
         }

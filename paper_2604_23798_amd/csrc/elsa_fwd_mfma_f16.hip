@@ -306,13 +306,19 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
     for (int nq = 0; nq < NQ; ++nq) {
         const int row = wrow0 + nq * 32 + j;
         if (row >= n) continue;
-        float f = 1.f;
+        float f = 1.f, fold = 0.f;               // out/state = new * f + stored state * fold
         long long obase;
         if (partial) {
             const long long prow = (bh * p.num_splits + c) * (long long)n + row;
+            float mo = mrun[nq], So = stot[nq];
+            if (p.accumulate) {                  // stored (+) new, Eq. 3; every lane of the row reads, lane h = 0 writes
+                const float ms = p.part_m[prow], Ss = p.part_S[prow];
+                mo = merge_factors(mrun[nq], ms, f, fold);
+                So = stot[nq] * f + Ss * fold;
+            }
             if (h == 0) {
-                p.part_m[prow] = p.m_natural ? mrun[nq] * kLn2 : mrun[nq];
-                p.part_S[prow] = stot[nq];
+                p.part_m[prow] = p.m_natural ? mo * kLn2 : mo;
+                p.part_S[prow] = So;
             }
             obase = prow * D;
         } else {
@@ -324,11 +330,15 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const f32x4 x = {oacc[nq][mb][4 * g] * f, oacc[nq][mb][4 * g + 1] * f, oacc[nq][mb][4 * g + 2] * f,
-                                 oacc[nq][mb][4 * g + 3] * f};
+                f32x4 x = {oacc[nq][mb][4 * g] * f, oacc[nq][mb][4 * g + 1] * f, oacc[nq][mb][4 * g + 2] * f,
+                           oacc[nq][mb][4 * g + 3] * f};
                 const int dv = 32 * mb + 8 * g + 4 * h;
-                if (partial) Io<float>::store4(p.part_W, obase + dv, x);
-                else Io<_Float16>::store4(p.out, obase + dv, x);
+                if (partial) {
+                    if (p.accumulate) x += Io<float>::load4(p.part_W, obase + dv) * fold;
+                    Io<float>::store4(p.part_W, obase + dv, x);
+                } else {
+                    Io<_Float16>::store4(p.out, obase + dv, x);
+                }
             }
     }
 }

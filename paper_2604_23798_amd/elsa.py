@@ -18,6 +18,7 @@ OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP = 0, 1, 2, 3
 PATH_AUTO, PATH_FMA, PATH_MFMA, PATH_MFMA16 = 0, 1, 2, 3
 
 EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_lse", "elsa_attn_fwd_cross", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
+           "elsa_stream_state_bytes", "elsa_attn_stream_step", "elsa_attn_stream_finish",
            "elsa_split_kv_workspace_bytes", "elsa_set_workspace", "elsa_set_option", "elsa_get_option",
            "elsa_variant_name", "elsa_last_kernel", "elsa_status_string", "elsa_debug_layout_probe")
 
@@ -31,6 +32,10 @@ _lib.elsa_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _i, _
 _lib.elsa_attn_fwd_masked.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
 _lib.elsa_attn_fwd_lse.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
 _lib.elsa_attn_fwd_cross.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
+_lib.elsa_stream_state_bytes.argtypes = [_i, _i, _i, _i]
+_lib.elsa_stream_state_bytes.restype = ctypes.c_size_t
+_lib.elsa_attn_stream_step.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _i, _vp, _i, _i, _vp]
+_lib.elsa_attn_stream_finish.argtypes = [_vp, _vp, _vp, _i, _i, _i, _i, _i, _vp]
 _lib.elsa_attn_fwd_varlen.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _i, _vp]
 _lib.elsa_attn_fwd_split_kv.argtypes = [_vp, _vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _i, _vp]
 _lib.elsa_combine.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _vp]
@@ -132,6 +137,39 @@ def elsa_attn_fwd_cross(q, k, v, out, scale, causal=False, kv_len=None, lse=None
         assert lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, H, nq)
     _check(_lib.elsa_attn_fwd_cross(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, nq, nk, d, float(scale),
                                     int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
+    return out
+
+
+def elsa_stream_state_bytes(B, H, n_q, d) -> int:
+    return int(_lib.elsa_stream_state_bytes(B, H, n_q, d))
+
+
+def elsa_attn_stream_step(q, k_chunk, v_chunk, state, scale, first, causal=False, causal_shift=0, kv_len=None,
+                          stream=None):
+    """One chunk of keys/values merged into the running state (uint8 device buffer of elsa_stream_state_bytes)."""
+    import torch
+    assert q.is_cuda and q.dim() == 4 and k_chunk.dim() == 4 and k_chunk.shape == v_chunk.shape
+    assert q.is_contiguous() and k_chunk.is_contiguous() and v_chunk.is_contiguous() and state.is_contiguous()
+    assert q.dtype == k_chunk.dtype == v_chunk.dtype
+    B, H, nq, d = q.shape
+    nc = k_chunk.shape[2]
+    assert tuple(k_chunk.shape) == (B, H, nc, d)
+    assert state.is_cuda and state.numel() * state.element_size() >= elsa_stream_state_bytes(B, H, nq, d)
+    if kv_len is not None:
+        assert kv_len.is_cuda and kv_len.dtype == torch.int32 and tuple(kv_len.shape) == (B,)
+    _check(_lib.elsa_attn_stream_step(_ptr(q), _ptr(k_chunk), _ptr(v_chunk), _ptr(state), B, H, nq, nc, d, float(scale),
+                                      int(bool(causal)), int(causal_shift), _ptr(kv_len), int(bool(first)),
+                                      _dtype_code(q), _stream(stream)))
+
+
+def elsa_attn_stream_finish(state, out, lse=None, stream=None):
+    import torch
+    B, H, nq, d = out.shape
+    assert out.is_cuda and out.is_contiguous() and state.is_cuda
+    if lse is not None:
+        assert lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, H, nq)
+    _check(_lib.elsa_attn_stream_finish(_ptr(state), _ptr(out), _ptr(lse), B, H, nq, d, _dtype_code(out),
+                                        _stream(stream)))
     return out
 
 

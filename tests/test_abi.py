@@ -87,3 +87,10 @@ def test_bad_arguments_are_rejected_before_any_launch():
                                              kw.get("d", 64), 0.125, 0, None, 0, None)
     assert x(q=None) == INV and x(nq=0) == INV and x(nk=0) == INV and x(nk=-3) == INV and x(d=96) == UNS
     assert x(nq=1, nk=1 << 24, d=128) == UNS   # the key slice, not the query count, sets the limit
+    st = lambda **kw: lib.elsa_attn_stream_step(kw.get("q", p), p, p, kw.get("state", p), 1, 1, kw.get("nq", 4),
+                                                kw.get("nc", 8), kw.get("d", 64), 0.125, 0, 0, None, 1, 0, None)
+    assert st(q=None) == INV and st(state=None) == INV and st(nq=0) == INV and st(nc=0) == INV and st(d=96) == UNS
+    assert st(state=ctypes.c_void_p(8)) == 3
+    fin = lambda **kw: lib.elsa_attn_stream_finish(kw.get("state", p), kw.get("out", p), None, 1, 1, 4, kw.get("d", 64), 0, None)
+    assert fin(state=None) == INV and fin(out=None) == INV and fin(d=5) == UNS and fin(state=ctypes.c_void_p(8)) == 3
+    assert elsa.elsa_stream_state_bytes(2, 3, 5, 64) == elsa.elsa_split_kv_workspace_bytes(2, 3, 5, 64, 1)

@@ -1,0 +1,144 @@
+"""GPU parity of the streaming (memory-lean) evaluation: keys and values arrive chunk by chunk and
+are merged into a running (m, S, W) state.  After EVERY step the state, in canonical form
+(lse = ln of the normaliser, y = W/S), is compared with the oracle's definition restricted to the
+keys seen so far; the finished output with the definition on all keys."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_23798_amd import inputs
+from tests import gpu_util as G
+from tests.parity import assert_parity, tolerance
+
+pytestmark = pytest.mark.gpu
+LN2 = 0.6931471805599453
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not G.have_gpu():
+        pytest.skip("no GPU")
+    from paper_2604_23798_amd import elsa  # noqa: F401
+
+
+def _rect(B, H, nq, nk, d, seed, fp16=False):
+    q = inputs.normal(seed, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
+    k = inputs.normal(seed, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
+    v = inputs.normal(seed, 2, 0, B * H * nk * d).reshape(B, H, nk, d)
+    if fp16:
+        q, k, v = (t.astype(np.float16) for t in (q, k, v))
+    return q, k, v
+
+
+def _state_views(state, B, H, nq, d):
+    """(m in log2 units, S, W) as float64 numpy from the documented layout."""
+    import torch
+    a = lambda x: (x + 255) & ~255
+    rows = B * H * nq
+    f = state.view(torch.float32)
+    m = f[:rows]
+    S = f[a(rows * 4) // 4: a(rows * 4) // 4 + rows]
+    W = f[2 * a(rows * 4) // 4: 2 * a(rows * 4) // 4 + rows * d].reshape(rows, d)
+    return m.double().cpu().numpy(), S.double().cpu().numpy(), W.double().cpu().numpy()
+
+
+def _run(q, k, v, scale, chunks, causal, fp16, opts, kv_full=None, check_steps=True):
+    import torch
+    from paper_2604_23798_amd import elsa
+    B, H, nq, d = q.shape
+    nk = k.shape[2]
+    f32 = lambda t: t.astype(np.float32)
+    tq = G.to_dev(q)
+    state = torch.empty(elsa.elsa_stream_state_bytes(B, H, nq, d), dtype=torch.uint8, device="cuda")
+    state.fill_(0xFF)                            # NaN patterns: the first step must not read them
+    tol = tolerance(max(nq, nk), fp16)
+    k0 = 0
+    with G.Options(**opts):
+        for ci, nc in enumerate(chunks):
+            kc = G.to_dev(np.ascontiguousarray(k[:, :, k0:k0 + nc]))
+            vc = G.to_dev(np.ascontiguousarray(v[:, :, k0:k0 + nc]))
+            kl = None
+            if kv_full is not None:              # visible keys of this chunk per batch entry
+                kl = G.to_dev(np.clip(kv_full - k0, 0, nc).astype(np.int32))
+            elsa.elsa_attn_stream_step(tq, kc, vc, state, scale, first=(ci == 0), causal=causal,
+                                       causal_shift=(nk - nq) - k0, kv_len=kl)
+            k0 += nc
+            if check_steps:
+                torch.cuda.synchronize()
+                seen = np.minimum(kv_full, k0).astype(np.int32) if kv_full is not None else np.full(B, k0, np.int32)
+                ref, ref_lse = oracle.cross_rows(f32(q), f32(k), f32(v), scale, causal=causal, kv_len=seen)
+                m, S, W = _state_views(state, B, H, nq, d)
+                vis = np.isfinite(ref_lse)
+                assert np.all(S[~vis] == 0) and np.all(np.isneginf(m[~vis])) and np.all(W[~vis] == 0), "identity rows"
+                lse = (m[vis] + np.log2(S[vis])) * LN2
+                assert np.max(np.abs(lse - ref_lse[vis]), initial=0.0) < (5e-3 if fp16 else 3e-5), "lse after step %d" % ci
+                if vis.any():
+                    assert_parity(W[vis] / S[vis][:, None], ref[vis], tol, "state after step %d %s" % (ci, opts))
+        out = torch.full_like(tq, float("nan"))
+        lse_t = torch.full((B, H, nq), float("nan"), device="cuda")
+        elsa.elsa_attn_stream_finish(state, out, lse_t)
+        torch.cuda.synchronize()
+    ref, ref_lse = oracle.cross_rows(f32(q), f32(k), f32(v), scale, causal=causal, kv_len=kv_full)
+    got = out.reshape(-1, d).double().cpu().numpy()
+    assert_parity(got, ref, tol, "finished %s" % opts)
+    vis = np.isfinite(ref_lse)
+    gl = lse_t.reshape(-1).double().cpu().numpy()
+    assert np.all(np.isneginf(gl[~vis])) and np.max(np.abs(gl[vis] - ref_lse[vis]), initial=0.0) < (5e-3 if fp16 else 3e-5)
+    return got
+
+
+CASES = [  # n_q, n_k, chunk lengths (ragged, not tile multiples)
+    (300, 1000, [256, 256, 488]),
+    (700, 700, [200, 200, 200, 100]),          # causal self-attention: early rows see nothing of late chunks
+    (1, 3001, [1000, 1000, 1001]),             # decoding
+    (4, 900, [300, 600]),
+    (70, 64, [64]),                            # a single step
+    (130, 40, [25, 15]),                       # more queries than keys
+]
+
+
+@pytest.mark.parametrize("fp16", [False, True])
+@pytest.mark.parametrize("causal", [False, True])
+def test_default_kernels_every_step_checked(causal, fp16):
+    for (nq, nk, chunks) in CASES:
+        for d in (64, 128):
+            q, k, v = _rect(2, 2, nq, nk, d, 700 + nq + d, fp16=fp16)
+            _run(q, k, v, d ** -0.5, chunks, causal, fp16, {})
+
+
+KERNELS = [dict(path=2, variant=v) for v in (1, 2, 3, 4, 7, 8)] + [dict(path=1, variant=v) for v in (1, 2, 3, 4)]
+
+
+@pytest.mark.parametrize("opts", KERNELS, ids=lambda o: "p%d_v%d" % (o["path"], o["variant"]))
+def test_every_fp32_kernel_family_accumulates(opts):
+    for (nq, nk, chunks) in CASES[:4]:
+        q, k, v = _rect(1, 3, nq, nk, 64, 800 + nq)
+        _run(q, k, v, 0.125, chunks, True, False, opts)
+    q, k, v = _rect(1, 2, 100, 500, 32, 801)
+    _run(q, k, v, 0.2, [130, 370], False, False, opts)
+
+
+@pytest.mark.parametrize("variant", [1, 2, 3])
+def test_every_fp16_matrix_core_kernel_accumulates(variant):
+    for (nq, nk, chunks) in CASES[:4]:
+        for d in (32, 128):
+            q, k, v = _rect(1, 3, nq, nk, d, 900 + nq, fp16=True)
+            _run(q, k, v, d ** -0.5, chunks, True, True, dict(path=3, variant=variant))
+
+
+def test_key_padding_per_chunk():
+    B, H, nq, nk, d = 3, 2, 90, 600, 64
+    q, k, v = _rect(B, H, nq, nk, d, 1000)
+    kv_full = np.array([600, 250, 0], np.int32)
+    for causal in (False, True):
+        _run(q, k, v, 0.125, [200, 200, 200], causal, False, {}, kv_full=kv_full)
+
+
+def test_streamed_result_matches_the_resident_result():
+    """eta = 1/4: four chunks of the 4096-token sweep workload against the one-call result."""
+    w = inputs.sweep(4096)
+    q, k, v, _ = inputs.make(w)
+    rows = inputs.sample_rows(w, per_head=16)
+    got = _run(q, k, v, w.scale, [1024] * 4, False, False, {}, check_steps=False)
+    res = G.fwd(q, k, v, w.scale)
+    assert np.max(np.linalg.norm(got[rows] - res[rows], axis=1) / np.linalg.norm(res[rows], axis=1)) < 2e-5
