@@ -7,8 +7,10 @@
  *     never allocates, frees or retains them (except the workspace registered
  *     with elsa_set_workspace, which it borrows until replaced).
  *   - Q, K, V, out are contiguous row-major [B][H][n][d] with d_v == d,
- *     self-attention (n queries, n keys) except for elsa_attn_fwd_cross.  d must be 32, 64 or
- *     128.  The K (and V) slice of one (batch, head) -- one sequence of a packed batch -- must
+ *     self-attention (n queries, n keys) except for elsa_attn_fwd_cross.  d must be 32, 64, 96,
+ *     128 or 256; 96 and 256 run on the matrix-core tiles, the one-query decode kernel and the
+ *     combine only (ELSA_OPT_PATH = 1 tiles and the LDS-free small-problem tiles return
+ *     ELSA_ERR_UNSUPPORTED for them).  The K (and V) slice of one (batch, head) -- one sequence of a packed batch -- must
  *     span less than 2 GiB (n*d*sizeof(element), or total_tokens*H*d*sizeof(element) for the
  *     packed layout); larger problems return ELSA_ERR_UNSUPPORTED on every path that fetches
  *     through buffer descriptors (all but the FP32 FMA tiles of ELSA_OPT_PATH = 1).
@@ -41,7 +43,7 @@ extern "C" {
 enum {
     ELSA_OK = 0,
     ELSA_ERR_INVALID_ARG = 1,  /* null pointer, B/H/n <= 0, num_splits out of range, non-finite scale */
-    ELSA_ERR_UNSUPPORTED = 2,  /* d not in {32,64,128}, dtype not in {0,1}, unknown option, slice >= 2 GiB */
+    ELSA_ERR_UNSUPPORTED = 2,  /* d not in {32,64,96,128,256}, dtype not in {0,1}, unknown option, slice >= 2 GiB */
     ELSA_ERR_WORKSPACE = 3,    /* registered workspace too small / misaligned */
     ELSA_ERR_HIP = 4           /* the HIP runtime reported a launch failure */
 };

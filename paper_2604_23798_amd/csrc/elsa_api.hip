@@ -19,10 +19,14 @@ constexpr int kNumCu = 256;
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
+// 32, 64, 128 on every path; 96 and 256 on the matrix-core tiles, the decode kernel and the combine
+bool head_dim_ok(int d) { return d == 32 || d == 64 || d == 96 || d == 128 || d == 256; }
+bool head_dim_wide(int d) { return d == 96 || d == 256; }
+
 int check_common(int B, int H, int n, int d, int dtype) {
     if (B <= 0 || H <= 0 || n <= 0) return ELSA_ERR_INVALID_ARG;
     if ((long long)B * H > 0x7fffffffLL / 64) return ELSA_ERR_INVALID_ARG;
-    if (d != 32 && d != 64 && d != 128) return ELSA_ERR_UNSUPPORTED;
+    if (!head_dim_ok(d)) return ELSA_ERR_UNSUPPORTED;
     if (dtype != ELSA_F32 && dtype != ELSA_F16) return ELSA_ERR_UNSUPPORTED;
     return ELSA_OK;
 }
@@ -87,11 +91,15 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     int decode_variant = 0;
     if (g.opt[ELSA_OPT_PATH] == 0 && g.opt[ELSA_OPT_VARIANT] == 0 && !cu_seqlens && n <= 4) {
         path = 1;
-        decode_variant = n == 1 ? 3 : 4;
+        decode_variant = (n == 1 || head_dim_wide(d)) ? 3 : 4;
     }
     if (path == 1 && (g.opt[ELSA_OPT_VARIANT] == 3 || g.opt[ELSA_OPT_VARIANT] == 4)) {
         if (cu_seqlens) return ELSA_ERR_UNSUPPORTED;
         decode_variant = g.opt[ELSA_OPT_VARIANT];
+    }
+    if (head_dim_wide(d)) {                      // no FMA tiles, no four-query decode, no LDS-free tiles
+        if (path == 1 && decode_variant != 3) return ELSA_ERR_UNSUPPORTED;
+        if (path == 2 && (g.opt[ELSA_OPT_VARIANT] == 9 || g.opt[ELSA_OPT_VARIANT] == 10)) return ELSA_ERR_UNSUPPORTED;
     }
     // the K/V slice of one (sequence, head) is addressed through a 31-bit buffer range
     const long long tok_stride = cu_seqlens ? (long long)H * d : d;
@@ -100,7 +108,7 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     int variant = decode_variant ? decode_variant : pick_variant(path, (long long)B * H, n, nk, d, num_splits);
     if (path == 2) {
         const bool ok = small_kernel_ok(cu_seqlens, num_splits, emit, n, nk);
-        if (g.opt[ELSA_OPT_VARIANT] == 0 && ok && n <= 128 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu)
+        if (g.opt[ELSA_OPT_VARIANT] == 0 && ok && !head_dim_wide(d) && n <= 128 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu)
             variant = 10;                        // thousands of tiny problems (window attention)
         if ((variant == 9 || variant == 10) && !ok) variant = d <= 64 ? 7 : 1;
     }
@@ -183,7 +191,7 @@ int auto_splits(int B, int H, int n, int nk, int d) {
 extern "C" {
 
 size_t elsa_split_kv_workspace_bytes(int B, int H, int n, int d, int num_splits) {
-    if (B <= 0 || H <= 0 || n <= 0 || (d != 32 && d != 64 && d != 128) || num_splits < 1) return 0;
+    if (B <= 0 || H <= 0 || n <= 0 || !head_dim_ok(d) || num_splits < 1) return 0;
     const size_t rows = (size_t)B * H * num_splits * n;
     return 2 * align256(rows * 4) + align256(rows * d * 4);
 }

@@ -5,7 +5,7 @@ namespace elsa {
 
 // out = W/S of part_0 (+) ... (+) part_{C-1}  (Prop. 1): m = max_c m_c, then every chunk
 // enters with weight e^{m_c - m} <= 1 (Eq. 3 folded over the chunks around the common
-// maximum).  One thread owns four value columns of one query row; the 16 or 32 threads
+// maximum).  One thread owns four value columns of one query row; the d/4 threads
 // of a row recompute the C weights, which is cheap next to the part_W traffic.
 // HBM-bound: reads C*(d+2) floats and writes d values per row.
 template <int D>
@@ -46,7 +46,10 @@ int launch_combine(const CombineParams &p, int d, hipStream_t s) {
     if (blocks <= 0 || blocks > 0x7fffffffLL) return (int)hipErrorInvalidConfiguration;
     if (d == 32) hipLaunchKernelGGL(combine_kernel<32>, dim3((unsigned)blocks), dim3(256), 0, s, p);
     else if (d == 64) hipLaunchKernelGGL(combine_kernel<64>, dim3((unsigned)blocks), dim3(256), 0, s, p);
-    else hipLaunchKernelGGL(combine_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    else if (d == 96) hipLaunchKernelGGL(combine_kernel<96>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    else if (d == 128) hipLaunchKernelGGL(combine_kernel<128>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    else if (d == 256) hipLaunchKernelGGL(combine_kernel<256>, dim3((unsigned)blocks), dim3(256), 0, s, p);
+    else return (int)hipErrorInvalidValue;
     return (int)hipGetLastError();
 }
 

@@ -3,7 +3,8 @@
 //
 // With one to four queries a 32-column matrix-core tile would spend 1/32 .. 1/8 of its work on
 // real rows, so this kernel forms the scores on the vector ALU instead.  A key row of d elements
-// is spread over LPR = d/8 lanes (8 columns each), so one wave instruction reads 64/LPR whole
+// is spread over LPR lanes (d/8 lanes of 8 columns each for d = 32, 64, 128; 4 lanes of 24 columns
+// for d = 96; 16 lanes of 16 columns for d = 256), so one wave instruction reads 64/LPR whole
 // consecutive rows, fully coalesced; a lane multiplies its 8 columns into the query, the LPR
 // lanes of a key add their partial sums with DPP row operations (no LDS), and every lane folds
 // the (key, score) pair into its OWN monoid state (m, S, W[8 columns]) with the merge operator of
@@ -49,11 +50,13 @@ template <> struct Row8<_Float16> {
 
 template <int D, typename T, int NQ>
 __global__ __launch_bounds__(256) void fwd_decode_kernel(FwdParams p) {
-    constexpr int LPR = D / 8;           // lanes per key row
+    constexpr int LPR = D == 96 ? 4 : D == 256 ? 16 : D / 8;   // lanes per key row (a power of two <= 16)
+    constexpr int CPL = D / LPR;         // columns per lane: 8, 16 or 24
     constexpr int KPI = 64 / LPR;        // keys per wave instruction
-    constexpr int U = 4;                 // key groups in flight per wave
+    constexpr int U = CPL == 8 ? 4 : 2;  // key groups in flight per wave
     constexpr int ES = (int)sizeof(T);
-    constexpr int NS = 10;               // floats of state per (lane, query): m, S, W[8]
+    constexpr int NS = 2 + CPL;          // floats of state per (lane, query): m, S, W[CPL]
+    static_assert(CPL % 8 == 0 && LPR * CPL == D && (CPL == 8 || NQ == 1), "unsupported shape");
     __shared__ float st[4 * 64 * NQ * NS];
 
     const int tid = threadIdx.x;
@@ -74,51 +77,54 @@ __global__ __launch_bounds__(256) void fwd_decode_kernel(FwdParams p) {
     int kend = min(kbeg + p.chunk, L);
     if (p.causal) kend = min(kend, q0 + NQ + coff);
 
-    float qr[NQ][8];
+    float qr[NQ][CPL];
     int lim[NQ];                         // first key the query cannot see
 #pragma unroll
     for (int iq = 0; iq < NQ; ++iq) {
         const int row = q0 + iq;
-        f32x4 a = {0.f, 0.f, 0.f, 0.f}, b = a;
-        if (row < n) {
-            a = Io<T>::load4(p.q, wi.base + (long long)row * D + 8 * cs);
-            b = Io<T>::load4(p.q, wi.base + (long long)row * D + 8 * cs + 4);
-        }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) { qr[iq][t] = a[t] * p.qscale; qr[iq][4 + t] = b[t] * p.qscale; }
+        for (int c4 = 0; c4 < CPL / 4; ++c4) {
+            f32x4 a = {0.f, 0.f, 0.f, 0.f};
+            if (row < n) a = Io<T>::load4(p.q, wi.base + (long long)row * D + CPL * cs + 4 * c4);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) qr[iq][4 * c4 + t] = a[t] * p.qscale;
+        }
         lim[iq] = p.causal ? min(kend, row + 1 + coff) : kend;
     }
     int lim_min = lim[0];
 #pragma unroll
     for (int iq = 1; iq < NQ; ++iq) lim_min = min(lim_min, lim[iq]);
 
-    float m[NQ], S[NQ], W[NQ][8];
+    float m[NQ], S[NQ], W[NQ][CPL];
 #pragma unroll
     for (int iq = 0; iq < NQ; ++iq) {
         m[iq] = -INFINITY;
         S[iq] = 0.f;
 #pragma unroll
-        for (int t = 0; t < 8; ++t) W[iq][t] = 0.f;
+        for (int t = 0; t < CPL; ++t) W[iq][t] = 0.f;
     }
 
     // rows at or beyond kend read as zero and are masked
     const long long slice_bytes = kend > 0 ? (long long)kend * D * ES : 0;
     const __amdgpu_buffer_rsrc_t krs = make_rsrc(static_cast<const T *>(p.k) + wi.kbase, slice_bytes);
     const __amdgpu_buffer_rsrc_t vrs = make_rsrc(static_cast<const T *>(p.v) + wi.kbase, slice_bytes);
-    const int voff = (ksub * D + 8 * cs) * ES;
+    const int voff = (ksub * D + CPL * cs) * ES;
 
     // the four waves take turns on runs of U key groups, so that the block reads one contiguous
     // stream of 4*U*KPI rows per round
     const int ngroups = kend > kbeg ? (kend - kbeg + KPI - 1) / KPI : 0;
     for (int g0 = wave * U; g0 < ngroups; g0 += 4 * U) {
-        float kf[U][8], vf[U][8];
+        float kf[U][CPL], vf[U][CPL];
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             // groups past the chunk start at or beyond kend: every lane reads zeros there
             const int key0 = min(kbeg + (g0 + u) * KPI, kend);
             const int soff = key0 * D * ES;
-            Row8<T>::load(krs, voff, soff, kf[u]);
-            Row8<T>::load(vrs, voff, soff, vf[u]);
+#pragma unroll
+            for (int c8 = 0; c8 < CPL / 8; ++c8) {
+                Row8<T>::load(krs, voff + 8 * c8 * ES, soff, kf[u] + 8 * c8);
+                Row8<T>::load(vrs, voff + 8 * c8 * ES, soff, vf[u] + 8 * c8);
+            }
         }
         const bool need_mask = kbeg + (g0 + U) * KPI > lim_min;
 #pragma unroll
@@ -128,7 +134,7 @@ __global__ __launch_bounds__(256) void fwd_decode_kernel(FwdParams p) {
             for (int u = 0; u < U; ++u) {
                 float acc = qr[iq][0] * kf[u][0];
 #pragma unroll
-                for (int t = 1; t < 8; ++t) acc = fmaf(qr[iq][t], kf[u][t], acc);
+                for (int t = 1; t < CPL; ++t) acc = fmaf(qr[iq][t], kf[u][t], acc);
                 s[u] = group_sum<LPR>(acc);
             }
             if (need_mask) {
@@ -151,7 +157,7 @@ __global__ __launch_bounds__(256) void fwd_decode_kernel(FwdParams p) {
             }
             S[iq] = S[iq] * alpha + ps;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) {
+            for (int t = 0; t < CPL; ++t) {
                 float w = W[iq][t] * alpha;
 #pragma unroll
                 for (int u = 0; u < U; ++u) w = fmaf(e[u], vf[u][t], w);
@@ -167,51 +173,51 @@ __global__ __launch_bounds__(256) void fwd_decode_kernel(FwdParams p) {
         dst[0] = m[iq];
         dst[1] = S[iq];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) dst[2 + t] = W[iq][t];
+        for (int t = 0; t < CPL; ++t) dst[2 + t] = W[iq][t];
     }
     __syncthreads();
-    if (tid >= LPR * NQ) return;
+    if (tid >= LPR * NQ) return;         // LPR * NQ <= 64: the threads below are one wave
     const int iq = tid / LPR, cs2 = tid % LPR;
     const int row = q0 + iq;
     if (row >= n) return;
-    float ma = -INFINITY, Sa = 0.f, Wa[8];
+    float ma = -INFINITY, Sa = 0.f, Wa[CPL];
 #pragma unroll
-    for (int t = 0; t < 8; ++t) Wa[t] = 0.f;
+    for (int t = 0; t < CPL; ++t) Wa[t] = 0.f;
     for (int w = 0; w < 4; ++w)
         for (int ks = 0; ks < KPI; ++ks) {
             const float *src = &st[((w * 64 + ks * LPR + cs2) * NQ + iq) * NS];
-            const float mb = src[0], Sb = src[1];
-            const float mnew = fmaxf(ma, mb);
-            const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
-            const float fa = exp2_fast(ma - msafe), fb = exp2_fast(mb - msafe);
-            ma = mnew;
-            Sa = Sa * fa + Sb * fb;
+            float fa, fb;
+            ma = merge_factors(ma, src[0], fa, fb);
+            Sa = Sa * fa + src[1] * fb;
 #pragma unroll
-            for (int t = 0; t < 8; ++t) Wa[t] = Wa[t] * fa + src[2 + t] * fb;
+            for (int t = 0; t < CPL; ++t) Wa[t] = Wa[t] * fa + src[2 + t] * fb;
         }
     if (p.emit_partials) {
         const long long prow = (bh * p.num_splits + c) * (long long)n + row;
-        f32x4 x0 = {Wa[0], Wa[1], Wa[2], Wa[3]}, x1 = {Wa[4], Wa[5], Wa[6], Wa[7]};
+        float fn = 1.f, fold = 0.f;
         if (p.accumulate) {                      // stored (+) new, Eq. 3; the LPR threads of a row all read first
             const float ms = p.part_m[prow], Ss = p.part_S[prow];
-            float fn, fold;
             ma = merge_factors(ma, ms, fn, fold);
             Sa = Sa * fn + Ss * fold;
-            x0 = x0 * fn + Io<float>::load4(p.part_W, prow * D + 8 * cs2) * fold;
-            x1 = x1 * fn + Io<float>::load4(p.part_W, prow * D + 8 * cs2 + 4) * fold;
         }
         if (cs2 == 0) {
             p.part_m[prow] = p.m_natural ? ma * kLn2 : ma;
             p.part_S[prow] = Sa;
         }
-        Io<float>::store4(p.part_W, prow * D + 8 * cs2, x0);
-        Io<float>::store4(p.part_W, prow * D + 8 * cs2 + 4, x1);
+#pragma unroll
+        for (int c4 = 0; c4 < CPL / 4; ++c4) {
+            const long long at = prow * D + CPL * cs2 + 4 * c4;
+            f32x4 x = f32x4{Wa[4 * c4], Wa[4 * c4 + 1], Wa[4 * c4 + 2], Wa[4 * c4 + 3]} * fn;
+            if (p.accumulate) x += Io<float>::load4(p.part_W, at) * fold;
+            Io<float>::store4(p.part_W, at, x);
+        }
     } else {
         const float f = Sa > 0.f ? 1.f / Sa : 0.f;
         if (p.lse && cs2 == 0) p.lse[bh * (long long)n + row] = lse_of(ma, Sa);
-        const long long o = wi.base + (long long)row * D + 8 * cs2;
-        Io<T>::store4(p.out, o, f32x4{Wa[0] * f, Wa[1] * f, Wa[2] * f, Wa[3] * f});
-        Io<T>::store4(p.out, o + 4, f32x4{Wa[4] * f, Wa[5] * f, Wa[6] * f, Wa[7] * f});
+        const long long o = wi.base + (long long)row * D + CPL * cs2;
+#pragma unroll
+        for (int c4 = 0; c4 < CPL / 4; ++c4)
+            Io<T>::store4(p.out, o + 4 * c4, f32x4{Wa[4 * c4] * f, Wa[4 * c4 + 1] * f, Wa[4 * c4 + 2] * f, Wa[4 * c4 + 3] * f});
     }
 }
 
@@ -227,7 +233,11 @@ static int launch_decode_one(const FwdParams &p, hipStream_t s) {
 
 template <int D, typename T>
 static int launch_decode_d(const FwdParams &p, int nq, hipStream_t s) {
-    return nq == 1 ? launch_decode_one<D, T, 1>(p, s) : launch_decode_one<D, T, 4>(p, s);
+    if constexpr (D == 96 || D == 256) {         // wide lanes: one query per block only
+        return nq == 1 ? launch_decode_one<D, T, 1>(p, s) : (int)hipErrorInvalidValue;
+    } else {
+        return nq == 1 ? launch_decode_one<D, T, 1>(p, s) : launch_decode_one<D, T, 4>(p, s);
+    }
 }
 
 // nq = 1 or 4 queries per block (p.tq must say the same).  Dense layout only.
@@ -236,6 +246,8 @@ int launch_fwd_decode(const FwdParams &p, int d, int f16, int nq, hipStream_t s)
     if (d == 32) return f16 ? launch_decode_d<32, _Float16>(p, nq, s) : launch_decode_d<32, float>(p, nq, s);
     if (d == 64) return f16 ? launch_decode_d<64, _Float16>(p, nq, s) : launch_decode_d<64, float>(p, nq, s);
     if (d == 128) return f16 ? launch_decode_d<128, _Float16>(p, nq, s) : launch_decode_d<128, float>(p, nq, s);
+    if (d == 96) return f16 ? launch_decode_d<96, _Float16>(p, nq, s) : launch_decode_d<96, float>(p, nq, s);
+    if (d == 256) return f16 ? launch_decode_d<256, _Float16>(p, nq, s) : launch_decode_d<256, float>(p, nq, s);
     return (int)hipErrorInvalidValue;
 }
 

@@ -36,6 +36,10 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     constexpr int QPR = D / 4;              // 4-element groups per row
     constexpr int LPT = TKB * QPR / NT;     // staged groups per thread per tensor
     constexpr int MB = D / 32;              // 32-row blocks of W^T
+    // Row r of block mb of W^T is value column MB*r + mb (a lane reads its MB columns of a key with
+    // one LDS instruction), except for MB = 3 where it is column 32*mb + r (three 4-byte reads).
+    constexpr bool VSPLIT = (MB == 3);
+    constexpr bool PIN = (MB == 1 || MB == 2 || MB == 4);   // scheduling pins are written for these shapes
     static_assert(TKB * QPR % NT == 0, "tile must divide evenly over the threads");
     static_assert(KS % 32 == 0, "a wave consumes keys 32 at a time");
 
@@ -192,13 +196,15 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                     kf = kn;
                 }
                 // pin the order: two fragment reads in flight ahead of every group of MFMAs
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                if constexpr (PIN) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
-                for (int cc = 0; cc < D / 8 - 2; ++cc) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 4 * NQ, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    for (int cc = 0; cc < D / 8 - 2; ++cc) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 4 * NQ, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 8 * NQ, 0);
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, 8 * NQ, 0);
 #pragma unroll
                 for (int nq = 0; nq < NQ; ++nq) {
                     if constexpr (NACC == 1) sacc[nq] = part[nq][0];
@@ -254,7 +260,19 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
             // ---- (a4) W^T += V^T P^T.  Step i contracts keys 8g+t (lower half-wave) and
             // 8g+4+t (upper), which is where accumulator register i = 4g+t holds them.
             // Row r of block mb of W^T is value column MB*r + mb.
-            {
+            if constexpr (VSPLIT) {
+                const float *vcol = &Vb[(kl + 4 * h) * VROW + j];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const float *vk = vcol + (8 * (i >> 2) + (i & 3)) * VROW;
+#pragma unroll
+                    for (int mb = 0; mb < MB; ++mb) {
+                        const float vx = vk[32 * mb];
+#pragma unroll
+                        for (int nq = 0; nq < NQ; ++nq) oacc[nq][mb] = mfma32(vx, sacc[nq][i], oacc[nq][mb]);
+                    }
+                }
+            } else {
                 typedef float vfrag __attribute__((ext_vector_type(MB)));
                 const float *vcol = &Vb[(kl + 4 * h) * VROW + MB * j];
                 vfrag vf = *reinterpret_cast<const vfrag *>(vcol);
@@ -269,13 +287,15 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                         for (int nq = 0; nq < NQ; ++nq) oacc[nq][mb] = mfma32(vf[mb], sacc[nq][i], oacc[nq][mb]);
                     vf = vn;
                 }
-                __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                if constexpr (PIN) {
+                    __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
 #pragma unroll
-                for (int i = 0; i < 14; ++i) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, MB * NQ, 0);
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    for (int i = 0; i < 14; ++i) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, MB * NQ, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                    }
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2 * MB * NQ, 0);
                 }
-                __builtin_amdgcn_sched_group_barrier(0x008, 2 * MB * NQ, 0);
             }
         }
         if (t + 1 < ntiles) lstore(buf ^ 1);
@@ -379,13 +399,22 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                                      oacc[nq][0][4 * g + t2 + 1] * f, oacc[nq][1][4 * g + t2 + 1] * f};
                     emit(obase + 2 * (8 * g + 4 * h + t2), x);
                 }
+            } else if constexpr (MB == 3) {
+#pragma unroll
+                for (int mb = 0; mb < 3; ++mb) {
+                    const f32x4 x = {oacc[nq][mb][4 * g] * f, oacc[nq][mb][4 * g + 1] * f, oacc[nq][mb][4 * g + 2] * f,
+                                     oacc[nq][mb][4 * g + 3] * f};
+                    emit(obase + 32 * mb + 8 * g + 4 * h, x);
+                }
             } else {
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const f32x4 x = {oacc[nq][0][4 * g + t] * f, oacc[nq][1][4 * g + t] * f,
-                                     oacc[nq][2][4 * g + t] * f, oacc[nq][3][4 * g + t] * f};
-                    emit(obase + 4 * (8 * g + 4 * h + t), x);
-                }
+                for (int t = 0; t < 4; ++t)
+#pragma unroll
+                    for (int m4 = 0; m4 < MB; m4 += 4) {
+                        const f32x4 x = {oacc[nq][m4][4 * g + t] * f, oacc[nq][m4 + 1][4 * g + t] * f,
+                                         oacc[nq][m4 + 2][4 * g + t] * f, oacc[nq][m4 + 3][4 * g + t] * f};
+                        emit(obase + MB * (8 * g + 4 * h + t) + m4, x);
+                    }
             }
         }
     }
@@ -406,9 +435,9 @@ static const char *kNames[kMfmaVariants] = {"mfma_q128_w4",   "mfma_q256_w4",   
 int mfma_variant_tq(int variant, int d) {
     switch (variant) {
         case 1: case 5: case 6: case 7: case 8: return 128;
-        case 2: return d == 128 ? 128 : 256;
-        case 4: return d == 128 ? 128 : 256;
-        case 3: return d == 128 ? 64 : 32;      // d = 128: two query waves x two key waves
+        case 2: return d <= 64 ? 256 : 128;
+        case 4: return d <= 64 ? 256 : 128;
+        case 3: return d == 256 ? 128 : d <= 64 ? 32 : 64;   // d = 96, 128: two query waves x two key waves
         case 9: return 64;                      // one wave per 64 (32) query rows, no LDS
         case 10: return 32;
         default: return 0;
@@ -442,6 +471,15 @@ static int launch_one(const FwdParams &p, hipStream_t s) {
 
 template <int D, typename T>
 static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
+    // d = 96 and d = 256: one tile shape (128 rows, 32-key tiles; two waves per SIMD at d = 96, one at
+    // d = 256 where the state and the query fragment fill the register file) and, for d = 96, the
+    // key-splitting shape
+    if constexpr (D == 96) {
+        if (variant == 3) return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
+        return launch_one<D, T, 1, 4, 1, 32, 2, 2, 1>(p, s);
+    } else if constexpr (D == 256) {
+        return launch_one<D, T, 1, 4, 1, 32, 1, 1, 1>(p, s);
+    } else {
     // keys per LDS buffer: 64 for d <= 64, 32 for d = 128 (same bytes)
     constexpr int KS = D == 128 ? 32 : 64;
     switch (variant) {
@@ -466,6 +504,7 @@ static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
         case 8: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 0>(p, s);
         default: return (int)hipErrorInvalidValue;
     }
+    }
 }
 
 int launch_fwd_mfma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name) {
@@ -474,6 +513,8 @@ int launch_fwd_mfma(const FwdParams &p, int d, int f16, int variant, hipStream_t
     if (d == 32) return f16 ? launch_variant<32, _Float16>(p, variant, s) : launch_variant<32, float>(p, variant, s);
     if (d == 64) return f16 ? launch_variant<64, _Float16>(p, variant, s) : launch_variant<64, float>(p, variant, s);
     if (d == 128) return f16 ? launch_variant<128, _Float16>(p, variant, s) : launch_variant<128, float>(p, variant, s);
+    if (d == 96) return f16 ? launch_variant<96, _Float16>(p, variant, s) : launch_variant<96, float>(p, variant, s);
+    if (d == 256) return f16 ? launch_variant<256, _Float16>(p, variant, s) : launch_variant<256, float>(p, variant, s);
     return (int)hipErrorInvalidValue;
 }
 

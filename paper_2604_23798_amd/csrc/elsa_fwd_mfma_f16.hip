@@ -350,8 +350,8 @@ static const char *kNames16[kMfma16Variants] = {"mfma16_q128_w4", "mfma16_q256_w
 int mfma16_variant_tq(int variant, int d) {
     switch (variant) {
         case 1: return 128;
-        case 2: return d == 128 ? 128 : 256;
-        case 3: return d == 128 ? 64 : 32;
+        case 2: return d <= 64 ? 256 : 128;
+        case 3: return d <= 64 ? 32 : 64;       // d >= 96: two query waves x two key waves
         default: return 0;
     }
 }
@@ -383,6 +383,14 @@ static int launch_one16(const FwdParams &p, hipStream_t s) {
 
 template <int D>
 static int launch_variant16(const FwdParams &p, int variant, hipStream_t s) {
+    // d = 96, 256: one query group per wave; 32-key tiles at d = 256 keep two blocks per CU in LDS
+    if constexpr (D == 96) {
+        if (variant == 3) return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
+        return launch_one16<D, 1, 4, 1, 64, 2>(p, s);
+    } else if constexpr (D == 256) {
+        if (variant == 3) return launch_one16<D, 1, 2, 2, 32, 1>(p, s);
+        return launch_one16<D, 1, 4, 1, 32, 2>(p, s);
+    } else
     switch (variant) {
         case 1: return launch_one16<D, 1, 4, 1, 64, 2>(p, s);
         case 2:
@@ -400,6 +408,8 @@ int launch_fwd_mfma16(const FwdParams &p, int d, int variant, hipStream_t s, con
     if (d == 32) return launch_variant16<32>(p, variant, s);
     if (d == 64) return launch_variant16<64>(p, variant, s);
     if (d == 128) return launch_variant16<128>(p, variant, s);
+    if (d == 96) return launch_variant16<96>(p, variant, s);
+    if (d == 256) return launch_variant16<256>(p, variant, s);
     return (int)hipErrorInvalidValue;
 }
 

@@ -68,7 +68,7 @@ def test_bad_arguments_are_rejected_before_any_launch():
                                        kw.get("dtype", 0), None)
     assert f(q=None) == INV and f(out=None) == INV
     assert f(B=0) == INV and f(H=-1) == INV and f(n=0) == INV
-    assert f(d=48) == UNS and f(d=256) == UNS and f(dtype=2) == UNS
+    assert f(d=48) == UNS and f(d=192) == UNS and f(dtype=2) == UNS
     assert f(scale=float("nan")) == INV and f(scale=float("inf")) == INV
     assert f(n=1 << 24, d=128) == UNS          # one K slice of 8 GiB: beyond the 2 GiB buffer range
     s = lambda C, **kw: lib.elsa_attn_fwd_split_kv(p, p, p, kw.get("pm", p), p, p, 1, 1, 8, 64, 0.125, 0, None, C, 0, None)
@@ -82,14 +82,14 @@ def test_bad_arguments_are_rejected_before_any_launch():
     vl = lambda **kw: lib.elsa_attn_fwd_varlen(p, p, p, p, kw.get("cu", p), kw.get("ns", 2), kw.get("T", 64),
                                                kw.get("mx", 40), 2, kw.get("d", 64), 0.125, 0, 0, None)
     assert vl(cu=None) == INV and vl(ns=0) == INV and vl(ns=5000) == INV and vl(T=0) == INV
-    assert vl(mx=0) == INV and vl(mx=65) == INV and vl(d=96) == UNS
+    assert vl(mx=0) == INV and vl(mx=65) == INV and vl(d=80) == UNS
     x = lambda **kw: lib.elsa_attn_fwd_cross(kw.get("q", p), p, p, p, None, 1, 1, kw.get("nq", 4), kw.get("nk", 8),
                                              kw.get("d", 64), 0.125, 0, None, 0, None)
-    assert x(q=None) == INV and x(nq=0) == INV and x(nk=0) == INV and x(nk=-3) == INV and x(d=96) == UNS
+    assert x(q=None) == INV and x(nq=0) == INV and x(nk=0) == INV and x(nk=-3) == INV and x(d=80) == UNS
     assert x(nq=1, nk=1 << 24, d=128) == UNS   # the key slice, not the query count, sets the limit
     st = lambda **kw: lib.elsa_attn_stream_step(kw.get("q", p), p, p, kw.get("state", p), 1, 1, kw.get("nq", 4),
                                                 kw.get("nc", 8), kw.get("d", 64), 0.125, 0, 0, None, 1, 0, None)
-    assert st(q=None) == INV and st(state=None) == INV and st(nq=0) == INV and st(nc=0) == INV and st(d=96) == UNS
+    assert st(q=None) == INV and st(state=None) == INV and st(nq=0) == INV and st(nc=0) == INV and st(d=80) == UNS
     assert st(state=ctypes.c_void_p(8)) == 3
     fin = lambda **kw: lib.elsa_attn_stream_finish(kw.get("state", p), kw.get("out", p), None, 1, 1, 4, kw.get("d", 64), 0, None)
     assert fin(state=None) == INV and fin(out=None) == INV and fin(d=5) == UNS and fin(state=ctypes.c_void_p(8)) == 3
