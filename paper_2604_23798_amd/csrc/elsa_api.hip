@@ -45,7 +45,7 @@ int variant_tq(int path, int variant, int d) {
 // within 2 % of the fastest configuration at every size while using two score chains; d = 128
 // uses the 128-row tile [1]; when fewer than 192 such blocks exist, the configuration whose waves
 // split the key range [3].  The 256-row tiles [2, 4] are opt-in.
-int pick_variant(int path, long long BH, int n, int nk, int d, int splits) {
+int pick_variant(int path, long long BH, int n, int nk, int d, int splits, int causal) {
     if (g.opt[ELSA_OPT_VARIANT] >= 1 && g.opt[ELSA_OPT_VARIANT] <= variant_count(path)) return g.opt[ELSA_OPT_VARIANT];
     // one query tile against a long key range: the waves of a block split the keys, not the queries
     if (path != 1 && (long long)n * 8 <= nk && n <= variant_tq(path, 3, d)) return 3;
@@ -55,7 +55,9 @@ int pick_variant(int path, long long BH, int n, int nk, int d, int splits) {
     }
     const long long b256 = BH * ((n + 255) / 256) * splits;
     const long long b128 = BH * ((n + 127) / 128) * splits;
-    if (path == 3) return (d <= 64 && b256 >= 2 * kNumCu) ? 2 : (b128 >= (3 * kNumCu) / 4 ? 1 : 3);
+    // FP16: the 256-row tile wins only without a causal mask (its diagonal tiles waste twice as much:
+    // 436 vs 287 TFLOP/s at n = 4096, 794 vs 756 at n = 16384, causal, d = 64)
+    if (path == 3) return (d <= 64 && b256 >= 2 * kNumCu && !causal) ? 2 : (b128 >= (3 * kNumCu) / 4 ? 1 : 3);
     if (b128 < (3 * kNumCu) / 4) return 3;
     return d <= 64 ? 7 : 1;
 }
@@ -105,7 +107,7 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     const long long tok_stride = cu_seqlens ? (long long)H * d : d;
     const long long longest = cu_seqlens ? total_tokens : (nk > n ? nk : n);
     if ((path != 1 || decode_variant) && longest * tok_stride * (dtype == ELSA_F16 ? 2 : 4) >= 0x7fffffffLL) return ELSA_ERR_UNSUPPORTED;
-    int variant = decode_variant ? decode_variant : pick_variant(path, (long long)B * H, n, nk, d, num_splits);
+    int variant = decode_variant ? decode_variant : pick_variant(path, (long long)B * H, n, nk, d, num_splits, causal);
     if (path == 2) {
         const bool ok = small_kernel_ok(cu_seqlens, num_splits, emit, n, nk);
         if (g.opt[ELSA_OPT_VARIANT] == 0 && ok && !head_dim_wide(d) && n <= 128 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu)
