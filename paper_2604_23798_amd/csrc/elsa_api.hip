@@ -7,7 +7,7 @@
 namespace {
 
 struct State {
-    int opt[4] = {0, 0, 0, 0};
+    int opt[5] = {0, 0, 0, 0, 0};
     void *ws = nullptr;
     size_t ws_bytes = 0;
     const char *last = "";
@@ -15,7 +15,7 @@ struct State {
 
 constexpr int kMaxSplits = 65535;
 constexpr int kMaxSeqs = 4096;       // the tile -> sequence lookup walks the list linearly
-constexpr int kNumCu = 256;
+using elsa::kNumCu;
 
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -138,6 +138,7 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     // every sequence wastes at most one partly filled tile
     p.var_tiles = cu_seqlens ? (int)(((long long)total_tokens + tq - 1) / tq + num_seqs) : 0;
     p.xcd_map = g.opt[ELSA_OPT_XCD_MAP];
+    p.snake = g.opt[ELSA_OPT_SNAKE] == 1 ? 0 : 1;
     const long long total = (long long)p.q_tiles * B * H * num_splits;
     if (total > 0x7fffffffLL - 8) return ELSA_ERR_INVALID_ARG;
     const char *name = nullptr;
@@ -315,10 +316,11 @@ int elsa_attn_stream_finish(const void *state, void *out, float *lse, int B, int
 }
 
 int elsa_set_option(int option, int value) {
-    if (option < 0 || option > 3) return ELSA_ERR_UNSUPPORTED;
+    if (option < 0 || option > 4) return ELSA_ERR_UNSUPPORTED;
     if (value < 0) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_PATH && value > 3) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_XCD_MAP && value > 2) return ELSA_ERR_INVALID_ARG;
+    if (option == ELSA_OPT_SNAKE && value > 1) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_SPLITS && value > kMaxSplits) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_VARIANT && value > 32) return ELSA_ERR_INVALID_ARG;
     g.opt[option] = value;
@@ -326,7 +328,7 @@ int elsa_set_option(int option, int value) {
 }
 
 int elsa_get_option(int option, int *value) {
-    if (option < 0 || option > 3) return ELSA_ERR_UNSUPPORTED;
+    if (option < 0 || option > 4) return ELSA_ERR_UNSUPPORTED;
     if (!value) return ELSA_ERR_INVALID_ARG;
     *value = g.opt[option];
     return ELSA_OK;

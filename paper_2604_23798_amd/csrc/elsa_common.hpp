@@ -15,6 +15,7 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kNumXcd = 8;  // MI355X: 8 accelerator dies, blocks are dealt to them round-robin
+constexpr int kNumCu = 256; // compute units
 
 // One forward launch.  Scores are held in log2 units inside the kernels: Q is
 // multiplied by qscale = scale * log2(e) once when it is loaded, so every
@@ -34,6 +35,7 @@ struct FwdParams {
     int emit_partials;               // 1: write (m,S,W) states instead of out
     int accumulate;                  // 1 (with emit_partials, num_splits == 1, log2-unit m): merge the new state
                                      //    into the one already stored at part_m/S/W (streamed key chunks)
+    int snake;                       // causal work order: 1 = second run of blocks reversed (see decode_work), 0 = plain
     int coff;                        // dense layout, causal: key j is visible to query i iff j <= i + coff
     int m_natural;                   // 1: part_m in natural-log units, 0: log2 units (internal)
     int xcd_map;                     // block -> work item order, see decode_work
@@ -145,6 +147,14 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
     }
     r.valid = w < total;
     if (p.xcd_map == 0) {
+        if (p.causal && p.snake && r.valid && w >= kNumCu && w < 2 * kNumCu) {
+            // Longest tiles first -- but the first 2*kNumCu blocks are all resident at once, placed
+            // round-robin, with no dynamic balancing among them: the second run of kNumCu is walked
+            // backwards, so that the k-th longest tile shares its CU with the k-th shortest of the
+            // two runs.  Later blocks fill slots as they free up, in descending order.
+            const long long last = total < 2 * kNumCu ? total : 2 * kNumCu;
+            w = kNumCu + (last - 1 - w);
+        }
         r.bh = w % BH;
         const long long t = w / BH;
         r.c = (int)(t % p.num_splits);

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libelsa.so")
 
 F32, F16 = 0, 1
-OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP = 0, 1, 2, 3
+OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP, OPT_SNAKE = 0, 1, 2, 3, 4
 PATH_AUTO, PATH_FMA, PATH_MFMA, PATH_MFMA16 = 0, 1, 2, 3
 
 EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_lse", "elsa_attn_fwd_cross", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",

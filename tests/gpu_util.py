@@ -13,8 +13,8 @@ def have_gpu():
 class Options:
     """Set libelsa options for a block of code and restore the defaults afterwards."""
 
-    def __init__(self, path=0, variant=0, splits=0, xcd_map=0):
-        self.vals = (path, variant, splits, xcd_map)
+    def __init__(self, path=0, variant=0, splits=0, xcd_map=0, snake=0):
+        self.vals = (path, variant, splits, xcd_map, snake)
 
     def __enter__(self):
         from paper_2604_23798_amd import elsa
@@ -24,7 +24,7 @@ class Options:
 
     def __exit__(self, *a):
         from paper_2604_23798_amd import elsa
-        for o in range(4):
+        for o in range(5):
             elsa.elsa_set_option(o, 0)
         return False
 

@@ -362,3 +362,18 @@ def test_deterministic_and_option_reporting():
     with G.Options(path=MFMA, variant=1, xcd_map=1):
         d_ = G.fwd(q, k, v, 0.125)
     assert np.array_equal(c, d_)            # the block-to-work mapping does not change any result
+
+
+def test_causal_work_orders_give_identical_results():
+    """Block -> work item maps are permutations: every order must produce the same bits."""
+    w = inputs.sweep(2048).with_(causal=True, H=20, name="order")     # 320 blocks: the reversed run is partial
+    q, k, v, _ = inputs.make(w)
+    rows = inputs.sample_rows(w, per_head=16)
+    ref = oracle.attn_rows(q, k, v, w.scale, causal=True, rows=rows)
+    for path in (0, 1):
+        outs = []
+        for opts in (dict(snake=1), dict(snake=0), dict(xcd_map=1), dict(xcd_map=2)):
+            with G.Options(path=path, **opts):
+                outs.append(G.fwd(q, k, v, w.scale, causal=True))
+            assert np.array_equal(outs[-1], outs[0]), (path, opts)
+        assert_parity(outs[0][rows], ref, tolerance(w.n), "order parity path %d" % path)
