@@ -35,6 +35,7 @@ struct FwdParams {
     int emit_partials;               // 1: write (m,S,W) states instead of out
     int accumulate;                  // 1 (with emit_partials, num_splits == 1, log2-unit m): merge the new state
                                      //    into the one already stored at part_m/S/W (streamed key chunks)
+    int sort_batches;                // 1: dense, non-causal, key padding, B <= 32: batch entries in descending kv_len order
     int snake;                       // causal work order: 1 = second run of blocks reversed (see decode_work), 0 = plain
     int coff;                        // dense layout, causal: key j is visible to query i iff j <= i + coff
     int m_natural;                   // 1: part_m in natural-log units, 0: log2 units (internal)
@@ -155,10 +156,39 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
             const long long last = total < 2 * kNumCu ? total : 2 * kNumCu;
             w = kNumCu + (last - 1 - w);
         }
-        r.bh = w % BH;
-        const long long t = w / BH;
-        r.c = (int)(t % p.num_splits);
-        r.qt = (int)(t / p.num_splits);
+        if (p.sort_batches && r.valid) {
+            // Key padding: the work of a block is set by kv_len of its batch entry.  Batch entries are
+            // taken longest first (their ranks are recomputed by every block from the B lengths, B <=
+            // 32), all (head, tile, chunk) items of an entry side by side, and the second run of
+            // kNumCu blocks is walked backwards as for causal launches.
+            if (w >= kNumCu && w < 2 * kNumCu) {
+                const long long last = total < 2 * kNumCu ? total : 2 * kNumCu;
+                w = kNumCu + (last - 1 - w);
+            }
+            const long long per_b = (long long)p.H * p.q_tiles * p.num_splits;
+            const int slot = (int)(w / per_b);                  // rank of the batch entry this block serves
+            const long long rem = w % per_b;
+            // lane l < B holds the length of entry l and counts the entries that precede it in the
+            // order (longer, or equal and earlier); the entry whose count equals the slot is ours
+            const int ln = (int)(threadIdx.x & 63);
+            const int mylen = ln < p.B ? min(max(p.kv_len[ln], 0), p.nk) : -1;
+            int rank = 0;
+            for (int o = 0; o < p.B; ++o) {
+                const int lo = __builtin_amdgcn_readlane(mylen, o);
+                rank += (lo > mylen || (lo == mylen && o < ln)) ? 1 : 0;
+            }
+            const unsigned long long hit = __builtin_amdgcn_ballot_w64(ln < p.B && rank == slot);
+            const int b = hit ? __builtin_ctzll(hit) : 0;
+            r.bh = (long long)b * p.H + rem % p.H;
+            const long long t = rem / p.H;
+            r.c = (int)(t % p.num_splits);
+            r.qt = (int)(t / p.num_splits);
+        } else {
+            r.bh = w % BH;
+            const long long t = w / BH;
+            r.c = (int)(t % p.num_splits);
+            r.qt = (int)(t / p.num_splits);
+        }
     } else {
         r.qt = (int)(w % p.q_tiles);
         const long long t = w / p.q_tiles;

@@ -377,3 +377,19 @@ def test_causal_work_orders_give_identical_results():
                 outs.append(G.fwd(q, k, v, w.scale, causal=True))
             assert np.array_equal(outs[-1], outs[0]), (path, opts)
         assert_parity(outs[0][rows], ref, tolerance(w.n), "order parity path %d" % path)
+
+
+def test_padded_batches_sorted_by_length_give_identical_results():
+    """Key padding: batch entries are served longest first (ranks recomputed on the device); the order
+    is a permutation of the work items, so the bits cannot change.  Ties and zero lengths included."""
+    B, H, n, d = 9, 3, 300, 64
+    q, k, v = _rand(B, H, n, d, 4242)
+    kv_len = np.array([300, 17, 300, 0, 128, 129, 17, 299, 1], np.int32)
+    ref = oracle.attn_rows(q, k, v, 0.125, kv_len=kv_len)
+    for path in (0, 1):
+        outs = []
+        for opts in (dict(snake=1), dict(snake=0)):
+            with G.Options(path=path, **opts):
+                outs.append(G.fwd(q, k, v, 0.125, kv_len=kv_len))
+        assert np.array_equal(outs[0], outs[1]), path
+        assert_parity(outs[1], ref, tolerance(n), "sorted padded batches path %d" % path)
