@@ -114,18 +114,54 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
     if (p.cu_seqlens) {
         // packed sequences: the head index runs fastest; the tile's sequence is found by walking
         // the (short) list of sequence lengths, every value being wave-uniform
-        const long long w = blockIdx.x;
-        const int hd = (int)(w % p.H);
-        const int t = (int)(w / p.H);
+        long long w = blockIdx.x;
         // offsets are clamped so that a malformed list cannot send an access outside the tensors
         int s = 0, before = 0, len = 0, tiles = 0, beg = 0;
-        for (; s < p.num_seqs; ++s) {
-            beg = min(max(p.cu_seqlens[s], 0), p.total_tokens);
-            len = min(max(p.cu_seqlens[s + 1], beg), p.total_tokens) - beg;
-            tiles = len > 0 ? (len + p.tq - 1) / p.tq : 0;
-            if (t < before + tiles) break;
-            before += tiles;
+        if (p.num_seqs <= 64 && p.snake) {
+            // Up to 64 sequences: longest first (the work of a tile grows with its sequence), ranks
+            // computed across the lanes as for padded batches, and the second run of kNumCu blocks
+            // walked backwards (positions beyond the last real tile stay invalid: the bound on the
+            // tile count is the same for every block, so the reversal is a bijection).
+            const long long bound = (long long)p.var_tiles * p.H;
+            if (w >= kNumCu && w < 2 * kNumCu && w < bound) {
+                const long long last = bound < 2 * kNumCu ? bound : 2 * kNumCu;
+                w = kNumCu + (last - 1 - w);
+            }
+            const int ln = (int)(threadIdx.x & 63);
+            int mybeg = 0, mylen = -1;
+            if (ln < p.num_seqs) {
+                mybeg = min(max(p.cu_seqlens[ln], 0), p.total_tokens);
+                mylen = min(max(p.cu_seqlens[ln + 1], mybeg), p.total_tokens) - mybeg;
+            }
+            int rank = 0;
+            for (int o = 0; o < p.num_seqs; ++o) {
+                const int lo = __builtin_amdgcn_readlane(mylen, o);
+                rank += (lo > mylen || (lo == mylen && o < ln)) ? 1 : 0;
+            }
+            const int t = (int)(w / p.H);
+            int k = 0;
+            for (; k < p.num_seqs; ++k) {
+                const unsigned long long hit = __builtin_amdgcn_ballot_w64(ln < p.num_seqs && rank == k);
+                s = hit ? __builtin_ctzll(hit) : 0;
+                beg = __builtin_amdgcn_readlane(mybeg, s);
+                len = __builtin_amdgcn_readlane(mylen, s);
+                tiles = len > 0 ? (len + p.tq - 1) / p.tq : 0;
+                if (t < before + tiles) break;
+                before += tiles;
+            }
+            if (k >= p.num_seqs) s = p.num_seqs;
+        } else {
+            const int t = (int)(w / p.H);
+            for (; s < p.num_seqs; ++s) {
+                beg = min(max(p.cu_seqlens[s], 0), p.total_tokens);
+                len = min(max(p.cu_seqlens[s + 1], beg), p.total_tokens) - beg;
+                tiles = len > 0 ? (len + p.tq - 1) / p.tq : 0;
+                if (t < before + tiles) break;
+                before += tiles;
+            }
         }
+        const int hd = (int)(w % p.H);
+        const int t = (int)(w / p.H);
         r.valid = s < p.num_seqs;
         r.c = 0;
         r.bh = (long long)s * p.H + hd;

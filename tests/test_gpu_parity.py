@@ -393,3 +393,18 @@ def test_padded_batches_sorted_by_length_give_identical_results():
                 outs.append(G.fwd(q, k, v, 0.125, kv_len=kv_len))
         assert np.array_equal(outs[0], outs[1]), path
         assert_parity(outs[1], ref, tolerance(n), "sorted padded batches path %d" % path)
+
+
+@pytest.mark.parametrize("causal", [False, True])
+def test_packed_sequences_sorted_by_length_give_identical_results(causal):
+    """Up to 64 packed sequences are served longest first; more than 64 in list order.  Either way
+    the bits are those of the plain order."""
+    for lengths in ([700, 3, 512, 0, 129, 700, 64, 1], list(range(1, 71))):
+        q, k, v, cu = inputs.make_varlen(4343, H=3, d=64, lengths=lengths)
+        ref = oracle.attn_varlen(q, k, v, cu, 0.125, causal=causal)
+        outs = []
+        for opts in (dict(snake=1), dict(snake=0)):
+            with G.Options(**opts):
+                outs.append(G.fwd_varlen(q, k, v, cu, max(lengths), 0.125, causal=causal))
+        assert np.array_equal(outs[0], outs[1]), len(lengths)
+        assert_parity(outs[1].reshape(-1, 64), ref.reshape(-1, 64), tolerance(max(lengths)), "sorted packed sequences")
