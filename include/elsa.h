@@ -187,9 +187,10 @@ int elsa_set_workspace(void *dev_ptr, size_t bytes);
  *   ELSA_OPT_XCD_MAP  block -> work order: 0 = head index fastest, longest causal tiles of all
  *                     heads first (default); 1 = query tile fastest; 2 = as 1, consecutive work
  *                     items steered to the same XCD
- *   ELSA_OPT_SNAKE    work order 0 of causal or key-padded launches: 0 = longest work first (padded
- *                     batch entries by descending kv_len when 2 <= B <= 32) with the second run of
- *                     256 blocks walked backwards (balances the blocks that are resident together),
+ *   ELSA_OPT_SNAKE    work order 0 of causal, key-padded or packed launches: 0 = longest work first
+ *                     (padded batch entries by descending kv_len when 2 <= B <= 32, packed sequences
+ *                     by descending length when there are at most 64) with the second run of 256
+ *                     blocks walked backwards (balances the blocks that are resident together),
  *                     1 = plain order
  */
 enum { ELSA_OPT_PATH = 0, ELSA_OPT_VARIANT = 1, ELSA_OPT_SPLITS = 2, ELSA_OPT_XCD_MAP = 3, ELSA_OPT_SNAKE = 4 };

@@ -139,7 +139,7 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     p.var_tiles = cu_seqlens ? (int)(((long long)total_tokens + tq - 1) / tq + num_seqs) : 0;
     p.xcd_map = g.opt[ELSA_OPT_XCD_MAP];
     p.snake = g.opt[ELSA_OPT_SNAKE] == 1 ? 0 : 1;
-    p.sort_batches = (kv_len && !cu_seqlens && !causal && B >= 2 && B <= 32 && p.snake && p.xcd_map == 0) ? 1 : 0;
+    p.sort_batches = (kv_len && !cu_seqlens && (!causal || p.q_tiles == 1) && B >= 2 && B <= 32 && p.snake && p.xcd_map == 0) ? 1 : 0;
     const long long total = (long long)p.q_tiles * B * H * num_splits;
     if (total > 0x7fffffffLL - 8) return ELSA_ERR_INVALID_ARG;
     const char *name = nullptr;

@@ -35,7 +35,8 @@ struct FwdParams {
     int emit_partials;               // 1: write (m,S,W) states instead of out
     int accumulate;                  // 1 (with emit_partials, num_splits == 1, log2-unit m): merge the new state
                                      //    into the one already stored at part_m/S/W (streamed key chunks)
-    int sort_batches;                // 1: dense, non-causal, key padding, B <= 32: batch entries in descending kv_len order
+    int sort_batches;                // 1: dense, key padding, B <= 32, non-causal or a single query tile: batch entries in
+                                     //    descending kv_len order
     int snake;                       // causal work order: 1 = second run of blocks reversed (see decode_work), 0 = plain
     int coff;                        // dense layout, causal: key j is visible to query i iff j <= i + coff
     int m_natural;                   // 1: part_m in natural-log units, 0: log2 units (internal)
@@ -184,7 +185,7 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
     }
     r.valid = w < total;
     if (p.xcd_map == 0) {
-        if (p.causal && p.snake && r.valid && w >= kNumCu && w < 2 * kNumCu) {
+        if (p.causal && p.snake && !p.sort_batches && r.valid && w >= kNumCu && w < 2 * kNumCu) {
             // Longest tiles first -- but the first 2*kNumCu blocks are all resident at once, placed
             // round-robin, with no dynamic balancing among them: the second run of kNumCu is walked
             // backwards, so that the k-th longest tile shares its CU with the k-th shortest of the
