@@ -185,13 +185,20 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
     }
     r.valid = w < total;
     if (p.xcd_map == 0) {
-        if (p.causal && p.snake && !p.sort_batches && r.valid && w >= kNumCu && w < 2 * kNumCu) {
-            // Longest tiles first -- but the first 2*kNumCu blocks are all resident at once, placed
-            // round-robin, with no dynamic balancing among them: the second run of kNumCu is walked
-            // backwards, so that the k-th longest tile shares its CU with the k-th shortest of the
-            // two runs.  Later blocks fill slots as they free up, in descending order.
-            const long long last = total < 2 * kNumCu ? total : 2 * kNumCu;
-            w = kNumCu + (last - 1 - w);
+        if (p.causal && p.snake && !p.sort_batches && r.valid) {
+            // Longest tiles first -- but the first blocks are all resident at once, placed round-robin
+            // over the CUs, with no dynamic balancing among them: the second run of kNumCu blocks is
+            // walked backwards, so that the k-th longest tile shares its CU with the k-th shortest of
+            // the two runs; later blocks fill slots as they free up, in descending order.  A launch of
+            // exactly four runs does best with its whole second half reversed (the fourth block of a
+            // CU then lands where the shortest resident one finishes first, and all sums are equal).
+            if (total > 3 * kNumCu && total <= 4 * kNumCu) {
+                const long long half = total / 2;
+                if (w >= half) w = half + (total - 1 - w);
+            } else if (w >= kNumCu && w < 2 * kNumCu) {
+                const long long last = total < 2 * kNumCu ? total : 2 * kNumCu;
+                w = kNumCu + (last - 1 - w);
+            }
         }
         if (p.sort_batches && r.valid) {
             // Key padding: the work of a block is set by kv_len of its batch entry.  Batch entries are

@@ -366,17 +366,19 @@ def test_deterministic_and_option_reporting():
 
 def test_causal_work_orders_give_identical_results():
     """Block -> work item maps are permutations: every order must produce the same bits."""
-    w = inputs.sweep(2048).with_(causal=True, H=20, name="order")     # 320 blocks: the reversed run is partial
-    q, k, v, _ = inputs.make(w)
-    rows = inputs.sample_rows(w, per_head=16)
-    ref = oracle.attn_rows(q, k, v, w.scale, causal=True, rows=rows)
-    for path in (0, 1):
-        outs = []
-        for opts in (dict(snake=1), dict(snake=0), dict(xcd_map=1), dict(xcd_map=2)):
-            with G.Options(path=path, **opts):
-                outs.append(G.fwd(q, k, v, w.scale, causal=True))
-            assert np.array_equal(outs[-1], outs[0]), (path, opts)
-        assert_parity(outs[0][rows], ref, tolerance(w.n), "order parity path %d" % path)
+    # 320 blocks: the reversed run is partial; 960 blocks: the whole second half is reversed
+    for w, paths in ((inputs.sweep(2048).with_(causal=True, H=20, name="order"), (0, 1)),
+                     (inputs.sweep(8192).with_(causal=True, H=15, name="order4"), (0,))):
+        q, k, v, _ = inputs.make(w)
+        rows = inputs.sample_rows(w, per_head=16)
+        ref = oracle.attn_rows(q, k, v, w.scale, causal=True, rows=rows)
+        for path in paths:
+            outs = []
+            for opts in (dict(snake=1), dict(snake=0), dict(xcd_map=1), dict(xcd_map=2)):
+                with G.Options(path=path, **opts):
+                    outs.append(G.fwd(q, k, v, w.scale, causal=True))
+                assert np.array_equal(outs[-1], outs[0]), (w.name, path, opts)
+            assert_parity(outs[0][rows], ref, tolerance(w.n), "order parity %s path %d" % (w.name, path))
 
 
 def test_padded_batches_sorted_by_length_give_identical_results():
