@@ -9,8 +9,11 @@
 // lanes of a key add their partial sums with DPP row operations (no LDS), and every lane folds
 // the (key, score) pair into its OWN monoid state (m, S, W[8 columns]) with the merge operator of
 // Eq. 3.  Lanes, waves and -- through the chunk states of Prop. 1 -- blocks cover disjoint key
-// subsets; the states of one block meet in LDS at the end, those of different blocks in the
-// combine kernel.
+// subsets.  At the end the lane states of a wave merge in registers, a log-depth tree of the same
+// operator over DPP rotations, one crossbar swizzle and the half-wave swap; the four wave states
+// meet in LDS, those of different blocks in the combine kernel.
+#include <type_traits>
+
 #include "elsa_common.hpp"
 
 namespace elsa {
@@ -27,6 +30,20 @@ template <int LPR> __device__ __forceinline__ float group_sum(float x) {
     if constexpr (LPR >= 8) x += dpp_get<0x141>(x);  // row_half_mirror: the other quad of each 8
     if constexpr (LPR >= 16) x += dpp_get<0x140>(x); // row_mirror: the other 8 of each 16
     return x;
+}
+
+// Value of the lane `STRIDE` away: a rotation inside the 16-lane row for 4 and 8 (DPP), the lane
+// l ^ 16 (LDS crossbar swizzle, no memory) and the lane l ^ 32 (half-wave swap).
+template <int STRIDE> __device__ __forceinline__ float lane_far(float x, int lane) {
+    if constexpr (STRIDE == 4) return dpp_get<0x124>(x);         // row_ror:4
+    else if constexpr (STRIDE == 8) return dpp_get<0x128>(x);    // row_ror:8
+    else if constexpr (STRIDE == 16)
+        return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, x), 0x401F));
+    else {
+        const unsigned u = __float_as_uint(x);
+        auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+        return __uint_as_float(lane < 32 ? r[1] : r[0]);
+    }
 }
 
 template <typename T> struct Row8;   // 8 consecutive elements of a row, widened to float
@@ -57,7 +74,7 @@ __global__ __launch_bounds__(256) void fwd_decode_kernel(FwdParams p) {
     constexpr int ES = (int)sizeof(T);
     constexpr int NS = 2 + CPL;          // floats of state per (lane, query): m, S, W[CPL]
     static_assert(CPL % 8 == 0 && LPR * CPL == D && (CPL == 8 || NQ == 1), "unsupported shape");
-    __shared__ float st[4 * 64 * NQ * NS];
+    __shared__ float st[4 * LPR * NQ * NS];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -166,14 +183,37 @@ __global__ __launch_bounds__(256) void fwd_decode_kernel(FwdParams p) {
         }
     }
 
-    // ---- the 4 * KPI lane states that share a column slice meet in LDS
+    // ---- in-register tree over the KPI lanes of the wave that share a column slice (log2 KPI levels
+    // of Eq. 3: lanes 4, 8 away inside the row by DPP rotations, 16 and 32 away across the rows);
+    // afterwards the lanes of key group 0 hold the wave's state
+    auto tree_level = [&](auto stride_tag) __attribute__((always_inline)) {
+        constexpr int STRIDE = decltype(stride_tag)::value;
 #pragma unroll
-    for (int iq = 0; iq < NQ; ++iq) {
-        float *dst = &st[((wave * 64 + lane) * NQ + iq) * NS];
-        dst[0] = m[iq];
-        dst[1] = S[iq];
+        for (int iq = 0; iq < NQ; ++iq) {
+            const float mo = lane_far<STRIDE>(m[iq], lane);
+            const float So = lane_far<STRIDE>(S[iq], lane);
+            float fa, fb;
+            m[iq] = merge_factors(m[iq], mo, fa, fb);
+            S[iq] = S[iq] * fa + So * fb;
 #pragma unroll
-        for (int t = 0; t < CPL; ++t) dst[2 + t] = W[iq][t];
+            for (int t = 0; t < CPL; ++t) W[iq][t] = W[iq][t] * fa + lane_far<STRIDE>(W[iq][t], lane) * fb;
+        }
+    };
+    if constexpr (LPR <= 4) tree_level(std::integral_constant<int, 4>{});
+    if constexpr (LPR <= 8) tree_level(std::integral_constant<int, 8>{});
+    tree_level(std::integral_constant<int, 16>{});
+    tree_level(std::integral_constant<int, 32>{});
+
+    // ---- the four wave states meet in LDS
+    if (ksub == 0) {
+#pragma unroll
+        for (int iq = 0; iq < NQ; ++iq) {
+            float *dst = &st[((wave * LPR + cs) * NQ + iq) * NS];
+            dst[0] = m[iq];
+            dst[1] = S[iq];
+#pragma unroll
+            for (int t = 0; t < CPL; ++t) dst[2 + t] = W[iq][t];
+        }
     }
     __syncthreads();
     if (tid >= LPR * NQ) return;         // LPR * NQ <= 64: the threads below are one wave
@@ -183,15 +223,15 @@ __global__ __launch_bounds__(256) void fwd_decode_kernel(FwdParams p) {
     float ma = -INFINITY, Sa = 0.f, Wa[CPL];
 #pragma unroll
     for (int t = 0; t < CPL; ++t) Wa[t] = 0.f;
-    for (int w = 0; w < 4; ++w)
-        for (int ks = 0; ks < KPI; ++ks) {
-            const float *src = &st[((w * 64 + ks * LPR + cs2) * NQ + iq) * NS];
-            float fa, fb;
-            ma = merge_factors(ma, src[0], fa, fb);
-            Sa = Sa * fa + src[1] * fb;
 #pragma unroll
-            for (int t = 0; t < CPL; ++t) Wa[t] = Wa[t] * fa + src[2 + t] * fb;
-        }
+    for (int w = 0; w < 4; ++w) {
+        const float *src = &st[((w * LPR + cs2) * NQ + iq) * NS];
+        float fa, fb;
+        ma = merge_factors(ma, src[0], fa, fb);
+        Sa = Sa * fa + src[1] * fb;
+#pragma unroll
+        for (int t = 0; t < CPL; ++t) Wa[t] = Wa[t] * fa + src[2 + t] * fb;
+    }
     if (p.emit_partials) {
         const long long prow = (bh * p.num_splits + c) * (long long)n + row;
         float fn = 1.f, fold = 0.f;
