@@ -1,0 +1,117 @@
+"""Seeded random sweep over shapes, masks, options and entry points (all inputs valid), every case
+checked against the FP64 oracle.  Meant to catch interactions that the structured tests do not
+enumerate: work orders x key chunks x masks x tile shapes x head dimensions."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2604_23798_amd import inputs
+from tests import gpu_util as G
+from tests.parity import assert_parity, tolerance
+
+pytestmark = pytest.mark.gpu
+f32 = lambda t: t.astype(np.float32)
+
+
+@pytest.fixture(scope="module", autouse=True)
+def _need_gpu():
+    if not G.have_gpu():
+        pytest.skip("no GPU")
+    from paper_2604_23798_amd import elsa  # noqa: F401
+
+
+def _case(rng):
+    d = int(rng.choice([32, 64, 64, 96, 128, 256]))
+    fp16 = bool(rng.integers(0, 2))
+    B = int(rng.integers(1, 5))
+    H = int(rng.integers(1, 5))
+    kind = rng.choice(["square", "square", "cross", "decode", "varlen", "stream"])
+    causal = bool(rng.integers(0, 2))
+    nk = int(rng.choice([1, 7, 31, 32, 33, 64, 100, 129, 257, 500, 777, 1300]))
+    if kind == "square":
+        nq = nk
+    elif kind == "decode":
+        nq = int(rng.integers(1, 5))
+    else:
+        nq = int(rng.choice([1, 5, 33, 64, 130, 300]))
+    use_len = bool(rng.integers(0, 2)) and kind in ("square", "cross", "decode")
+    kv_len = rng.integers(0, nk + 1, size=B).astype(np.int32) if use_len else None
+    opts = {}
+    wide = d in (96, 256)
+    r = rng.integers(0, 4)
+    if r == 1:
+        opts = dict(path=2, variant=int(rng.choice([1, 3] if wide else [1, 2, 3, 4, 7, 8])))
+    elif r == 2 and fp16:
+        opts = dict(path=3, variant=int(rng.choice([1, 2, 3])))
+    elif r == 3 and not wide:
+        opts = dict(path=1, variant=int(rng.choice([1, 2])))
+    opts["snake"] = int(rng.integers(0, 2))
+    opts["xcd_map"] = int(rng.choice([0, 0, 1, 2]))
+    splits = int(rng.choice([0, 0, 2, 3])) if kind in ("square", "cross", "decode") else 0
+    if splits > nk:
+        splits = 0
+    return dict(kind=kind, B=B, H=H, nq=nq, nk=nk, d=d, fp16=fp16, causal=causal, kv_len=kv_len, opts=opts, splits=splits)
+
+
+def _tensors(c, seed):
+    B, H, nq, nk, d = c["B"], c["H"], c["nq"], c["nk"], c["d"]
+    q = inputs.normal(seed, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
+    k = inputs.normal(seed, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
+    v = inputs.normal(seed, 2, 0, B * H * nk * d).reshape(B, H, nk, d)
+    if c["fp16"]:
+        q, k, v = (t.astype(np.float16) for t in (q, k, v))
+    return q, k, v
+
+
+@pytest.mark.parametrize("block", range(16))
+def test_random_cases(block):
+    import torch
+    from paper_2604_23798_amd import elsa
+    rng = np.random.default_rng(9000 + block)
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    for i in range(20):
+        c = _case(rng)
+        seed = 9100 + 100 * block + i
+        d, scale = c["d"], float(np.float32(c["d"] ** -0.5))
+        what = "fuzz %d/%d %s" % (block, i, {k_: v_ for k_, v_ in c.items() if k_ != "kv_len"})
+        tol = tolerance(max(c["nq"], c["nk"]), c["fp16"])
+        if c["kind"] == "varlen":
+            lengths = [int(x) for x in rng.integers(0, 200, size=int(rng.integers(1, 9)))]
+            if sum(lengths) == 0:
+                lengths[0] = 5
+            q, k, v, cu = inputs.make_varlen(seed, H=c["H"], d=d, fp16=c["fp16"], lengths=lengths)
+            ref = oracle.attn_varlen(f32(q), f32(k), f32(v), cu, scale, causal=c["causal"])
+            with G.Options(**c["opts"]):
+                out = G.fwd_varlen(q, k, v, cu, max(lengths), scale, causal=c["causal"])
+            assert_parity(out.reshape(-1, d), ref.reshape(-1, d), tol, what)
+            continue
+        q, k, v = _tensors(c, seed)
+        ref, ref_lse = oracle.cross_rows(f32(q), f32(k), f32(v), scale, causal=c["causal"], kv_len=c["kv_len"])
+        opts = dict(c["opts"], splits=c["splits"])
+        try:
+            elsa.elsa_set_workspace(ws if c["splits"] else None)
+            with G.Options(**opts):
+                if c["kind"] == "stream":
+                    cuts = sorted(set(int(x) for x in rng.integers(1, c["nk"], size=2))) if c["nk"] > 2 else []
+                    edges = [0] + cuts + [c["nk"]]
+                    tq = G.to_dev(q)
+                    state = torch.empty(elsa.elsa_stream_state_bytes(c["B"], c["H"], c["nq"], d), dtype=torch.uint8, device="cuda")
+                    for j in range(len(edges) - 1):
+                        a, b = edges[j], edges[j + 1]
+                        elsa.elsa_attn_stream_step(tq, G.to_dev(np.ascontiguousarray(k[:, :, a:b])),
+                                                   G.to_dev(np.ascontiguousarray(v[:, :, a:b])), state, scale, first=(j == 0),
+                                                   causal=c["causal"], causal_shift=(c["nk"] - c["nq"]) - a)
+                    o = torch.full_like(tq, float("nan"))
+                    elsa.elsa_attn_stream_finish(state, o)
+                    torch.cuda.synchronize()
+                    out = o.reshape(-1, d).double().cpu().numpy()
+                elif c["kind"] == "square" and rng.integers(0, 2):
+                    out = G.fwd(q, k, v, scale, causal=c["causal"], kv_len=c["kv_len"], masked_entry=True)
+                else:
+                    out, lse = G.fwd_cross(q, k, v, scale, causal=c["causal"], kv_len=c["kv_len"], want_lse=True)
+                    vis = np.isfinite(ref_lse)
+                    assert np.all(np.isneginf(lse[~vis])), what
+                    assert np.max(np.abs(lse[vis] - ref_lse[vis]), initial=0.0) < (5e-3 if c["fp16"] else 3e-5), what
+        finally:
+            elsa.elsa_set_workspace(None)
+        assert_parity(out, ref, tol, what)
