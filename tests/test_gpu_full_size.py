@@ -46,6 +46,18 @@ def test_long_sequence_sweep(n, fp16):
     _check(inputs.sweep(n, fp16), per_head=24)
 
 
+@pytest.mark.parametrize("n", [1024, 4096, 16384])
+def test_row_error_within_a_small_multiple_of_the_merge_depth_bound(n):
+    """Thm 1: ||y_hat - y|| / ||y|| <= u * L(n, B) + O(u^2) per row for the scan with exact scores.
+    The kernel also rounds the scores (FP32 dot products), so the check allows a factor 8 on top of
+    u * L(n, 128): N(0,1) inputs keep the score rounding at the same order as the bound."""
+    from oracle.scan import merge_depth
+    w = inputs.sweep(n)
+    m = _check(w, per_head=24)
+    u = 2.0 ** -24
+    assert m["e_row"] <= 8 * u * merge_depth(n, 128), (m["e_row"], u * merge_depth(n, 128))
+
+
 def test_sweep_16k_vector_fma_path():
     _check(inputs.sweep(16384), per_head=8, path=1)
 
