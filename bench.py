@@ -111,16 +111,26 @@ def scaling_fit(a):
             torch.cuda.synchronize()
             ns.append(n)
             ts.append(e0.elapsed_time(e1) / a.steps / H)
-        L = [math.ceil(math.log2(128)) + 2 * math.ceil(math.log2(n / 128)) + 3 for n in ns]
-        A = np.array([[l, float(n) * n, 1.0] for l, n in zip(L, ns)])
-        coef, *_ = np.linalg.lstsq(A, np.array(ts), rcond=None)
-        pred = A @ coef
-        ss_res = float(np.sum((np.array(ts) - pred) ** 2))
-        ss_tot = float(np.sum((np.array(ts) - np.mean(ts)) ** 2))
-        res["fits"]["fp16" if fp16 else "fp32"] = {
-            "n": ns, "L": L, "ms_per_head": ts, "a": float(coef[0]), "b": float(coef[1]), "c": float(coef[2]),
-            "r2": 1.0 - ss_res / ss_tot}
+        fit = fit_scaling_law(ns, ts)
+        fit["ms_per_head"] = ts
+        res["fits"]["fp16" if fp16 else "fp32"] = fit
     return res
+
+
+def fit_scaling_law(ns, ts, block=128):
+    """Least-squares fit of T(n) = a*L(n,B) + b*n^2 + c (the paper's scaling model, L from Eq. 5)
+    to latencies ``ts`` at lengths ``ns``.  Returns n, L, a, b, c and R^2."""
+    import math
+    import numpy as np
+    L = [math.ceil(math.log2(block)) + 2 * max(0, math.ceil(math.log2(n / block))) + 3 for n in ns]
+    A = np.array([[l, float(n) * n, 1.0] for l, n in zip(L, ns)])
+    y = np.asarray(ts, dtype=np.float64)
+    coef, *_ = np.linalg.lstsq(A, y, rcond=None)
+    pred = A @ coef
+    ss_res = float(np.sum((y - pred) ** 2))
+    ss_tot = float(np.sum((y - np.mean(y)) ** 2))
+    return {"n": list(ns), "L": L, "a": float(coef[0]), "b": float(coef[1]), "c": float(coef[2]),
+            "r2": 1.0 - ss_res / ss_tot if ss_tot > 0 else 1.0}
 
 
 def main():
