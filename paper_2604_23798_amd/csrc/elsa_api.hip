@@ -164,7 +164,7 @@ void carve(void *ws, int B, int H, int n, int d, int C, float **pm, float **pS, 
 // Number of key chunks for elsa_attn_fwd when a workspace is lent: enough 128-row blocks for
 // one per CU, chunks no shorter than 256 keys, at most 8 (64 when decoding), and only if the
 // workspace holds them.
-int auto_splits(int B, int H, int n, int nk, int d) {
+int auto_splits(int B, int H, int n, int nk, int d, bool fp16_tiles) {
     int C = g.opt[ELSA_OPT_SPLITS];
     if (C <= 0) {
         const long long blocks = (long long)B * H * ((n + 127) / 128);
@@ -175,7 +175,10 @@ int auto_splits(int B, int H, int n, int nk, int d) {
         // (measured at n = 1024, H = 16: 2 chunks 47.5 us, 4 chunks 51 us, none 77 us).
         const bool few_q = (long long)n * 8 <= nk;
         const int want = few_q ? 5 * kNumCu : kNumCu;
-        if (blocks <= want) {
+        // The FP16 tiles are so much faster per key that, outside decoding, a second launch costs more
+        // than idle CUs do (n = 1024, H = 16: 13.4 us in one pass of the key-splitting tile, 20 us cut
+        // in two; n = 2048: 39.6 against 41.6 us).
+        if (blocks <= want && (few_q || !fp16_tiles)) {
             C = (int)((want + blocks - 1) / blocks);
             if (C < 2) C = 2;                    // exactly one block per CU still gains from two chunks
             const int cap = nk / 256 > 1 ? nk / 256 : 1;
@@ -216,7 +219,8 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     if (nk <= 0) nk = n;
     int rc = check_common(B, H, n, d, dtype);
     if (rc != ELSA_OK) return rc;
-    const int C = g.ws ? auto_splits(B, H, n, nk, d) : 1;
+    const bool fp16_tiles = dtype == ELSA_F16 && scale != 0.f && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 3);
+    const int C = g.ws ? auto_splits(B, H, n, nk, d, fp16_tiles) : 1;
     Extra x;
     x.nk = nk;
     if (C == 1) {
