@@ -57,7 +57,7 @@ int pick_variant(int path, long long BH, int n, int nk, int d, int splits, int c
     const long long b128 = BH * ((n + 127) / 128) * splits;
     // FP16: the 256-row tile wins only without a causal mask (its diagonal tiles waste twice as much:
     // 436 vs 287 TFLOP/s at n = 4096, 794 vs 756 at n = 16384, causal, d = 64)
-    if (path == 3) return (d <= 64 && b256 >= 2 * kNumCu && !causal) ? 2 : (b128 >= (3 * kNumCu) / 4 ? 1 : 3);
+    if (path == 3) return (d <= 64 && n >= 256 && b256 >= 2 * kNumCu && !causal) ? 2 : (b128 >= (3 * kNumCu) / 4 ? 1 : 3);
     if (b128 < (3 * kNumCu) / 4) return 3;
     return d <= 64 ? 7 : 1;
 }
@@ -110,8 +110,9 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     int variant = decode_variant ? decode_variant : pick_variant(path, (long long)B * H, n, nk, d, num_splits, causal);
     if (path == 2) {
         const bool ok = small_kernel_ok(cu_seqlens, num_splits, emit, n, nk);
-        if (g.opt[ELSA_OPT_VARIANT] == 0 && ok && !head_dim_wide(d) && n <= 128 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu)
-            variant = 10;                        // thousands of tiny problems (window attention)
+        // thousands of tiny problems (window attention); at n = 128 or d = 128 the 128-row tile is faster
+        if (g.opt[ELSA_OPT_VARIANT] == 0 && ok && d <= 64 && n <= 96 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu)
+            variant = 10;
         if ((variant == 9 || variant == 10) && !ok) variant = d <= 64 ? 7 : 1;
     }
     const int tq = variant_tq(path, variant, d);
