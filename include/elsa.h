@@ -181,7 +181,8 @@ int elsa_set_workspace(void *dev_ptr, size_t bytes);
 /*
  * Measurement / tuning knobs (process-wide, not thread-safe).  Defaults are 0.
  *   ELSA_OPT_PATH     0 = auto (FP32 I/O: FP32 MFMA; FP16 I/O: FP16 MFMA with FP32 state; one to
- *                     four queries per (batch, head): the FP32 vector kernel that streams K and V),
+ *                     four queries per (batch, head), eight for FP32 at d >= 128: the FP32 vector
+ *                     kernel that streams K and V),
  *                     1 = FP32 FMA (vector ALU), 2 = FP32 MFMA (FP16 inputs widened to FP32),
  *                     3 = FP16 MFMA (FP16 I/O and scale != 0 only, else ELSA_ERR_UNSUPPORTED)
  *   ELSA_OPT_VARIANT  0 = auto, otherwise a tile configuration id (see elsa_variant_name)

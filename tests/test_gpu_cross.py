@@ -172,3 +172,13 @@ def test_decode_kernel_wide_scores():
     out = G.fwd_cross(q, k, v, 0.125)
     assert np.all(np.isfinite(out))
     assert_parity(out, ref, tolerance(6000, False), "decode wide")
+
+
+def test_decode_kernel_reaches_eight_queries_for_fp32_at_d128():
+    from paper_2604_23798_amd import elsa
+    for nq, fp16, decode in ((8, False, True), (9, False, False), (8, True, False)):
+        q, k, v = _rect(1, 4, nq, 3000, 128, 700 + nq, fp16=fp16)
+        ref, _ = _ref(q, k, v, 128 ** -0.5, causal=True)
+        out = G.fwd_cross(q, k, v, 128 ** -0.5, causal=True)
+        assert_parity(out, ref, tolerance(3000, fp16), "d128 nq=%d fp16=%d" % (nq, fp16))
+        assert elsa.elsa_last_kernel().startswith("fma_decode") == decode
