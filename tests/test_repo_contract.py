@@ -56,7 +56,7 @@ def test_documented_files_exist():
     srcs = _read("paper_2604_23798_amd/build.py")
     for name in re.findall(r'"(elsa_\w+\.hip)"', srcs):
         assert os.path.exists(os.path.join(ROOT, "paper_2604_23798_amd", "csrc", name)), name
-        assert name in design or name.replace(".hip", "") in design, "DESIGN.md does not mention " + name
+        assert name in design or name.replace(".hip", "") in design, "the design document does not mention " + name
 
 
 def test_every_gpu_test_module_is_marked():
