@@ -54,6 +54,7 @@ def _load():
         lib.elsa_oracle_merge_unsum.restype = None
         lib.elsa_oracle_combine_rows.argtypes = [dp, dp, dp, L, I, I, dp]
         lib.elsa_oracle_cross_rows.argtypes = [fp, fp, fp, I, I, I, I, I, D, I, ip, lp, L, dp, dp]
+        lib.elsa_oracle_dv_rows.argtypes = [fp, fp, fp, I, I, I, I, I, I, D, I, ip, lp, L, dp, dp]
         lib.elsa_ladder_f32_fold_rows.argtypes = [fp, fp, fp, I, I, I, I, ctypes.c_float, I, ip, lp, L, fp]
         _lib = lib
     return _lib
@@ -191,6 +192,36 @@ def cross_rows(q, k, v, scale, causal=False, kv_len=None, rows=None):
     rc = _load().elsa_oracle_cross_rows(qp, kp, vp, B, H, nq, nk, d, float(scale), int(bool(causal)), klp,
                                         rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), rows.size,
                                         out.ctypes.data_as(dp), lse.ctypes.data_as(dp))
+    assert rc == 0
+    return out, lse
+
+
+def dv_rows(q, k, v, scale, causal=False, kv_len=None, rows=None):
+    """Attention whose values have their own width: ``q [B,H,n_q,d]``, ``k [B,H,n_k,d]``,
+    ``v [B,H,n_k,d_v]`` (the paper's V in R^{n x d_v}, W in R^{d_v}).  Masks as in ``cross_rows``.
+    Returns ``(out [R,d_v], lse [R])`` float64; a row is ``(b*H + h)*n_q + i``."""
+    q, qp = _f32(q)
+    k, kp = _f32(k)
+    v, vp = _f32(v)
+    assert q.ndim == 4 and k.ndim == 4 and v.ndim == 4
+    B, H, nq, d = q.shape
+    nk, dv = v.shape[2], v.shape[3]
+    assert k.shape == (B, H, nk, d) and v.shape == (B, H, nk, dv)
+    klp = None
+    if kv_len is not None:
+        kl = np.ascontiguousarray(kv_len, dtype=np.int32)
+        assert kl.shape == (B,)
+        klp = kl.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))
+    if rows is None:
+        rows = np.arange(B * H * nq, dtype=np.int64)
+    rows = np.ascontiguousarray(rows, dtype=np.int64)
+    assert rows.ndim == 1 and (rows.size == 0 or (rows.min() >= 0 and rows.max() < B * H * nq))
+    out = np.empty((rows.size, dv), dtype=np.float64)
+    lse = np.empty(rows.size, dtype=np.float64)
+    dp = ctypes.POINTER(ctypes.c_double)
+    rc = _load().elsa_oracle_dv_rows(qp, kp, vp, B, H, nq, nk, d, dv, float(scale), int(bool(causal)), klp,
+                                     rows.ctypes.data_as(ctypes.POINTER(ctypes.c_int64)), rows.size,
+                                     out.ctypes.data_as(dp), lse.ctypes.data_as(dp))
     assert rc == 0
     return out, lse
 

@@ -347,6 +347,61 @@ int elsa_oracle_cross_rows(const float *q, const float *k, const float *v,
 }
 
 /*
+ * Attention with value rows of their own width d_v (the paper's setting V in R^{n x d_v},
+ * Sec. "Problem setup"; the state's W lives in R^{d_v}): scores use the d columns of q and k,
+ * the weighted sum runs over the d_v columns of v.  Written out as the definition, one row at a
+ * time:  y_i = sum_j softmax_j(scale q_i.k_j) v_j  over the visible keys.
+ * q: [B][H][n_q][d]; k: [B][H][n_k][d]; v: [B][H][n_k][d_v]; masks as for the rectangular routine
+ * above (causal: key j visible to query i iff j <= i + (n_k - n_q); kv_len per batch entry).
+ * out: [nrows][d_v]; lse: [nrows] or NULL.
+ */
+int elsa_oracle_dv_rows(const float *q, const float *k, const float *v,
+                        int B, int H, int nq, int nk, int d, int dv, double scale, int causal,
+                        const int32_t *kv_len,
+                        const int64_t *rows, int64_t nrows, double *out, double *lse)
+{
+    (void)B;
+    double *w = (double *)malloc(sizeof(double) * (size_t)(nk > 0 ? nk : 1));
+    if (!w) return -1;
+    for (int64_t r = 0; r < nrows; ++r) {
+        int64_t row = rows[r];
+        int64_t i = row % nq, bh = row / nq, b = bh / H;
+        const float *qrow = q + (size_t)row * d;
+        const float *keys = k + (size_t)bh * nk * d;
+        const float *vals = v + (size_t)bh * nk * dv;
+        double *y = out + (size_t)r * dv;
+        int64_t vis = kv_len ? (int64_t)kv_len[b] : nk;          /* number of visible keys */
+        if (vis > nk) vis = nk;
+        if (causal) {
+            int64_t diag = i + ((int64_t)nk - (int64_t)nq) + 1;  /* keys 0 .. diag-1 */
+            if (diag < vis) vis = diag;
+        }
+        if (vis < 0) vis = 0;
+        for (int c = 0; c < dv; ++c) y[c] = 0.0;
+        if (lse) lse[r] = -INFINITY;
+        if (vis == 0) continue;
+        double top = -INFINITY;
+        for (int64_t j = 0; j < vis; ++j) {
+            w[j] = score(qrow, keys + (size_t)j * d, d, scale);
+            if (w[j] > top) top = w[j];
+        }
+        double Z = 0.0;
+        for (int64_t j = 0; j < vis; ++j) {
+            w[j] = exp(w[j] - top);
+            Z += w[j];
+        }
+        for (int c = 0; c < dv; ++c) {
+            double acc = 0.0;
+            for (int64_t j = 0; j < vis; ++j) acc += w[j] * (double)vals[(size_t)j * dv + c];
+            y[c] = acc / Z;
+        }
+        if (lse) lse[r] = top + log(Z);
+    }
+    free(w);
+    return 0;
+}
+
+/*
  * FP32 ladder (diagnostic only): the sequential fold of Alg. 1 carried out
  * entirely in IEEE single precision (float products, float sums, expf).  It
  * shows what error any FP32-accumulating evaluation carries on a given input,

@@ -86,6 +86,24 @@ def battery():
         sp = sx.masked_fill((j >= torch.from_numpy(kl).long()[:, None, None, None]), float("-inf"))
         o, _ = oracle.cross_rows(qq, kk, vv, 0.4, kv_len=kl)
         _close(o, (torch.softmax(sp, -1) @ c).numpy().reshape(-1, 8))
+    # values of their own width: library softmax, both masks, and the log-normaliser
+    for nq, nk, dd, dv in ((23, 5, 4, 16), (5, 23, 8, 3)):      # the first case keeps every planted index inside v
+        qq = inputs.normal(13, 0, 0, 2 * 2 * nq * dd).reshape(2, 2, nq, dd)
+        kk = inputs.normal(13, 1, 0, 2 * 2 * nk * dd).reshape(2, 2, nk, dd)
+        vv = inputs.normal(13, 2, 0, 2 * 2 * nk * dv).reshape(2, 2, nk, dv)
+        a, b_, c = (torch.from_numpy(x).double() for x in (qq, kk, vv))
+        sx = (a @ b_.transpose(-1, -2)) * 0.4
+        o, l = oracle.dv_rows(qq, kk, vv, 0.4)
+        _close(o, (torch.softmax(sx, -1) @ c).numpy().reshape(-1, dv))
+        _close(l, torch.logsumexp(sx, -1).numpy().reshape(-1))
+        i, j = torch.arange(nq)[:, None], torch.arange(nk)[None, :]
+        sm = sx.masked_fill(j > i + (nk - nq), float("-inf"))
+        o, _ = oracle.dv_rows(qq, kk, vv, 0.4, causal=True)
+        _close(o, (torch.nan_to_num(torch.softmax(sm, -1), nan=0.0) @ c).numpy().reshape(-1, dv))
+        kl = np.array([nk, 3], np.int32)
+        sp = sx.masked_fill((j >= torch.from_numpy(kl).long()[:, None, None, None]), float("-inf"))
+        o, _ = oracle.dv_rows(qq, kk, vv, 0.4, kv_len=kl)
+        _close(o, (torch.softmax(sp, -1) @ c).numpy().reshape(-1, dv))
     lad = oracle.ladder_f32_fold_rows(q, k, v, 0.3).astype(np.float64)
     ref = oracle.attn_rows(q, k, v, 0.3)
     assert np.max(np.linalg.norm(lad - ref, axis=1) / np.linalg.norm(ref, axis=1)) < 1e-5
@@ -112,6 +130,12 @@ MUTATIONS = [
     ("rectangular: keys strided by the query count", "const float *kb = k + (size_t)bh * nk * d;", "const float *kb = k + (size_t)bh * nq * d;"),
     ("rectangular: padding ignored", "int64_t L = kv_len ? (int64_t)kv_len[b] : nk;", "int64_t L = nk;"),
     ("rectangular: log-normaliser without its maximum", "if (lse) lse[r] = m + log(S);", "if (lse) lse[r] = log(S);"),
+    ("own value width: values strided by the key width", "const float *vals = v + (size_t)bh * nk * dv;", "const float *vals = v + (size_t)bh * nk * d;"),
+    ("own value width: value rows strided by the key width", "acc += w[j] * (double)vals[(size_t)j * dv + c];", "acc += w[j] * (double)vals[(size_t)j * d + c];"),
+    ("own value width: not normalised", "y[c] = acc / Z;", "y[c] = acc;"),
+    ("own value width: diagonal off by one", "int64_t diag = i + ((int64_t)nk - (int64_t)nq) + 1;", "int64_t diag = i + ((int64_t)nk - (int64_t)nq);"),
+    ("own value width: padding ignored", "int64_t vis = kv_len ? (int64_t)kv_len[b] : nk;", "int64_t vis = nk;"),
+    ("own value width: weights without their maximum in the log-normaliser", "if (lse) lse[r] = top + log(Z);", "if (lse) lse[r] = log(Z);"),
     ("single-precision ladder: past not rescaled", "S = S * beta + 1.0f;", "S = S + 1.0f;"),
 ]
 

@@ -302,3 +302,83 @@ def test_cross_key_padding_and_row_subset():
     rows = np.array([3, 23, 0], np.int64)
     sub, _ = oracle.cross_rows(q, k, v, 0.7, kv_len=kv_len, rows=rows)
     _close(sub, out[rows])
+
+
+# ---- values of their own width d_v != d (V in R^{n x d_v}, W in R^{d_v}) ---------------------------
+def _rect_dv(B, H, nq, nk, d, dv, seed):
+    q = inputs.normal(seed, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
+    k = inputs.normal(seed, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
+    v = inputs.normal(seed, 2, 0, B * H * nk * dv).reshape(B, H, nk, dv)
+    return q, k, v
+
+
+def test_dv_two_keys_three_value_columns_by_hand():
+    q = np.array([[[[2.0, 1.0]]]], np.float32)
+    k = np.array([[[[1.0, 0.0], [0.0, 3.0]]]], np.float32)
+    v = np.array([[[[4.0, -2.0, 1.0], [-6.0, 10.0, 5.0]]]], np.float32)
+    s1, s2 = 0.5 * 2.0, 0.5 * 3.0
+    w1 = 1.0 / (1.0 + math.exp(s2 - s1))
+    out, lse = oracle.dv_rows(q, k, v, 0.5)
+    assert out.shape == (1, 3)
+    _close(out[0], [w1 * 4.0 + (1 - w1) * -6.0, w1 * -2.0 + (1 - w1) * 10.0, w1 * 1.0 + (1 - w1) * 5.0])
+    _close(lse[0], math.log(math.exp(s1) + math.exp(s2)))
+    # one value column, d = 2: the output is the softmax-weighted mean of that column
+    out1, _ = oracle.dv_rows(q, k, v[..., 2:], 0.5)
+    _close(out1[0], [w1 * 1.0 + (1 - w1) * 5.0])
+
+
+def test_dv_brute_force_in_python_floats():
+    B, H, nq, nk, d, dv = 1, 2, 3, 5, 2, 3
+    q, k, v = _rect_dv(B, H, nq, nk, d, dv, 61)
+    for causal in (False, True):
+        out, lse = oracle.dv_rows(q, k, v, 0.9, causal=causal)
+        for h in range(H):
+            for i in range(nq):
+                vis = [j for j in range(nk) if not causal or j <= i + nk - nq]
+                s = [0.9 * sum(float(q[0, h, i, t]) * float(k[0, h, j, t]) for t in range(d)) for j in vis]
+                z = sum(math.exp(x) for x in s)
+                for c in range(dv):
+                    y = sum(math.exp(x) * float(v[0, h, j, c]) for x, j in zip(s, vis)) / z
+                    assert abs(out[h * nq + i, c] - y) < 1e-12 * (1 + abs(y))
+                assert abs(lse[h * nq + i] - math.log(z)) < 1e-12
+
+
+@pytest.mark.parametrize("nq,nk,d,dv", [(5, 23, 8, 3), (23, 5, 4, 16), (1, 40, 16, 8), (17, 17, 8, 24)])
+@pytest.mark.parametrize("causal", [False, True])
+def test_dv_against_library_softmax(nq, nk, d, dv, causal):
+    B, H = 2, 3
+    q, k, v = _rect_dv(B, H, nq, nk, d, dv, 67 + nq)
+    tq, tk, tv = (torch.from_numpy(t).double() for t in (q, k, v))
+    s = (tq @ tk.transpose(-1, -2)) * 0.4
+    if causal:
+        i = torch.arange(nq)[:, None]
+        j = torch.arange(nk)[None, :]
+        s = s.masked_fill(j > i + (nk - nq), float("-inf"))
+    p = torch.nan_to_num(torch.softmax(s, -1), nan=0.0)
+    out, lse = oracle.dv_rows(q, k, v, 0.4, causal=causal)
+    _close(out, (p @ tv).numpy().reshape(-1, dv))
+    ref_lse = torch.logsumexp(s, -1).numpy().reshape(-1)
+    vis = np.isfinite(ref_lse)
+    _close(lse[vis], ref_lse[vis])
+    assert np.all(np.isneginf(lse[~vis])) and np.all(out[~vis] == 0)
+
+
+def test_dv_columns_are_independent_and_equal_width_is_the_rectangular_routine():
+    """out(V = [V1 | V2]) = [out(V1) | out(V2)]: each block through the equal-width routine."""
+    B, H, nq, nk, d = 2, 2, 9, 21, 8
+    q, k, v = _rect_dv(B, H, nq, nk, d, 2 * d, 71)
+    kv_len = np.array([21, 6], np.int32)
+    for causal in (False, True):
+        out, lse = oracle.dv_rows(q, k, v, 0.3, causal=causal, kv_len=kv_len)
+        for blk in range(2):
+            vb = np.ascontiguousarray(v[..., blk * d:(blk + 1) * d])
+            ref, ref_lse = oracle.cross_rows(q, k, vb, 0.3, causal=causal, kv_len=kv_len)
+            _close(out[:, blk * d:(blk + 1) * d], ref)
+            _close(lse, ref_lse)
+    # constant value rows come back unchanged whatever the scores are
+    vc = np.broadcast_to(np.arange(5, dtype=np.float32), (B, H, nk, 5)).copy()
+    out, _ = oracle.dv_rows(q, k, vc, 1.7)
+    _close(out, np.broadcast_to(np.arange(5.0), out.shape))
+    rows = np.array([7, 0, 30], np.int64)
+    sub, _ = oracle.dv_rows(q, k, v, 0.3, kv_len=kv_len, rows=rows)
+    _close(sub, oracle.dv_rows(q, k, v, 0.3, kv_len=kv_len)[0][rows])
