@@ -9,7 +9,7 @@ the one the headline metric is quoted on: the long-sequence sweep at n = 16384, 
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--path auto|fma|mfma|mfma16]
 
-``--workload`` takes any name of ``paper_2604_23798_amd.inputs.WORKLOADS``, ``decode_32k[_fp16]`` or ``varlen_8x1792``
+``--workload`` takes any name of ``paper_2604_23798_amd.inputs.WORKLOADS``, ``decode_32k[_fp16]``, ``dv_<d>_<d_v>_<n>[_causal][_fp16]`` or ``varlen_8x1792``
 (8 packed sequences with lengths uniform on [256, 1792], H = 12, d = 64; add ``_fp16`` for FP16).
 """
 import argparse
@@ -173,7 +173,22 @@ def main():
         return
     varlen = a.workload.startswith("varlen_8x1792")
     decode = a.workload.startswith("decode_32k")
-    if decode:
+    dvw = a.workload.startswith("dv_")
+    if dvw:
+        # values of their own width: dv_<d>_<d_v>_<n>[_causal][_fp16], B = 1, H = 16, n queries = n keys
+        parts = a.workload.split("_")
+        d, dv, n_dv = int(parts[1]), int(parts[2]), int(parts[3])
+        fp16, causal = "fp16" in parts[4:], "causal" in parts[4:]
+        B, H, nq, nk = 1, 16, n_dv, n_dv
+        q = inputs.normal(1012, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
+        k = inputs.normal(1012, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
+        v = inputs.normal(1012, 2, 0, B * H * nk * dv).reshape(B, H, nk, dv)
+        if fp16:
+            q, k, v = (t.astype(np.float16) for t in (q, k, v))
+        scale = float(np.float32(d ** -0.5))
+        flops = 2 * B * H * nq * nk * (d + dv)           # scores contract over d, the weighted sum over d_v
+        kv_len = None
+    elif decode:
         # one new position per sequence against a 32K-token cache, LLaMA-13B head shape
         fp16 = a.workload.endswith("_fp16")
         B, H, d, nq, nk = 2, 40, 128, 1, 32768
@@ -198,9 +213,18 @@ def main():
         w = inputs.WORKLOADS[a.workload]
         q, k, v, kv_len = inputs.make(w)
         fp16, causal, scale, flops = w.fp16, w.causal, w.scale, w.flops
+    # multiply-adds the kernels have to execute (visible keys only): what the roofline fraction is taken on
+    exec_flops = float(flops)
+    if dvw and causal:
+        exec_flops = 2.0 * B * H * (d + dv) * (nq * (nq + 1) / 2)
+    elif not (dvw or decode or varlen):
+        if w.causal:
+            exec_flops = 4.0 * w.B * w.H * w.d * (w.n * (w.n + 1) / 2)
+        elif kv_len is not None:
+            exec_flops = 4.0 * w.H * w.n * w.d * float(np.minimum(kv_len, w.n).sum())
     tq, tk, tv = (torch.from_numpy(t).cuda() for t in (q, k, v))
     tl = None if kv_len is None else torch.from_numpy(kv_len).cuda()
-    out = torch.empty_like(tq)
+    out = torch.empty(tq.shape[:3] + (tv.shape[-1],), dtype=tq.dtype, device="cuda")
     ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
     elsa.elsa_set_workspace(ws)
     elsa.elsa_set_option(elsa.OPT_PATH, {"auto": 0, "fma": 1, "mfma": 2, "mfma16": 3}[a.path])
@@ -225,6 +249,9 @@ def main():
                 elsa.elsa_attn_stream_step(tq, kcs[i], vcs[i], state, scale, first=(i == 0), causal=causal,
                                            causal_shift=-i * nc)
             elsa.elsa_attn_stream_finish(state, out)
+    elif dvw:
+        def step():
+            elsa.elsa_attn_fwd_dv(tq, tk, tv, out, scale, causal, tl)
     elif decode:
         def step():
             elsa.elsa_attn_fwd_cross(tq, tk, tv, out, scale, causal, tl)
@@ -282,7 +309,7 @@ def main():
 
     # flops: 4 B H n^2 d, the square count the metric is defined on (sum of len^2 for packed batches)
     value = flops / (ms_step * 1e-3) / 1e12
-    achieved = flops / (ms_kernel * 1e-3) / 1e12
+    achieved = exec_flops / (ms_kernel * 1e-3) / 1e12
     if kernel.startswith("fma"):
         bound, peak = "alu", PEAK_FP32_VALU_UNPACKED
     elif kernel.startswith("mfma16"):
@@ -316,6 +343,11 @@ def main():
         rec["config"].update({"B": B, "H": H, "n_q": nq, "n_k": nk, "d": d})
         rec["tokens_per_s"] = B * nq / (ms_step * 1e-3)
         del rec["pct_of_fp32_peak"]
+    elif dvw:
+        rec["metric"] = "attention TFLOP/s (2*B*H*n^2*(d + d_v) / time)"
+        rec["config"].update({"B": B, "H": H, "n": nq, "d": d, "d_v": dv})
+        if causal:
+            rec["causal_effective_tflops"] = 2.0 * B * H * (d + dv) * (nq * (nq + 1) / 2) / (ms_step * 1e-3) / 1e12
     elif varlen:
         rec["config"].update({"num_seqs": 8, "lengths": [int(x) for x in lens], "H": H, "d": d})
         rec["tokens_per_s"] = float(lens.sum()) / (ms_step * 1e-3)
@@ -337,6 +369,18 @@ def main():
             err = np.linalg.norm(host.reshape(-1, d)[rows] - ref, axis=1) / np.linalg.norm(ref, axis=1)
             base = {"value": rows.size * 2.0 * nk * d * (2 if fp16 else 4) / dt / 1e9, "unit": "GB/s", "cores": 1,
                     "kind": "oracle", "sample": "%d of %d (batch, head) rows, all %d keys" % (rows.size, B * H, nk)}
+            par = {"rows": int(rows.size), "e_row": float(err.max())}
+        elif dvw:
+            import oracle
+            f32 = lambda x: x.astype(np.float32)
+            rows = np.linspace(0, B * H * nq - 1, min(a.oracle_rows, 2048)).astype(np.int64)
+            t0 = time.perf_counter()
+            ref, _ = oracle.dv_rows(f32(q), f32(k), f32(v), scale, causal=causal, rows=rows)
+            dt = time.perf_counter() - t0
+            err = np.linalg.norm(host.reshape(-1, dv)[rows] - ref, axis=1) / np.linalg.norm(ref, axis=1)
+            vis = (rows % nq + 1).sum() if causal else rows.size * nk
+            base = {"value": 2.0 * (d + dv) * float(vis) / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+                    "sample": "%d of %d rows (evenly spaced), visible keys only" % (rows.size, B * H * nq)}
             par = {"rows": int(rows.size), "e_row": float(err.max())}
         elif varlen:
             base, par = cpu_baseline_varlen(q, k, v, cu, scale, host, fp16)

@@ -6,8 +6,9 @@
  *   - All tensor pointers are DEVICE pointers owned by the caller.  The library
  *     never allocates, frees or retains them (except the workspace registered
  *     with elsa_set_workspace, which it borrows until replaced).
- *   - Q, K, V, out are contiguous row-major [B][H][n][d] with d_v == d,
- *     self-attention (n queries, n keys) except for elsa_attn_fwd_cross.  d must be 32, 64, 96,
+ *   - Q, K, V, out are contiguous row-major [B][H][n][d] with d_v == d (elsa_attn_fwd_dv lifts
+ *     that), self-attention (n queries, n keys) except for elsa_attn_fwd_cross and
+ *     elsa_attn_fwd_dv.  d must be 32, 64, 96,
  *     128 or 256; 96 and 256 run on the matrix-core tiles, the one-query decode kernel and the
  *     combine only (ELSA_OPT_PATH = 1 tiles and the LDS-free small-problem tiles return
  *     ELSA_ERR_UNSUPPORTED for them).  The K (and V) slice of one (batch, head) -- one sequence of a packed batch -- must
@@ -94,6 +95,28 @@ int elsa_attn_fwd_lse(const void *q, const void *k, const void *v, void *out, fl
 int elsa_attn_fwd_cross(const void *q, const void *k, const void *v, void *out, float *lse,
                         int B, int H, int n_q, int n_k, int d, float scale, int causal,
                         const int32_t *kv_len, int dtype, void *stream);
+
+/*
+ * Rectangular attention whose values have a width of their own: the paper's setting
+ * Q, K in R^{n x d}, V in R^{n x d_v} (Sec. "Problem setup"), state (m, S, W) with W in R^{d_v};
+ * the scores contract over d, the weighted sum of Eq. 1 runs over the d_v columns of V.
+ *   q: [B][H][n_q][d];  k: [B][H][n_k][d];  v: [B][H][n_k][d_v];  out: [B][H][n_q][d_v];
+ *   lse: FP32 [B][H][n_q] or NULL (not written).
+ * Masks, causal alignment, kv_len and the internal key split exactly as elsa_attn_fwd_cross (the
+ * registered workspace must hold elsa_split_kv_workspace_bytes(B, H, n_q, d_v, C) for C chunks).
+ * d == d_v is forwarded to elsa_attn_fwd_cross.  Otherwise the pairs served are d, d_v in
+ * {32, 64, 128} and (d, d_v) = (192, 128); they run on the matrix-core tiles (FP32 tiles for
+ * ELSA_F32, FP16 tiles for ELSA_F16 with scale != 0, FP32 tiles with FP16 I/O otherwise).  Of the
+ * options only ELSA_OPT_PATH in {0, 2, 3}, ELSA_OPT_VARIANT in {0, 1 = 128 query rows,
+ * 3 = waves split the keys (not for FP32 tiles at d = 192)}, ELSA_OPT_SPLITS, ELSA_OPT_XCD_MAP and
+ * ELSA_OPT_SNAKE apply.
+ * Errors: ELSA_ERR_INVALID_ARG (NULL tensor, non-positive size, non-finite scale),
+ * ELSA_ERR_UNSUPPORTED (pair, dtype or option not served; a K or V slice of 2 GiB or more),
+ * ELSA_ERR_HIP (launch failure).
+ */
+int elsa_attn_fwd_dv(const void *q, const void *k, const void *v, void *out, float *lse,
+                     int B, int H, int n_q, int n_k, int d, int d_v, float scale, int causal,
+                     const int32_t *kv_len, int dtype, void *stream);
 
 /*
  * Padding-free variable-length batches (the packed layout of the paper's

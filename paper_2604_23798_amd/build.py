@@ -9,7 +9,8 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libelsa.so")
-SOURCES = ["elsa_api.hip", "elsa_fwd_mfma.hip", "elsa_fwd_mfma_f16.hip", "elsa_fwd_fma.hip", "elsa_fwd_small.hip", "elsa_fwd_decode.hip", "elsa_combine.hip"]
+SOURCES = ["elsa_api.hip", "elsa_fwd_mfma.hip", "elsa_fwd_mfma_f16.hip", "elsa_fwd_fma.hip", "elsa_fwd_small.hip", "elsa_fwd_decode.hip", "elsa_combine.hip",
+           "elsa_fwd_dv.hip", "elsa_fwd_dv_f16.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument"]
@@ -38,7 +39,7 @@ def build_library(verbose: bool = False) -> str:
             print(err, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=6) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     tmp = LIB + ".tmp.%d" % os.getpid()
     r = subprocess.run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", tmp, *objs],

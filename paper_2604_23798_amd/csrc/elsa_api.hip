@@ -156,6 +156,63 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     return ELSA_OK;
 }
 
+// (d, d_v) pairs with d_v != d: the matrix-core tiles only (no vector-FMA, decode or LDS-free kernels)
+bool dv_pair_ok(int d, int dv) {
+    if (d == dv) return false;
+    if (d == 192) return dv == 128;
+    return (d == 32 || d == 64 || d == 128) && (dv == 32 || dv == 64 || dv == 128);
+}
+
+// Forward launch for d_v != d; dense layout only.  Tile 3 (the waves of a block split the keys) for a
+// single query tile against a long key range or when the 128-row tile yields too few blocks, tile 1
+// (128 query rows) otherwise.
+int run_forward_dv(const void *q, const void *k, const void *v, void *out, float *lse, float *pm, float *pS, float *pW,
+                   int B, int H, int n, int nk, int d, int dv, float scale, int causal, const int32_t *kv_len,
+                   int num_splits, int emit, int dtype, void *stream) {
+    int path = g.opt[ELSA_OPT_PATH];
+    if (path == 0) path = (dtype == ELSA_F16 && scale != 0.f) ? 3 : 2;
+    if (path == 1) return ELSA_ERR_UNSUPPORTED;
+    if (path == 3 && (dtype != ELSA_F16 || scale == 0.f)) return ELSA_ERR_UNSUPPORTED;
+    const int fp16_tiles = path == 3;
+    const long long esz = dtype == ELSA_F16 ? 2 : 4;
+    if ((long long)(nk > n ? nk : n) * (d > dv ? d : dv) * esz >= 0x7fffffffLL) return ELSA_ERR_UNSUPPORTED;
+    int variant = g.opt[ELSA_OPT_VARIANT];
+    if (variant != 0 && variant != 1 && variant != 3) return ELSA_ERR_UNSUPPORTED;
+    const int tq3 = elsa::dv_variant_tq(fp16_tiles, 3, d, dv);
+    if (variant == 0) {
+        const long long b128 = (long long)B * H * ((n + 127) / 128) * num_splits;
+        variant = 1;
+        if (tq3 > 0 && (((long long)n * 8 <= nk && n <= tq3) || b128 < (3 * kNumCu) / 4)) variant = 3;
+    }
+    const int tq = elsa::dv_variant_tq(fp16_tiles, variant, d, dv);
+    if (tq <= 0) return ELSA_ERR_UNSUPPORTED;
+    elsa::FwdParams p{};
+    p.q = q; p.k = k; p.v = v; p.out = out;
+    p.lse = lse;
+    p.part_m = pm; p.part_S = pS; p.part_W = pW;
+    p.kv_len = kv_len;
+    p.B = B; p.H = H; p.n = n; p.nk = nk;
+    p.qscale = scale * elsa::kLog2e;
+    p.causal = causal ? 1 : 0;
+    p.num_splits = num_splits;
+    p.chunk = (nk + num_splits - 1) / num_splits;
+    p.emit_partials = emit;
+    p.coff = nk - n;                             // last query aligned with the last key
+    p.q_tiles = (n + tq - 1) / tq;
+    p.tq = tq;
+    p.xcd_map = g.opt[ELSA_OPT_XCD_MAP];
+    p.snake = g.opt[ELSA_OPT_SNAKE] == 1 ? 0 : 1;
+    p.sort_batches = (kv_len && (!causal || p.q_tiles == 1) && B >= 2 && B <= 32 && p.snake && p.xcd_map == 0) ? 1 : 0;
+    if ((long long)p.q_tiles * B * H * num_splits > 0x7fffffffLL - 8) return ELSA_ERR_INVALID_ARG;
+    const char *name = nullptr;
+    const hipStream_t s = static_cast<hipStream_t>(stream);
+    const int rc = fp16_tiles ? elsa::launch_fwd_dv16(p, d, dv, variant, s, &name)
+                              : elsa::launch_fwd_dv32(p, d, dv, dtype == ELSA_F16, variant, s, &name);
+    if (rc != 0) return ELSA_ERR_HIP;
+    g.last = name ? name : "";
+    return ELSA_OK;
+}
+
 void carve(void *ws, int B, int H, int n, int d, int C, float **pm, float **pS, float **pW) {
     const size_t rows = (size_t)B * H * C * n;
     char *base = static_cast<char *>(ws);
@@ -259,6 +316,32 @@ int elsa_attn_fwd_cross(const void *q, const void *k, const void *v, void *out, 
                         const int32_t *kv_len, int dtype, void *stream) {
     if (n_k <= 0) return ELSA_ERR_INVALID_ARG;
     return attn_fwd_impl(q, k, v, out, lse, B, H, n_q, d, scale, causal, kv_len, dtype, stream, n_k);
+}
+
+int elsa_attn_fwd_dv(const void *q, const void *k, const void *v, void *out, float *lse,
+                     int B, int H, int n_q, int n_k, int d, int d_v, float scale, int causal,
+                     const int32_t *kv_len, int dtype, void *stream) {
+    if (n_k <= 0) return ELSA_ERR_INVALID_ARG;
+    if (d == d_v) return attn_fwd_impl(q, k, v, out, lse, B, H, n_q, d, scale, causal, kv_len, dtype, stream, n_k);
+    if (!q || !k || !v || !out) return ELSA_ERR_INVALID_ARG;
+    if (!std::isfinite(scale)) return ELSA_ERR_INVALID_ARG;
+    if (B <= 0 || H <= 0 || n_q <= 0) return ELSA_ERR_INVALID_ARG;
+    if ((long long)B * H > 0x7fffffffLL / 64) return ELSA_ERR_INVALID_ARG;
+    if (dtype != ELSA_F32 && dtype != ELSA_F16) return ELSA_ERR_UNSUPPORTED;
+    if (!dv_pair_ok(d, d_v)) return ELSA_ERR_UNSUPPORTED;
+    const bool fp16_tiles = dtype == ELSA_F16 && scale != 0.f && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 3);
+    // the states of a key split hold d_v columns: the workspace is sized by d_v
+    const int C = g.ws ? auto_splits(B, H, n_q, n_k, d_v, fp16_tiles) : 1;
+    if (C == 1)
+        return run_forward_dv(q, k, v, out, lse, nullptr, nullptr, nullptr, B, H, n_q, n_k, d, d_v, scale, causal, kv_len,
+                              1, 0, dtype, stream);
+    float *pm, *pS, *pW;
+    carve(g.ws, B, H, n_q, d_v, C, &pm, &pS, &pW);
+    const int rc = run_forward_dv(q, k, v, nullptr, nullptr, pm, pS, pW, B, H, n_q, n_k, d, d_v, scale, causal, kv_len,
+                                  C, 1, dtype, stream);
+    if (rc != ELSA_OK) return rc;
+    elsa::CombineParams cp{pm, pS, pW, out, lse, (long long)B * H * n_q, n_q, C, 0, dtype == ELSA_F16};
+    return elsa::launch_combine(cp, d_v, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
 }
 
 int elsa_attn_fwd(const void *q, const void *k, const void *v, void *out,

@@ -291,6 +291,10 @@ int launch_fwd_fma(const FwdParams &p, int d, int f16, int variant, hipStream_t 
 int launch_fwd_mfma16(const FwdParams &p, int d, int variant, hipStream_t s, const char **name);
 int launch_fwd_mfma_small(const FwdParams &p, int d, int f16, int nq, hipStream_t s);
 int launch_fwd_decode(const FwdParams &p, int d, int f16, int nq, hipStream_t s);
+// d_v != d (see elsa_fwd_dv.hip): FP32 matrix cores for either I/O type, FP16 matrix cores for FP16 I/O
+int launch_fwd_dv32(const FwdParams &p, int d, int dv, int f16, int variant, hipStream_t s, const char **name);
+int launch_fwd_dv16(const FwdParams &p, int d, int dv, int variant, hipStream_t s, const char **name);
+int dv_variant_tq(int fp16_tiles, int variant, int d, int dv);   // queries per block (0: no such tile)
 int launch_combine(const CombineParams &p, int d, hipStream_t s);
 int launch_probe(float *out, hipStream_t s);
 int mfma_variant_tq(int variant, int d);   // queries per block of a variant (0 if unknown)

@@ -16,8 +16,9 @@ LIB_PATH = os.path.join(_HERE, "libelsa.so")
 F32, F16 = 0, 1
 OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP, OPT_SNAKE = 0, 1, 2, 3, 4
 PATH_AUTO, PATH_FMA, PATH_MFMA, PATH_MFMA16 = 0, 1, 2, 3
+OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
-EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_lse", "elsa_attn_fwd_cross", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
+EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_lse", "elsa_attn_fwd_cross", "elsa_attn_fwd_dv", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
            "elsa_stream_state_bytes", "elsa_attn_stream_step", "elsa_attn_stream_finish",
            "elsa_split_kv_workspace_bytes", "elsa_set_workspace", "elsa_set_option", "elsa_get_option",
            "elsa_variant_name", "elsa_last_kernel", "elsa_status_string", "elsa_debug_layout_probe")
@@ -32,6 +33,7 @@ _lib.elsa_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _i, _
 _lib.elsa_attn_fwd_masked.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
 _lib.elsa_attn_fwd_lse.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
 _lib.elsa_attn_fwd_cross.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
+_lib.elsa_attn_fwd_dv.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
 _lib.elsa_stream_state_bytes.argtypes = [_i, _i, _i, _i]
 _lib.elsa_stream_state_bytes.restype = ctypes.c_size_t
 _lib.elsa_attn_stream_step.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _i, _vp, _i, _i, _vp]
@@ -137,6 +139,24 @@ def elsa_attn_fwd_cross(q, k, v, out, scale, causal=False, kv_len=None, lse=None
         assert lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, H, nq)
     _check(_lib.elsa_attn_fwd_cross(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, nq, nk, d, float(scale),
                                     int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
+    return out
+
+
+def elsa_attn_fwd_dv(q, k, v, out, scale, causal=False, kv_len=None, lse=None, stream=None):
+    """q: [B, H, n_q, d]; k: [B, H, n_k, d]; v: [B, H, n_k, d_v]; out: [B, H, n_q, d_v]; lse (optional): float32 [B, H, n_q]."""
+    import torch
+    assert q.is_cuda and q.dim() == 4 and k.dim() == 4 and v.dim() == 4 and out.dim() == 4
+    assert q.is_contiguous() and k.is_contiguous() and v.is_contiguous() and out.is_contiguous()
+    assert q.dtype == k.dtype == v.dtype == out.dtype
+    B, H, nq, d = q.shape
+    nk, dv = v.shape[2], v.shape[3]
+    assert tuple(k.shape) == (B, H, nk, d) and tuple(v.shape) == (B, H, nk, dv) and tuple(out.shape) == (B, H, nq, dv)
+    if kv_len is not None:
+        assert kv_len.is_cuda and kv_len.dtype == torch.int32 and tuple(kv_len.shape) == (B,)
+    if lse is not None:
+        assert lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, H, nq)
+    _check(_lib.elsa_attn_fwd_dv(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, nq, nk, d, dv, float(scale),
+                                 int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
     return out
 
 

@@ -97,3 +97,16 @@ def fwd_cross(q, k, v, scale, causal=False, kv_len=None, want_lse=False):
     torch.cuda.synchronize()
     o = out.reshape(-1, q.shape[-1]).double().cpu().numpy()
     return (o, lse.reshape(-1).double().cpu().numpy()) if want_lse else o
+
+
+def fwd_dv(q, k, v, scale, causal=False, kv_len=None, want_lse=False):
+    """elsa_attn_fwd_dv on numpy inputs (q [B,H,nq,d]; k [B,H,nk,d]; v [B,H,nk,dv]) -> float64 [R, dv] (, lse [R])."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    tq, tk, tv, tl = to_dev(q), to_dev(k), to_dev(v), to_dev(kv_len)
+    out = torch.full(tq.shape[:3] + (v.shape[-1],), float("nan"), device="cuda", dtype=tq.dtype)
+    lse = torch.full(tq.shape[:3], float("nan"), device="cuda") if want_lse else None
+    elsa.elsa_attn_fwd_dv(tq, tk, tv, out, scale, causal, tl, lse)
+    torch.cuda.synchronize()
+    o = out.reshape(-1, v.shape[-1]).double().cpu().numpy()
+    return (o, lse.reshape(-1).double().cpu().numpy()) if want_lse else o

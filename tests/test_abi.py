@@ -87,6 +87,15 @@ def test_bad_arguments_are_rejected_before_any_launch():
                                              kw.get("d", 64), 0.125, 0, None, 0, None)
     assert x(q=None) == INV and x(nq=0) == INV and x(nk=0) == INV and x(nk=-3) == INV and x(d=80) == UNS
     assert x(nq=1, nk=1 << 24, d=128) == UNS   # the key slice, not the query count, sets the limit
+    dv = lambda **kw: lib.elsa_attn_fwd_dv(kw.get("q", p), p, p, kw.get("out", p), None, 1, 1, kw.get("nq", 4), kw.get("nk", 8),
+                                           kw.get("d", 64), kw.get("dv", 128), kw.get("scale", 0.125), 0, None,
+                                           kw.get("dtype", 0), None)
+    assert dv(q=None) == INV and dv(out=None) == INV and dv(nq=0) == INV and dv(nk=0) == INV
+    assert dv(scale=float("nan")) == INV and dv(dtype=2) == UNS
+    for d_, dv_ in ((64, 96), (96, 64), (192, 64), (64, 192), (256, 128), (48, 64), (64, 0)):
+        assert dv(d=d_, dv=dv_) == UNS
+    assert dv(d=80, dv=80) == UNS               # equal widths: the rules of the rectangular entry point
+    assert dv(nq=1, nk=1 << 23, d=32, dv=128) == UNS   # the wider of the K and V slices sets the 2 GiB limit
     st = lambda **kw: lib.elsa_attn_stream_step(kw.get("q", p), p, p, kw.get("state", p), 1, 1, kw.get("nq", 4),
                                                 kw.get("nc", 8), kw.get("d", 64), 0.125, 0, 0, None, 1, 0, None)
     assert st(q=None) == INV and st(state=None) == INV and st(nq=0) == INV and st(nc=0) == INV and st(d=80) == UNS
