@@ -115,3 +115,51 @@ def test_random_cases(block):
         finally:
             elsa.elsa_set_workspace(None)
         assert_parity(out, ref, tol, what)
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_random_cases_with_a_value_width_of_their_own(block):
+    """The same sweep for elsa_attn_fwd_dv: pairs, shapes, masks, tiles, work orders, key chunks."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    rng = np.random.default_rng(9500 + block)
+    ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+    pairs = [(32, 64), (32, 128), (64, 32), (64, 128), (128, 32), (128, 64), (192, 128)]
+    for i in range(20):
+        d, dv = pairs[int(rng.integers(0, len(pairs)))]
+        fp16 = bool(rng.integers(0, 2))
+        B, H = int(rng.integers(1, 5)), int(rng.integers(1, 5))
+        nk = int(rng.choice([1, 7, 31, 32, 33, 64, 100, 129, 257, 500, 777, 1300]))
+        nq = nk if rng.integers(0, 2) else int(rng.choice([1, 2, 5, 33, 64, 130, 300]))
+        causal = bool(rng.integers(0, 2))
+        kv_len = rng.integers(0, nk + 1, size=B).astype(np.int32) if rng.integers(0, 2) else None
+        variant = int(rng.choice([0, 1, 3]))
+        splits = int(rng.choice([0, 0, 2, 3]))
+        if splits > nk:
+            splits = 0
+        opts = dict(variant=variant, snake=int(rng.integers(0, 2)), xcd_map=int(rng.choice([0, 0, 1, 2])), splits=splits)
+        if fp16 and rng.integers(0, 4) == 0:
+            opts["path"] = 2
+        if variant == 3 and d == 192 and (not fp16 or opts.get("path") == 2):
+            opts["variant"] = 0                  # the FP32 tiles have no key-splitting shape at d = 192
+        seed = 9600 + 100 * block + i
+        what = "fuzz dv %d/%d d=%d dv=%d fp16=%d B=%d H=%d nq=%d nk=%d causal=%d len=%s %s" % (
+            block, i, d, dv, fp16, B, H, nq, nk, causal, kv_len is not None, opts)
+        print(what, flush=True)
+        q = inputs.normal(seed, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
+        k = inputs.normal(seed, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
+        v = inputs.normal(seed, 2, 0, B * H * nk * dv).reshape(B, H, nk, dv)
+        if fp16:
+            q, k, v = (t.astype(np.float16) for t in (q, k, v))
+        scale = float(np.float32(d ** -0.5))
+        ref, ref_lse = oracle.dv_rows(f32(q), f32(k), f32(v), scale, causal=causal, kv_len=kv_len)
+        try:
+            elsa.elsa_set_workspace(ws if splits else None)
+            with G.Options(**opts):
+                out, lse = G.fwd_dv(q, k, v, scale, causal=causal, kv_len=kv_len, want_lse=True)
+        finally:
+            elsa.elsa_set_workspace(None)
+        vis = np.isfinite(ref_lse)
+        assert np.all(np.isneginf(lse[~vis])), what
+        assert np.max(np.abs(lse[vis] - ref_lse[vis]), initial=0.0) < (5e-3 if fp16 else 3e-5), what
+        assert_parity(out, ref, tolerance(max(nq, nk), fp16), what)
