@@ -3,14 +3,17 @@
 
 namespace elsa {
 
-// out = W/S of part_0 (+) ... (+) part_{C-1}  (Prop. 1): m = max_c m_c, then every chunk
-// enters with weight e^{m_c - m} <= 1 (Eq. 3 folded over the chunks around the common
-// maximum).  One thread owns four value columns of one query row; the d/4 threads
-// of a row recompute the C weights, which is cheap next to the part_W traffic.
+// out = W/S of part_0 (+) ... (+) part_{C-1}  (Prop. 1).  The chunks are taken eight at a time:
+// the 8 x (m, S, W) loads of a group are independent and in flight together, the group's maximum
+// joins the running one, the running (S, W) is re-anchored (Eq. 3) and every chunk of the group
+// enters with weight e^{m_c - m} <= 1.  Up to eight chunks this is the plain two-pass form
+// (maximum first, then the weighted sums).  One thread owns four value columns of one query row;
+// the d/4 threads of a row recompute the weights, which is cheap next to the part_W traffic.
 // HBM-bound: reads C*(d+2) floats and writes d values per row.
 template <int D>
 __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
     constexpr int QPR = D / 4;
+    constexpr int G = 8;
     const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
     const long long row = idx / QPR;
     const int c4 = (int)(idx % QPR);
@@ -21,18 +24,36 @@ __global__ __launch_bounds__(256) void combine_kernel(CombineParams p) {
     const float unit = p.m_natural ? kLog2e : 1.f;
     const long long base = bh * C * (long long)p.n + i;     // + c*n per chunk
 
-    float m = -INFINITY;
-    for (int c = 0; c < C; ++c) m = fmaxf(m, p.part_m[base + (long long)c * p.n]);
-    const float msafe = (m == -INFINITY) ? 0.f : m;
-    float S = 0.f;
+    float m = -INFINITY, S = 0.f;
     f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < C; ++c) {
-        const long long pr = base + (long long)c * p.n;
-        const float wgt = exp2_fast((p.part_m[pr] - msafe) * unit);
-        S += p.part_S[pr] * wgt;
-        const f32x4 wv = Io<float>::load4(p.part_W, pr * D + 4 * c4);
-        acc += wv * wgt;
+    for (int c0 = 0; c0 < C; c0 += G) {
+        float mc[G], Sc[G];
+        f32x4 wv[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            // a group that sticks out of the chunk list re-reads the last chunk with weight zero
+            const long long pr = base + (long long)min(c0 + g, C - 1) * p.n;
+            mc[g] = p.part_m[pr];
+            Sc[g] = p.part_S[pr];
+            wv[g] = Io<float>::load4(p.part_W, pr * D + 4 * c4);
+            if (c0 + g >= C) mc[g] = -INFINITY;
+        }
+        float mnew = m;
+#pragma unroll
+        for (int g = 0; g < G; ++g) mnew = fmaxf(mnew, mc[g]);
+        const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+        const float keep = exp2_fast((m - msafe) * unit);       // 0 for the first group (m = -inf)
+        S *= keep;
+        acc *= keep;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const float wgt = exp2_fast((mc[g] - msafe) * unit);
+            S += Sc[g] * wgt;
+            acc += wv[g] * wgt;
+        }
+        m = mnew;
     }
+    const float msafe = (m == -INFINITY) ? 0.f : m;
     const float f = S > 0.f ? 1.f / S : 0.f;
     acc *= f;
     if (p.lse && c4 == 0) p.lse[row] = lse_of(msafe * unit, S);
