@@ -28,7 +28,7 @@ PEAK_FP16_TFLOPS = 2500.0       # MI355X dense FP16 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for a plain copy of known size in the same run (profiles/*_counters.md).
 MEASURED_TRAFFIC = {("sweep_n16384", "mfma_q128_k32"): 1.156e9, ("sweep_n16384", "mfma_q256_w4"): 6.606e8,
-                    ("decode_32k", "fma_decode_q1"): 2.824e9}
+                    ("decode_32k", "fma_decode_q1"): 2.685e9}
 
 
 def cpu_baseline(w, q, k, v, kv_len, gpu_out, budget_rows):
