@@ -136,6 +136,7 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     p.m_natural = m_natural;
     p.q_tiles = (n + tq - 1) / tq;
     p.tq = tq;
+    p.kv_once = p.q_tiles == 1 ? 1 : 0;
     p.cu_seqlens = cu_seqlens;
     p.num_seqs = num_seqs;
     p.total_tokens = total_tokens;
@@ -200,6 +201,7 @@ int run_forward_dv(const void *q, const void *k, const void *v, void *out, float
     p.coff = nk - n;                             // last query aligned with the last key
     p.q_tiles = (n + tq - 1) / tq;
     p.tq = tq;
+    p.kv_once = p.q_tiles == 1 ? 1 : 0;
     p.xcd_map = g.opt[ELSA_OPT_XCD_MAP];
     p.snake = g.opt[ELSA_OPT_SNAKE] == 1 ? 0 : 1;
     p.sort_batches = (kv_len && (!causal || p.q_tiles == 1) && B >= 2 && B <= 32 && p.snake && p.xcd_map == 0) ? 1 : 0;

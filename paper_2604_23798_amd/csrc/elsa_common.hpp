@@ -41,6 +41,7 @@ struct FwdParams {
     int coff;                        // dense layout, causal: key j is visible to query i iff j <= i + coff
     int m_natural;                   // 1: part_m in natural-log units, 0: log2 units (internal)
     int xcd_map;                     // block -> work item order, see decode_work
+    int kv_once;                     // 1: one query tile per (batch, head) -- every K/V byte is read once, loads may stream
     int q_tiles;                     // ceil(n / T_q) for the launched configuration
     int tq;                          // T_q of the launched configuration
     // packed variable-length layout [total_tokens][H][d] (nullptr = dense [B][H][n][d]):
@@ -269,6 +270,9 @@ template <> struct Io<float> {
     static __device__ __forceinline__ f32x4 bload4(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
         return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0));
     }
+    static __device__ __forceinline__ f32x4 bload4_nt(__amdgpu_buffer_rsrc_t r, int voff, int soff) {   // non-temporal
+        return __builtin_bit_cast(f32x4, __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 2));
+    }
 };
 template <> struct Io<_Float16> {
     static __device__ __forceinline__ f32x4 load4(const void *base, long long elem) {
@@ -281,6 +285,10 @@ template <> struct Io<_Float16> {
     }
     static __device__ __forceinline__ f32x4 bload4(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
         const f16x4 h = __builtin_bit_cast(f16x4, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0));
+        return f32x4{(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
+    }
+    static __device__ __forceinline__ f32x4 bload4_nt(__amdgpu_buffer_rsrc_t r, int voff, int soff) {
+        const f16x4 h = __builtin_bit_cast(f16x4, __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 2));
         return f32x4{(float)h[0], (float)h[1], (float)h[2], (float)h[3]};
     }
 };

@@ -20,7 +20,7 @@ static int launch_dv32(const FwdParams &p, int variant, hipStream_t s) {
     if (variant == 3) {
         if constexpr (D == 192) return (int)hipErrorInvalidValue;
         else if constexpr (small) return launch_one<D, T, 1, 1, 4, 32, 2, 2, 1, DV>(p, s);
-        else return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1, DV>(p, s);
+        else return launch_one<D, T, 1, 2, 2, 32, 1, 2, 1, DV>(p, s);   // its tiles leave room for one block per CU: no register cap
     }
     // waves per SIMD the registers allow: three for the narrow pairs, one at d = 192
     constexpr int WPE = D == 192 ? 1 : small ? 3 : 2;

@@ -49,7 +49,9 @@ static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
             if constexpr (D == 128) return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1>(p, s);   // no room for two query groups
             else return launch_one<D, T, 2, 4, 1, KS, 2, 2, 1>(p, s);
         case 3:
-            if constexpr (D == 128) return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
+            // d = 128: two 64-key tiles of K and V fill the LDS of a CU, so one block (one wave per SIMD)
+            // is resident anyway: no register cap (the cap of two waves per SIMD spilled 20 registers)
+            if constexpr (D == 128) return launch_one<D, T, 1, 2, 2, 32, 1, 2, 1>(p, s);
             else return launch_one<D, T, 1, 1, 4, 32, 2, 2, 1>(p, s);
         case 4:
             // d = 64: 8 waves on 32-key tiles, 4 per SIMD in 128 registers.  d = 128 has no such

@@ -132,6 +132,20 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
     }
     auto gload = [&](int t) {
         const int soff = (int)((long long)(kbeg + t * TKB) * ts * 2);
+        if constexpr (WK > 1) {
+            // key-splitting tiles with a single query tile per head read K and V exactly once:
+            // non-temporal loads (whole lines per instruction) keep the stream out of the caches' way
+            if (p.kv_once) {
+                const int soffv = (int)((long long)(kbeg + t * TKB) * tsv * 2);
+#pragma unroll
+                for (int i = 0; i < LPT; ++i)
+                    kst[i] = __builtin_bit_cast(f16x8, __builtin_amdgcn_raw_buffer_load_b128(krs, voff[i], soff, 2));
+#pragma unroll
+                for (int i = 0; i < LPTV; ++i)
+                    vst[i] = __builtin_bit_cast(f16x8, __builtin_amdgcn_raw_buffer_load_b128(vrs, voffv[i], soffv, 2));
+                return;
+            }
+        }
         if constexpr (DV == D) {                // K and V loads interleaved
 #pragma unroll
             for (int i = 0; i < LPT; ++i) {

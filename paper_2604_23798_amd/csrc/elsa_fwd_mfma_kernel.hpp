@@ -131,6 +131,18 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
         const int kb0 = kbeg + t * TKB;
         if constexpr (BUF) {
             const int soff = (int)((long long)kb0 * ts * (long long)sizeof(T));
+            if constexpr (WK > 1) {
+                // key-splitting tiles with a single query tile per head read K and V exactly once:
+                // non-temporal loads (whole lines per instruction) keep the stream out of the caches' way
+                if (p.kv_once) {
+                    const int soffv = (int)((long long)kb0 * tsv * (long long)sizeof(T));
+#pragma unroll
+                    for (int i = 0; i < LPT; ++i) kst[i] = Io<T>::bload4_nt(krs, voff[i], soff);
+#pragma unroll
+                    for (int i = 0; i < LPTV; ++i) vst[i] = Io<T>::bload4_nt(vrs, voffv[i], soffv);
+                    return;
+                }
+            }
             if constexpr (DV == D) {            // K and V loads interleaved
 #pragma unroll
                 for (int i = 0; i < LPT; ++i) {
