@@ -142,6 +142,7 @@ def main():
     ap.add_argument("--path", default="auto", choices=["auto", "fma", "mfma", "mfma16"])
     ap.add_argument("--variant", type=int, default=0)
     ap.add_argument("--xcd-map", type=int, default=0)
+    ap.add_argument("--splits", type=int, default=0, help="key chunks per (batch, head): 0 = the library's choice, 1 = single pass")
     ap.add_argument("--oracle-rows", type=int, default=16384, help="row budget of the cpu_baseline leg (0 = skip)")
     ap.add_argument("--pre-warm-ms", type=float, default=0.0,
                     help="run untimed steps for this long before the W warm-up steps (short workloads otherwise "
@@ -230,6 +231,7 @@ def main():
     elsa.elsa_set_option(elsa.OPT_PATH, {"auto": 0, "fma": 1, "mfma": 2, "mfma16": 3}[a.path])
     elsa.elsa_set_option(elsa.OPT_VARIANT, a.variant)
     elsa.elsa_set_option(elsa.OPT_XCD_MAP, a.xcd_map)
+    elsa.elsa_set_option(elsa.OPT_SPLITS, a.splits)
 
     if a.calibrate_copy:               # a copy kernel of known size: 256 MiB read + 256 MiB written
         src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
@@ -325,7 +327,7 @@ def main():
         "dtype": "f16 io / f32 state" if fp16 else "f32", "data": "synthetic",
         "pct_of_fp32_peak": 100.0 * value / PEAK_FP32_TFLOPS,
         "config": {"workload": name, "causal": bool(causal), "kernel": kernel, "path": a.path, "graph": bool(a.graph),
-                   "stream_chunks": a.stream_chunks},
+                   "stream_chunks": a.stream_chunks, "splits": a.splits},
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
                      "frac": achieved / peak, "traffic": MEASURED_TRAFFIC.get((name, kernel)),
                      "kernel_ms": ms_kernel},

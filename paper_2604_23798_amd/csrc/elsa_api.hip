@@ -62,6 +62,53 @@ int pick_variant(int path, long long BH, int n, int nk, int d, int splits, int c
     return d <= 64 ? 7 : 1;
 }
 
+// Tile shape and number of key chunks for small FP32 problems (d <= 64, dense layout), where the
+// choice decides how evenly the blocks fill the 256 CUs.  A block's time is its 32-key steps per
+// wave times the step time (the matrix core and the vector ALU of a SIMD take turns, so blocks
+// that share a CU add up); a launch takes the steps of its busiest CU, plus a prologue, plus the
+// combine pass when the keys are cut.  Step times are measured (d = 64; us): 128-row tile 2.0 (2.25
+// when a CU holds one block), 64-row tile with two key waves 2.15 (2.4), 32-row tile with four key
+// waves 2.25.  Within about 10 % of the measured launch times on B*H = 8 .. 192, n = 197 .. 4096.
+struct TileChoice { int variant, splits; };
+TileChoice choose_small_fp32(long long BH, int n, int nk, int d, int causal, int max_splits) {
+    // `uneven`: how far the busiest CU exceeds the mean when the blocks differ in length (causal mask)
+    struct Shape { int variant, rows, key_waves, resident; double t1, t2, uneven; };
+    static const Shape shapes[3] = {{7, 128, 1, 3, 2.25, 2.0, 1.3}, {11, 64, 2, 2, 2.4, 2.15, 1.1}, {3, 32, 4, 1, 2.25, 2.25, 1.3}};
+    const double dscale = 0.12 + 0.88 * d / 64.0;        // the MFMA part of a step grows with d
+    const double prologue = 5.0;
+    const int coff = nk - n;
+    TileChoice best{7, 1};
+    double best_t = 1e30;
+    for (const Shape &sh : shapes) {
+        const int q_tiles = (n + sh.rows - 1) / sh.rows;
+        for (int C = 1; C <= max_splits; ++C) {
+            if (C > 1 && (sh.variant == 3 || nk / C < 256)) break;   // the 32-row tile splits the keys by itself
+            const int chunk = (nk + C - 1) / C;
+            long long total = 0;
+            int smax = 0;
+            for (int t = 0; t < q_tiles; ++t)
+                for (int c = 0; c < C; ++c) {
+                    int hi = nk < (c + 1) * chunk ? nk : (c + 1) * chunk;
+                    if (causal) { const int lim = (t + 1) * sh.rows + coff; if (lim < hi) hi = lim; }
+                    const int vis = hi - c * chunk;
+                    const int steps = vis > 0 ? (vis + 32 * sh.key_waves - 1) / (32 * sh.key_waves) : 0;
+                    total += steps;
+                    if (steps > smax) smax = steps;
+                }
+            const long long blocks = BH * q_tiles * C;
+            const long long rounds = (blocks + kNumCu - 1) / kNumCu;
+            // steps of the busiest CU: equal blocks stack in rounds; unequal (causal) ones are dealt longest first
+            double busiest = causal ? sh.uneven * (double)(total * BH) / kNumCu : (double)rounds * smax;
+            if (busiest < smax) busiest = smax;
+            const double step = (rounds >= 2 && sh.resident >= 2 ? sh.t2 : sh.t1) * dscale;
+            const double combine = C > 1 ? 7.0 + 3.0 * (double)(rounds - 1) : 0.0;   // state traffic + second launch
+            const double t = prologue * (sh.resident == 1 ? (double)rounds : 1.0) + busiest * step + combine;
+            if (t < best_t) { best_t = t; best = TileChoice{sh.variant, C}; }
+        }
+    }
+    return best;
+}
+
 // The LDS-free one-wave-per-tile kernel serves dense single-pass calls only.
 bool small_kernel_ok(const int32_t *cu_seqlens, int splits, int emit, int n, int nk) {
     return !cu_seqlens && splits == 1 && !emit && n == nk;
@@ -76,6 +123,7 @@ struct Extra {
     int accumulate = 0;                          // merge the emitted state into the stored one
     bool has_coff = false;                       // causal diagonal given explicitly (streamed chunks)
     int coff = 0;
+    int variant = 0;                             // FP32 matrix-core tile chosen by the caller (0: pick_variant decides)
 };
 
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
@@ -111,7 +159,9 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     const long long longest = cu_seqlens ? total_tokens : (nk > n ? nk : n);
     if ((path != 1 || decode_variant) && longest * tok_stride * (dtype == ELSA_F16 ? 2 : 4) >= 0x7fffffffLL) return ELSA_ERR_UNSUPPORTED;
     int variant = decode_variant ? decode_variant : pick_variant(path, (long long)B * H, n, nk, d, num_splits, causal);
-    if (path == 2) {
+    const bool hinted = path == 2 && !decode_variant && x.variant > 0 && g.opt[ELSA_OPT_VARIANT] == 0;
+    if (hinted) variant = x.variant;
+    if (path == 2 && !hinted) {
         const bool ok = small_kernel_ok(cu_seqlens, num_splits, emit, n, nk);
         // thousands of tiny problems (window attention); at n = 128 or d = 128 the 128-row tile is faster
         if (g.opt[ELSA_OPT_VARIANT] == 0 && ok && d <= 64 && n <= 96 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu)
@@ -283,9 +333,24 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     int rc = check_common(B, H, n, d, dtype);
     if (rc != ELSA_OK) return rc;
     const bool fp16_tiles = dtype == ELSA_F16 && scale != 0.f && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 3);
-    const int C = g.ws ? auto_splits(B, H, n, nk, d, fp16_tiles) : 1;
+    int C = g.ws ? auto_splits(B, H, n, nk, d, fp16_tiles) : 1;
     Extra x;
     x.nk = nk;
+    // small FP32 problems: tile shape and key chunks together, from the block-placement model
+    const long long b128 = (long long)B * H * ((n + 127) / 128);
+    const bool fp32_tiles = !fp16_tiles && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 2);
+    const bool window = n <= 96 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu;    // served by the LDS-free tile
+    if (fp32_tiles && d <= 64 && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= 4 * kNumCu &&
+        (long long)n * 8 > nk && n > 8 && !window) {
+        int max_c = 1;
+        if (g.ws) {
+            max_c = 8;
+            while (max_c > 1 && elsa_split_kv_workspace_bytes(B, H, n, d, max_c) > g.ws_bytes) --max_c;
+        }
+        const TileChoice tc = choose_small_fp32((long long)B * H, n, nk, d, causal, max_c);
+        x.variant = tc.variant;
+        C = tc.splits;
+    }
     if (C == 1) {
         x.lse = lse;
         return run_forward(q, k, v, out, nullptr, nullptr, nullptr, B, H, n, d, scale, causal, kv_len, 1, 0, 0, dtype,

@@ -10,10 +10,11 @@ namespace elsa {
 //     7 q128k32: 32-key tiles, 3 waves per SIMD       8 q128 with plain global loads (no descriptors)
 // All but 8 fetch tiles through buffer descriptors; all but 5/6 use 2 score chains.
 //     9/10 small: one wave per 64 / 32 query rows, operands straight from memory (elsa_fwd_small.hip)
+//     11 q64xw2: 64 query rows, two query waves x two key waves (the key-splitting shape of d >= 96)
 
 static const char *kNames[kMfmaVariants] = {"mfma_q128_w4",   "mfma_q256_w4",   "mfma_xwave",    "mfma_q256_w8",
                                             "mfma_q128_acc1", "mfma_q128_acc4", "mfma_q128_k32", "mfma_q128_gld",
-                                            "mfma_small_q64", "mfma_small_q32"};
+                                            "mfma_small_q64", "mfma_small_q32", "mfma_q64_xw2"};
 
 int mfma_variant_tq(int variant, int d) {
     switch (variant) {
@@ -23,6 +24,7 @@ int mfma_variant_tq(int variant, int d) {
         case 3: return d == 256 ? 128 : d <= 64 ? 32 : 64;   // d = 96, 128: two query waves x two key waves
         case 9: return 64;                      // one wave per 64 (32) query rows, no LDS
         case 10: return 32;
+        case 11: return d == 256 ? 128 : 64;
         default: return 0;
     }
 }
@@ -36,7 +38,7 @@ static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
     // d = 256 where the state and the query fragment fill the register file) and, for d = 96, the
     // key-splitting shape
     if constexpr (D == 96) {
-        if (variant == 3) return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
+        if (variant == 3 || variant == 11) return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
         return launch_one<D, T, 1, 4, 1, 32, 2, 2, 1>(p, s);
     } else if constexpr (D == 256) {
         return launch_one<D, T, 1, 4, 1, 32, 1, 1, 1>(p, s);
@@ -65,6 +67,9 @@ static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
             if constexpr (D == 128) return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1>(p, s);
             else return launch_one<D, T, 1, 4, 1, 32, 3, 2, 1>(p, s);
         case 8: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 0>(p, s);
+        case 11:
+            if constexpr (D == 128) return launch_one<D, T, 1, 2, 2, 32, 1, 2, 1>(p, s);
+            else return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
         default: return (int)hipErrorInvalidValue;
     }
     }

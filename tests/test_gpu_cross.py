@@ -33,7 +33,7 @@ def _ref(q, k, v, scale, **kw):
 
 
 SHAPES = [(1, 777), (5, 300), (37, 2000), (200, 64), (129, 131), (64, 1100), (300, 333)]
-KERNELS = [(2, v) for v in range(1, 9)] + [(1, 1), (1, 2)]
+KERNELS = [(2, v) for v in range(1, 9)] + [(2, 11), (1, 1), (1, 2)]
 
 
 @pytest.mark.parametrize("path,variant", KERNELS)

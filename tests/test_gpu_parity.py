@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 
 MFMA, FMA, MFMA16 = 2, 1, 3
 ALL_KERNELS = [(MFMA, 1), (MFMA, 2), (MFMA, 3), (MFMA, 4), (MFMA, 5), (MFMA, 6), (MFMA, 7), (MFMA, 8),
-               (MFMA, 9), (MFMA, 10), (FMA, 1), (FMA, 2)]
+               (MFMA, 9), (MFMA, 10), (MFMA, 11), (FMA, 1), (FMA, 2)]
 
 
 def _rand(B, H, n, d, seed, sigma=1.0, fp16=False):

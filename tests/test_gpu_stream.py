@@ -106,7 +106,7 @@ def test_default_kernels_every_step_checked(causal, fp16):
             _run(q, k, v, d ** -0.5, chunks, causal, fp16, {})
 
 
-KERNELS = [dict(path=2, variant=v) for v in (1, 2, 3, 4, 7, 8)] + [dict(path=1, variant=v) for v in (1, 2, 3, 4)]
+KERNELS = [dict(path=2, variant=v) for v in (1, 2, 3, 4, 7, 8, 11)] + [dict(path=1, variant=v) for v in (1, 2, 3, 4)]
 
 
 @pytest.mark.parametrize("opts", KERNELS, ids=lambda o: "p%d_v%d" % (o["path"], o["variant"]))
