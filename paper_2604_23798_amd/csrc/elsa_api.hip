@@ -62,7 +62,7 @@ int pick_variant(int path, long long BH, int n, int nk, int d, int splits, int c
     return d <= 64 ? 7 : 1;
 }
 
-// Tile shape and number of key chunks for small FP32 problems (d <= 64, dense layout), where the
+// Tile shape and number of key chunks for small FP32 problems (d = 32, 64, 128; dense layout), where the
 // choice decides how evenly the blocks fill the 256 CUs.  A block's time is its 32-key steps per
 // wave times the step time (the matrix core and the vector ALU of a SIMD take turns, so blocks
 // that share a CU add up); a launch takes the steps of its busiest CU, plus a prologue, plus the
@@ -73,13 +73,19 @@ struct TileChoice { int variant, splits; };
 TileChoice choose_small_fp32(long long BH, int n, int nk, int d, int causal, int max_splits) {
     // `uneven`: how far the busiest CU exceeds the mean when the blocks differ in length (causal mask)
     struct Shape { int variant, rows, key_waves, resident; double t1, t2, uneven; };
-    static const Shape shapes[3] = {{7, 128, 1, 3, 2.25, 2.0, 1.3}, {11, 64, 2, 2, 2.4, 2.15, 1.1}, {3, 32, 4, 1, 2.25, 2.25, 1.3}};
+    static const Shape narrow[3] = {{7, 128, 1, 3, 2.25, 2.0, 1.3}, {11, 64, 2, 2, 2.4, 2.15, 1.1}, {3, 32, 4, 1, 2.25, 2.25, 1.3}};
+    // d = 128: the 128-row tile holds two blocks per CU, the 64-row tile (its LDS tiles fill a CU) one
+    // (measured 5.8 us per step at d = 128 = 3.1 at d = 64 scale: one wave per SIMD hides no latency)
+    static const Shape wide[2] = {{1, 128, 1, 2, 2.25, 2.0, 1.3}, {11, 64, 2, 1, 3.1, 3.1, 1.1}};
+    const Shape *shapes = d == 128 ? wide : narrow;
+    const int nshapes = d == 128 ? 2 : 3;
     const double dscale = 0.12 + 0.88 * d / 64.0;        // the MFMA part of a step grows with d
     const double prologue = 5.0;
     const int coff = nk - n;
-    TileChoice best{7, 1};
+    TileChoice best{d == 128 ? 1 : 7, 1};
     double best_t = 1e30;
-    for (const Shape &sh : shapes) {
+    for (int si = 0; si < nshapes; ++si) {
+        const Shape &sh = shapes[si];
         const int q_tiles = (n + sh.rows - 1) / sh.rows;
         for (int C = 1; C <= max_splits; ++C) {
             if (C > 1 && (sh.variant == 3 || nk / C < 256)) break;   // the 32-row tile splits the keys by itself
@@ -340,7 +346,7 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     const long long b128 = (long long)B * H * ((n + 127) / 128);
     const bool fp32_tiles = !fp16_tiles && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 2);
     const bool window = n <= 96 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu;    // served by the LDS-free tile
-    if (fp32_tiles && d <= 64 && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= 4 * kNumCu &&
+    if (fp32_tiles && (d <= 64 || d == 128) && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= 4 * kNumCu &&
         (long long)n * 8 > nk && n > 8 && !window) {
         int max_c = 1;
         if (g.ws) {
