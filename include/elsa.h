@@ -219,16 +219,23 @@ int elsa_set_workspace(void *dev_ptr, size_t bytes);
  *                     by descending length when there are at most 64) with the second run of 256
  *                     blocks walked backwards (balances the blocks that are resident together),
  *                     1 = plain order
+ *   ELSA_OPT_DRY_RUN  1 = plan only: every entry point validates its arguments and chooses kernel,
+ *                     tile and key chunks as usual but launches nothing and touches no tensor (no GPU
+ *                     is needed); elsa_last_kernel / elsa_last_splits then report the choice
  */
-enum { ELSA_OPT_PATH = 0, ELSA_OPT_VARIANT = 1, ELSA_OPT_SPLITS = 2, ELSA_OPT_XCD_MAP = 3, ELSA_OPT_SNAKE = 4 };
+enum { ELSA_OPT_PATH = 0, ELSA_OPT_VARIANT = 1, ELSA_OPT_SPLITS = 2, ELSA_OPT_XCD_MAP = 3, ELSA_OPT_SNAKE = 4,
+       ELSA_OPT_DRY_RUN = 5 };
 int elsa_set_option(int option, int value);
 int elsa_get_option(int option, int *value);
 
 /* Name of tile configuration `variant` for path `path` (NULL when out of range). */
 const char *elsa_variant_name(int path, int variant);
 
-/* Name of the kernel configuration the last successful forward call launched. */
+/* Name of the kernel configuration the last successful forward call launched (or planned, in a dry run). */
 const char *elsa_last_kernel(void);
+
+/* Number of key chunks per (batch, head) of that call (1 = single pass, no combine launch). */
+int elsa_last_splits(void);
 
 const char *elsa_status_string(int code);
 

@@ -7,10 +7,11 @@
 namespace {
 
 struct State {
-    int opt[5] = {0, 0, 0, 0, 0};
+    int opt[6] = {0, 0, 0, 0, 0, 0};
     void *ws = nullptr;
     size_t ws_bytes = 0;
     const char *last = "";
+    int last_splits = 1;
 } g;
 
 constexpr int kMaxSplits = 65535;
@@ -203,6 +204,13 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     p.sort_batches = (kv_len && !cu_seqlens && (!causal || p.q_tiles == 1) && B >= 2 && B <= 32 && p.snake && p.xcd_map == 0) ? 1 : 0;
     const long long total = (long long)p.q_tiles * B * H * num_splits;
     if (total > 0x7fffffffLL - 8) return ELSA_ERR_INVALID_ARG;
+    g.last_splits = num_splits;
+    if (g.opt[ELSA_OPT_DRY_RUN]) {               // plan only: report what would be launched
+        const char *planned = path == 1 ? elsa::fma_variant_name(variant)
+                            : path == 3 ? elsa::mfma16_variant_name(variant) : elsa::mfma_variant_name(variant);
+        g.last = planned ? planned : "";
+        return ELSA_OK;
+    }
     const char *name = nullptr;
     const hipStream_t s = static_cast<hipStream_t>(stream);
     const int rc = path == 1   ? elsa::launch_fwd_fma(p, d, dtype == ELSA_F16, variant, s, &name)
@@ -262,6 +270,11 @@ int run_forward_dv(const void *q, const void *k, const void *v, void *out, float
     p.snake = g.opt[ELSA_OPT_SNAKE] == 1 ? 0 : 1;
     p.sort_batches = (kv_len && (!causal || p.q_tiles == 1) && B >= 2 && B <= 32 && p.snake && p.xcd_map == 0) ? 1 : 0;
     if ((long long)p.q_tiles * B * H * num_splits > 0x7fffffffLL - 8) return ELSA_ERR_INVALID_ARG;
+    g.last_splits = num_splits;
+    if (g.opt[ELSA_OPT_DRY_RUN]) {
+        g.last = fp16_tiles ? (variant == 3 ? "mfma16_dv_xwave" : "mfma16_dv_q128") : (variant == 3 ? "mfma_dv_xwave" : "mfma_dv_q128");
+        return ELSA_OK;
+    }
     const char *name = nullptr;
     const hipStream_t s = static_cast<hipStream_t>(stream);
     const int rc = fp16_tiles ? elsa::launch_fwd_dv16(p, d, dv, variant, s, &name)
@@ -367,6 +380,7 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     // internal split: maxima stay in log2 units, so the second pass adds no rounding of m
     rc = run_forward(q, k, v, nullptr, pm, pS, pW, B, H, n, d, scale, causal, kv_len, C, 1, 0, dtype, stream, x);
     if (rc != ELSA_OK) return rc;
+    if (g.opt[ELSA_OPT_DRY_RUN]) return ELSA_OK;
     elsa::CombineParams cp{pm, pS, pW, out, lse, (long long)B * H * n, n, C, 0, dtype == ELSA_F16};
     return elsa::launch_combine(cp, d, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
 }
@@ -413,6 +427,7 @@ int elsa_attn_fwd_dv(const void *q, const void *k, const void *v, void *out, flo
     const int rc = run_forward_dv(q, k, v, nullptr, nullptr, pm, pS, pW, B, H, n_q, n_k, d, d_v, scale, causal, kv_len,
                                   C, 1, dtype, stream);
     if (rc != ELSA_OK) return rc;
+    if (g.opt[ELSA_OPT_DRY_RUN]) return ELSA_OK;
     elsa::CombineParams cp{pm, pS, pW, out, lse, (long long)B * H * n_q, n_q, C, 0, dtype == ELSA_F16};
     return elsa::launch_combine(cp, d_v, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
 }
@@ -441,6 +456,7 @@ int elsa_combine(const float *part_m, const float *part_S, const float *part_W, 
     int rc = check_common(B, H, n, d, dtype);
     if (rc != ELSA_OK) return rc;
     if (num_splits < 1 || num_splits > n || num_splits > kMaxSplits) return ELSA_ERR_INVALID_ARG;
+    if (g.opt[ELSA_OPT_DRY_RUN]) return ELSA_OK;
     elsa::CombineParams cp{part_m, part_S, part_W, out, nullptr, (long long)B * H * n, n, num_splits, 1, dtype == ELSA_F16};
     return elsa::launch_combine(cp, d, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
 }
@@ -476,13 +492,15 @@ int elsa_attn_stream_finish(const void *state, void *out, float *lse, int B, int
     if (rc != ELSA_OK) return rc;
     float *pm, *pS, *pW;
     carve(const_cast<void *>(state), B, H, n_q, d, 1, &pm, &pS, &pW);
+    if (g.opt[ELSA_OPT_DRY_RUN]) return ELSA_OK;
     elsa::CombineParams cp{pm, pS, pW, out, lse, (long long)B * H * n_q, n_q, 1, 0, dtype == ELSA_F16};
     return elsa::launch_combine(cp, d, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
 }
 
 int elsa_set_option(int option, int value) {
-    if (option < 0 || option > 4) return ELSA_ERR_UNSUPPORTED;
+    if (option < 0 || option > 5) return ELSA_ERR_UNSUPPORTED;
     if (value < 0) return ELSA_ERR_INVALID_ARG;
+    if (option == ELSA_OPT_DRY_RUN && value > 1) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_PATH && value > 3) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_XCD_MAP && value > 2) return ELSA_ERR_INVALID_ARG;
     if (option == ELSA_OPT_SNAKE && value > 1) return ELSA_ERR_INVALID_ARG;
@@ -493,7 +511,7 @@ int elsa_set_option(int option, int value) {
 }
 
 int elsa_get_option(int option, int *value) {
-    if (option < 0 || option > 4) return ELSA_ERR_UNSUPPORTED;
+    if (option < 0 || option > 5) return ELSA_ERR_UNSUPPORTED;
     if (!value) return ELSA_ERR_INVALID_ARG;
     *value = g.opt[option];
     return ELSA_OK;
@@ -527,6 +545,8 @@ const char *elsa_variant_name(int path, int variant) {
 }
 
 const char *elsa_last_kernel(void) { return g.last; }
+
+int elsa_last_splits(void) { return g.last_splits; }
 
 const char *elsa_status_string(int code) {
     switch (code) {

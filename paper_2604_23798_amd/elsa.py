@@ -14,14 +14,14 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libelsa.so")
 
 F32, F16 = 0, 1
-OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP, OPT_SNAKE = 0, 1, 2, 3, 4
+OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP, OPT_SNAKE, OPT_DRY_RUN = 0, 1, 2, 3, 4, 5
 PATH_AUTO, PATH_FMA, PATH_MFMA, PATH_MFMA16 = 0, 1, 2, 3
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
 EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_lse", "elsa_attn_fwd_cross", "elsa_attn_fwd_dv", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
            "elsa_stream_state_bytes", "elsa_attn_stream_step", "elsa_attn_stream_finish",
            "elsa_split_kv_workspace_bytes", "elsa_set_workspace", "elsa_set_option", "elsa_get_option",
-           "elsa_variant_name", "elsa_last_kernel", "elsa_status_string", "elsa_debug_layout_probe")
+           "elsa_variant_name", "elsa_last_kernel", "elsa_last_splits", "elsa_status_string", "elsa_debug_layout_probe")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError("libelsa.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -262,6 +262,10 @@ def elsa_variant_name(path, variant):
 
 def elsa_last_kernel() -> str:
     return _lib.elsa_last_kernel().decode()
+
+
+def elsa_last_splits() -> int:
+    return int(_lib.elsa_last_splits())
 
 
 def elsa_debug_layout_probe(out, stream=None):

@@ -24,7 +24,7 @@ class Options:
 
     def __exit__(self, *a):
         from paper_2604_23798_amd import elsa
-        for o in range(5):
+        for o in range(6):
             elsa.elsa_set_option(o, 0)
         return False
 

@@ -32,7 +32,7 @@ def test_status_strings_and_options():
     from paper_2604_23798_amd import elsa
     assert elsa.status_string(0) == "ok"
     assert "invalid" in elsa.status_string(1) and "unknown" in elsa.status_string(99)
-    for opt in range(5):
+    for opt in range(6):
         assert elsa.elsa_get_option(opt) == 0
     elsa.elsa_set_option(elsa.OPT_PATH, 1)
     assert elsa.elsa_get_option(elsa.OPT_PATH) == 1

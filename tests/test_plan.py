@@ -1,0 +1,105 @@
+"""Host logic without a GPU: with ELSA_OPT_DRY_RUN every entry point validates, chooses kernel, tile
+and key chunks as usual and launches nothing, so the choices documented for the workloads can be
+checked on the CPU.  Pointers are dummies that are never dereferenced."""
+import ctypes
+
+import pytest
+
+from paper_2604_23798_amd import elsa
+
+P = ctypes.c_void_p(1 << 20)          # 256-byte aligned, never dereferenced
+
+
+@pytest.fixture(autouse=True)
+def _dry_run():
+    elsa.elsa_set_option(elsa.OPT_DRY_RUN, 1)
+    yield
+    for o in range(6):
+        elsa.elsa_set_option(o, 0)
+    elsa.raw().elsa_set_workspace(None, 0)
+
+
+def plan(B, H, nq, nk, d, causal=False, dtype=0, kv_len=False, ws_mib=0, dv=None, scale=0.125, **opts):
+    lib = elsa.raw()
+    assert lib.elsa_set_workspace(P if ws_mib else None, ws_mib << 20) == 0
+    for name, val in opts.items():
+        elsa.elsa_set_option(getattr(elsa, "OPT_" + name.upper()), val)
+    if dv is None:
+        rc = lib.elsa_attn_fwd_cross(P, P, P, P, None, B, H, nq, nk, d, scale, int(causal), P if kv_len else None, dtype, None)
+    else:
+        rc = lib.elsa_attn_fwd_dv(P, P, P, P, None, B, H, nq, nk, d, dv, scale, int(causal), P if kv_len else None, dtype, None)
+    for name in opts:
+        elsa.elsa_set_option(getattr(elsa, "OPT_" + name.upper()), 0)
+    assert rc == 0, elsa.status_string(rc)
+    return elsa.elsa_last_kernel(), elsa.elsa_last_splits()
+
+
+def test_headline_and_long_sequences_take_the_128_row_tiles_in_one_pass():
+    assert plan(1, 16, 16384, 16384, 64, ws_mib=256) == ("mfma_q128_k32", 1)
+    assert plan(1, 16, 65536, 65536, 64, ws_mib=256) == ("mfma_q128_k32", 1)
+    assert plan(1, 40, 32768, 32768, 128, causal=True, ws_mib=256) == ("mfma_q128_w4", 1)
+    assert plan(16, 12, 512, 512, 64, ws_mib=256) == ("mfma_q128_k32", 1)
+    assert plan(1, 16, 16384, 16384, 64, dtype=1) == ("mfma16_q256_w4", 1)
+    assert plan(1, 16, 16384, 16384, 64, dtype=1, causal=True) == ("mfma16_q128_w4", 1)   # diagonal tiles waste less
+    assert plan(1, 40, 32768, 32768, 128, causal=True, dtype=1) == ("mfma16_q128_w4", 1)
+    assert plan(1, 16, 8192, 8192, 96) == ("mfma_q128_w4", 1) and plan(1, 16, 8192, 8192, 256) == ("mfma_q128_w4", 1)
+
+
+def test_small_problems_follow_the_block_placement_model():
+    # one image of ViT-B/16: 84 blocks of 32 rows whose waves split the keys
+    assert plan(1, 12, 197, 197, 64) == ("mfma_xwave", 1)
+    assert plan(1, 12, 197, 197, 64, ws_mib=64) == ("mfma_xwave", 1)         # never cut further
+    assert plan(4, 12, 197, 197, 64) == ("mfma_q64_xw2", 1)
+    assert plan(1, 16, 1024, 1024, 64, ws_mib=64) == ("mfma_q64_xw2", 1)
+    assert plan(1, 16, 1024, 1024, 64, causal=True, ws_mib=64) == ("mfma_q64_xw2", 2)
+    assert plan(1, 16, 1024, 1024, 64, causal=True) == ("mfma_xwave", 1)     # no workspace, no key chunks: 32-row tiles
+    # 192 blocks of 128 rows would fill the CUs 0.75 times, 768 fill them exactly three times
+    assert plan(1, 16, 1536, 1536, 64, ws_mib=64) == ("mfma_q128_k32", 4)
+    assert plan(1, 16, 3072, 3072, 64, ws_mib=64) == ("mfma_q128_k32", 2)
+    assert plan(1, 40, 1024, 1024, 128, ws_mib=256) == ("mfma_q128_w4", 4)
+    # a forced tile or chunk count switches the model off
+    assert plan(1, 16, 1024, 1024, 64, ws_mib=64, variant=7) == ("mfma_q128_k32", 2)
+    assert plan(1, 16, 1024, 1024, 64, ws_mib=64, splits=3)[1] == 3
+    # FP16 tiles are not cut outside decoding
+    assert plan(1, 16, 1024, 1024, 64, dtype=1, ws_mib=64) == ("mfma16_xwave", 1)
+
+
+def test_window_attention_takes_the_lds_free_tile():
+    assert plan(512, 3, 49, 49, 32) == ("mfma_small_q32", 1)
+    assert plan(392, 3, 64, 64, 32) == ("mfma_small_q32", 1)
+    assert plan(128, 3, 196, 196, 32) == ("mfma_q128_k32", 1)
+    assert plan(128, 3, 256, 256, 32) == ("mfma_q128_k32", 1)
+
+
+def test_decoding_streams_the_cache_with_the_vector_kernel():
+    assert plan(2, 40, 1, 32768, 128, causal=True) == ("fma_decode_q1", 1)
+    assert plan(2, 40, 1, 32768, 128, causal=True, ws_mib=256) == ("fma_decode_q1", 16)   # five blocks per CU
+    assert plan(2, 40, 4, 32768, 128, causal=True, dtype=1, ws_mib=256) == ("fma_decode_q4", 16)
+    assert plan(2, 40, 8, 32768, 128, ws_mib=256)[0] == "fma_decode_q4"                  # FP32, d = 128: up to eight
+    assert plan(2, 40, 8, 32768, 128, dtype=1, ws_mib=256)[0] == "mfma16_xwave"
+    assert plan(2, 40, 16, 32768, 64, ws_mib=256)[0] == "mfma_xwave"
+    assert plan(2, 40, 1, 32768, 256)[0] == "fma_decode_q1" and plan(2, 40, 3, 32768, 96)[0] == "fma_decode_q1"
+    name, C = plan(1, 1, 1, 1 << 20, 64, ws_mib=256)
+    assert name == "fma_decode_q1" and C == 64                                            # at most 64 chunks
+    assert plan(1, 8, 1, 300, 64, ws_mib=256) == ("fma_decode_q1", 1)                     # chunks of >= 256 keys only
+
+
+def test_value_width_of_its_own():
+    assert plan(1, 16, 8192, 8192, 192, dv=128) == ("mfma_dv_q128", 1)
+    assert plan(1, 16, 8192, 8192, 192, dv=128, dtype=1) == ("mfma16_dv_q128", 1)
+    assert plan(1, 16, 8192, 8192, 64, dv=128, dtype=1, scale=0.0) == ("mfma_dv_q128", 1)     # FP16 tiles need a scale
+    assert plan(2, 3, 1, 5000, 64, dv=128) == ("mfma_dv_xwave", 1)
+    assert plan(2, 3, 1, 5000, 192, dv=128) == ("mfma_dv_q128", 1)       # no FP32 key-splitting tile at d = 192
+    assert plan(2, 3, 1, 5000, 192, dv=128, dtype=1) == ("mfma16_dv_xwave", 1)
+    name, C = plan(2, 3, 1, 5000, 64, dv=128, ws_mib=64)
+    assert name == "mfma_dv_xwave" and C == 19                           # 5000 // 256 chunks
+    assert plan(1, 4, 130, 500, 64, dv=64, causal=True) == plan(1, 4, 130, 500, 64, causal=True)   # forwarded
+
+
+def test_a_dry_run_still_validates():
+    lib = elsa.raw()
+    assert lib.elsa_attn_fwd_cross(None, P, P, P, None, 1, 1, 8, 8, 64, 0.125, 0, None, 0, None) == elsa.ERR_INVALID_ARG
+    assert lib.elsa_attn_fwd_cross(P, P, P, P, None, 1, 1, 8, 8, 80, 0.125, 0, None, 0, None) == elsa.ERR_UNSUPPORTED
+    assert lib.elsa_attn_fwd_dv(P, P, P, P, None, 1, 1, 8, 8, 64, 96, 0.125, 0, None, 0, None) == elsa.ERR_UNSUPPORTED
+    with pytest.raises(elsa.ElsaError):
+        elsa.elsa_set_option(elsa.OPT_DRY_RUN, 2)
