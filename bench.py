@@ -225,7 +225,7 @@ def main():
             exec_flops = 4.0 * w.H * w.n * w.d * float(np.minimum(kv_len, w.n).sum())
     tq, tk, tv = (torch.from_numpy(t).cuda() for t in (q, k, v))
     tl = None if kv_len is None else torch.from_numpy(kv_len).cuda()
-    out = torch.empty(tq.shape[:3] + (tv.shape[-1],), dtype=tq.dtype, device="cuda")
+    out = torch.empty(tq.shape[:-1] + (tv.shape[-1],), dtype=tq.dtype, device="cuda")
     ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
     elsa.elsa_set_workspace(ws)
     elsa.elsa_set_option(elsa.OPT_PATH, {"auto": 0, "fma": 1, "mfma": 2, "mfma16": 3}[a.path])
