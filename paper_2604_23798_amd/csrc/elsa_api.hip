@@ -152,9 +152,11 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     if (g.opt[ELSA_OPT_PATH] == 0 && g.opt[ELSA_OPT_VARIANT] == 0 && !cu_seqlens && n <= decode_max) {
         path = 1;
         decode_variant = (n == 1 || head_dim_wide(d)) ? 3 : 4;
+        if (n > 4 && dtype == ELSA_F32 && d == 128) decode_variant = 5;   // eight queries per block: K and V read once
     }
-    if (path == 1 && (g.opt[ELSA_OPT_VARIANT] == 3 || g.opt[ELSA_OPT_VARIANT] == 4)) {
+    if (path == 1 && g.opt[ELSA_OPT_VARIANT] >= 3 && g.opt[ELSA_OPT_VARIANT] <= 5) {
         if (cu_seqlens) return ELSA_ERR_UNSUPPORTED;
+        if (g.opt[ELSA_OPT_VARIANT] == 5 && (dtype != ELSA_F32 || d != 128)) return ELSA_ERR_UNSUPPORTED;
         decode_variant = g.opt[ELSA_OPT_VARIANT];
     }
     if (head_dim_wide(d)) {                      // no FMA tiles, no four-query decode, no LDS-free tiles

@@ -312,7 +312,7 @@ const char *mfma16_variant_name(int variant);
 const char *mfma_variant_name(int variant);
 const char *fma_variant_name(int variant);
 constexpr int kMfmaVariants = 11;
-constexpr int kFmaVariants = 4;
+constexpr int kFmaVariants = 5;
 constexpr int kMfma16Variants = 3;
 
 }  // namespace elsa

@@ -82,7 +82,7 @@ template <int AUX> struct Piece<_Float16, AUX> {
 }  // namespace
 
 template <int D, typename T, int NQ>
-__global__ __launch_bounds__(256, (NQ == 1 && D != 96 && D != 256) ? 5 : 1) void fwd_decode_kernel(FwdParams p) {
+__global__ __launch_bounds__(256, (NQ == 1 && D != 96 && D != 256) ? 5 : NQ == 8 ? 2 : 1) void fwd_decode_kernel(FwdParams p) {
     constexpr int LPR = D == 96 ? 4 : D == 256 ? 16 : D / 8;   // lanes per key row (a power of two <= 16)
     constexpr int CPL = D / LPR;         // columns per lane: 8, 16 or 24
     constexpr int KPI = 64 / LPR;        // keys per wave instruction
@@ -243,7 +243,7 @@ __global__ __launch_bounds__(256, (NQ == 1 && D != 96 && D != 256) ? 5 : 1) void
         }
     }
     __syncthreads();
-    if (tid >= LPR * NQ) return;         // LPR * NQ <= 64: the threads below are one wave
+    if (tid >= LPR * NQ) return;         // the LPR * NQ <= 128 threads below meet no further barrier
     const int iq = tid / LPR, cs2 = tid % LPR;
     const int row = q0 + iq;
     if (row >= n) return;
@@ -303,13 +303,17 @@ static int launch_decode_d(const FwdParams &p, int nq, hipStream_t s) {
     if constexpr (D == 96 || D == 256) {         // wide lanes: one query per block only
         return nq == 1 ? launch_decode_one<D, T, 1>(p, s) : (int)hipErrorInvalidValue;
     } else {
+        if constexpr (D == 128 && std::is_same<T, float>::value) {
+            if (nq == 8) return launch_decode_one<D, T, 8>(p, s);
+        }
+        if (nq == 8) return (int)hipErrorInvalidValue;
         return nq == 1 ? launch_decode_one<D, T, 1>(p, s) : launch_decode_one<D, T, 4>(p, s);
     }
 }
 
-// nq = 1 or 4 queries per block (p.tq must say the same).  Dense layout only.
+// nq = 1, 4 or 8 (FP32, d = 128) queries per block (p.tq must say the same).  Dense layout only.
 int launch_fwd_decode(const FwdParams &p, int d, int f16, int nq, hipStream_t s) {
-    if (p.cu_seqlens || (nq != 1 && nq != 4) || p.tq != nq) return (int)hipErrorInvalidValue;
+    if (p.cu_seqlens || (nq != 1 && nq != 4 && nq != 8) || p.tq != nq) return (int)hipErrorInvalidValue;
     if (d == 32) return f16 ? launch_decode_d<32, _Float16>(p, nq, s) : launch_decode_d<32, float>(p, nq, s);
     if (d == 64) return f16 ? launch_decode_d<64, _Float16>(p, nq, s) : launch_decode_d<64, float>(p, nq, s);
     if (d == 128) return f16 ? launch_decode_d<128, _Float16>(p, nq, s) : launch_decode_d<128, float>(p, nq, s);

@@ -157,10 +157,10 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
     }
 }
 
-// 3, 4: one / four queries per block against a long key range (elsa_fwd_decode.hip)
-static const char *kFmaNames[kFmaVariants] = {"fma_q256_w4", "fma_q64_xw4", "fma_decode_q1", "fma_decode_q4"};
+// 3, 4, 5: one / four / eight queries per block against a long key range (elsa_fwd_decode.hip; eight: FP32, d = 128)
+static const char *kFmaNames[kFmaVariants] = {"fma_q256_w4", "fma_q64_xw4", "fma_decode_q1", "fma_decode_q4", "fma_decode_q8"};
 int fma_variant_tq(int variant, int) {
-    return variant == 1 ? 256 : variant == 2 ? 64 : variant == 3 ? 1 : variant == 4 ? 4 : 0;
+    return variant == 1 ? 256 : variant == 2 ? 64 : variant == 3 ? 1 : variant == 4 ? 4 : variant == 5 ? 8 : 0;
 }
 const char *fma_variant_name(int variant) {
     return (variant >= 1 && variant <= kFmaVariants) ? kFmaNames[variant - 1] : nullptr;
@@ -197,7 +197,7 @@ static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
 
 int launch_fwd_fma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name) {
     if (name) *name = fma_variant_name(variant);
-    if (variant == 3 || variant == 4) return launch_fwd_decode(p, d, f16, variant == 3 ? 1 : 4, s);
+    if (variant >= 3 && variant <= 5) return launch_fwd_decode(p, d, f16, variant == 3 ? 1 : variant == 4 ? 4 : 8, s);
     if (d == 32) return f16 ? launch_variant<32, _Float16>(p, variant, s) : launch_variant<32, float>(p, variant, s);
     if (d == 64) return f16 ? launch_variant<64, _Float16>(p, variant, s) : launch_variant<64, float>(p, variant, s);
     if (d == 128) return f16 ? launch_variant<128, _Float16>(p, variant, s) : launch_variant<128, float>(p, variant, s);

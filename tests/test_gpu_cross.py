@@ -182,3 +182,41 @@ def test_decode_kernel_reaches_eight_queries_for_fp32_at_d128():
         out = G.fwd_cross(q, k, v, 128 ** -0.5, causal=True)
         assert_parity(out, ref, tolerance(3000, fp16), "d128 nq=%d fp16=%d" % (nq, fp16))
         assert elsa.elsa_last_kernel().startswith("fma_decode") == decode
+        if decode:
+            assert elsa.elsa_last_kernel() == "fma_decode_q8"      # one block per (head, chunk): K and V read once
+
+
+def test_eight_query_decode_kernel_masks_and_chunks():
+    import torch
+    from paper_2604_23798_amd import elsa
+    d = 128
+    ws = torch.empty(32 << 20, dtype=torch.uint8, device="cuda")
+    for nq, nk in [(5, 1), (8, 64), (6, 777), (8, 4100), (13, 300), (8, 3)]:
+        B, H = 2, 3
+        q, k, v = _rect(B, H, nq, nk, d, 800 + nq + nk)
+        kv_len = np.array([nk, max(0, nk // 3)], np.int32)
+        for causal in (False, True):
+            for kl in (None, kv_len):
+                ref, ref_lse = _ref(q, k, v, d ** -0.5, causal=causal, kv_len=kl)
+                vis = np.isfinite(ref_lse)
+                for splits in (0, 3):
+                    if splits > nk:
+                        continue
+                    elsa.elsa_set_workspace(ws if splits else None)
+                    try:
+                        with G.Options(path=1, variant=5, splits=splits):
+                            out, lse = G.fwd_cross(q, k, v, d ** -0.5, causal=causal, kv_len=kl, want_lse=True)
+                            assert elsa.elsa_last_kernel() == "fma_decode_q8"
+                    finally:
+                        elsa.elsa_set_workspace(None)
+                    what = "decode q8 %dx%d c%d pad%d s%d" % (nq, nk, causal, kl is not None, splits)
+                    assert_parity(out, ref, tolerance(nk, False), what)
+                    assert np.all(out[~vis] == 0) and np.all(np.isneginf(lse[~vis])), what
+                    assert np.max(np.abs(lse[vis] - ref_lse[vis]), initial=0.0) < 2e-5, what
+    # other shapes do not have it
+    q, k, v = _rect(1, 1, 8, 64, 64, 5)
+    with G.Options(path=1, variant=5), pytest.raises(elsa.ElsaError):
+        G.fwd_cross(q, k, v, 0.125)
+    q, k, v = _rect(1, 1, 8, 64, 128, 5, fp16=True)
+    with G.Options(path=1, variant=5), pytest.raises(elsa.ElsaError):
+        G.fwd_cross(q, k, v, 0.1)

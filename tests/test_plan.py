@@ -75,7 +75,7 @@ def test_decoding_streams_the_cache_with_the_vector_kernel():
     assert plan(2, 40, 1, 32768, 128, causal=True) == ("fma_decode_q1", 1)
     assert plan(2, 40, 1, 32768, 128, causal=True, ws_mib=256) == ("fma_decode_q1", 16)   # five blocks per CU
     assert plan(2, 40, 4, 32768, 128, causal=True, dtype=1, ws_mib=256) == ("fma_decode_q4", 16)
-    assert plan(2, 40, 8, 32768, 128, ws_mib=256)[0] == "fma_decode_q4"                  # FP32, d = 128: up to eight
+    assert plan(2, 40, 8, 32768, 128, ws_mib=256)[0] == "fma_decode_q8"                  # FP32, d = 128: up to eight
     assert plan(2, 40, 8, 32768, 128, dtype=1, ws_mib=256)[0] == "mfma16_xwave"
     assert plan(2, 40, 16, 32768, 64, ws_mib=256)[0] == "mfma_xwave"
     assert plan(2, 40, 1, 32768, 256)[0] == "fma_decode_q1" and plan(2, 40, 3, 32768, 96)[0] == "fma_decode_q1"
