@@ -28,6 +28,9 @@
  *     Arguments are validated before anything is launched.
  *   - Results are deterministic: no atomics; two calls on the same inputs with
  *     the same options are bit-identical.
+ *   - Host threads.  Options, the lent workspace, the record of the last launch and the cache of
+ *     the last tile choice are process-wide and unguarded: calls from different host threads must
+ *     be serialised by the caller.  (Streams are the unit of concurrency on the device.)
  *   - Masks.  causal != 0: key j is visible to query i iff j <= i.  kv_len
  *     (device int32 [B], may be NULL): key j of batch b is visible iff
  *     j < kv_len[b]; values are clamped to [0, n]; query rows beyond kv_len are

@@ -72,6 +72,11 @@ int pick_variant(int path, long long BH, int n, int nk, int d, int splits, int c
 // waves 2.25.  Within about 10 % of the measured launch times on B*H = 8 .. 192, n = 197 .. 4096.
 struct TileChoice { int variant, splits; };
 TileChoice choose_small_fp32(long long BH, int n, int nk, int d, int causal, int max_splits) {
+    // the last question is usually asked again (a layer stack, a benchmark loop): remember its answer
+    struct Memo { long long BH; int n, nk, d, causal, max_splits; TileChoice choice; };
+    static Memo memo{-1, 0, 0, 0, 0, 0, {0, 0}};
+    if (memo.BH == BH && memo.n == n && memo.nk == nk && memo.d == d && memo.causal == causal && memo.max_splits == max_splits)
+        return memo.choice;
     // `uneven`: how far the busiest CU exceeds the mean when the blocks differ in length (causal mask)
     struct Shape { int variant, rows, key_waves, resident; double t1, t2, uneven; };
     static const Shape narrow[3] = {{7, 128, 1, 3, 2.25, 2.0, 1.3}, {11, 64, 2, 2, 2.4, 2.15, 1.1}, {3, 32, 4, 1, 2.25, 2.25, 1.3}};
@@ -113,6 +118,7 @@ TileChoice choose_small_fp32(long long BH, int n, int nk, int d, int causal, int
             if (t < best_t) { best_t = t; best = TileChoice{sh.variant, C}; }
         }
     }
+    memo = Memo{BH, n, nk, d, causal, max_splits, best};
     return best;
 }
 
@@ -362,7 +368,7 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     const bool fp32_tiles = !fp16_tiles && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 2);
     const bool window = n <= 96 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu;    // served by the LDS-free tile
     if (fp32_tiles && (d <= 64 || d == 128) && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= 4 * kNumCu &&
-        (long long)n * 8 > nk && n > 8 && !window) {
+        (long long)n * 8 > nk && n > 8 && n <= 16384 && !window) {
         int max_c = 1;
         if (g.ws) {
             max_c = 8;
