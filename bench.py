@@ -211,7 +211,10 @@ def main():
         flops = int(4 * H * d * np.sum(lens * lens))
         causal, kv_len = False, None
     else:
-        w = inputs.WORKLOADS[a.workload]
+        if a.workload not in inputs.WORKLOADS and a.workload.endswith("_fp16") and a.workload[:-5] in inputs.WORKLOADS:
+            w = inputs.WORKLOADS[a.workload[:-5]].with_(fp16=True, name=a.workload)     # any workload with FP16 I/O
+        else:
+            w = inputs.WORKLOADS[a.workload]
         q, k, v, kv_len = inputs.make(w)
         fp16, causal, scale, flops = w.fp16, w.causal, w.scale, w.flops
     # multiply-adds the kernels have to execute (visible keys only): what the roofline fraction is taken on
