@@ -106,3 +106,51 @@ def test_small_workloads_with_workspace_split():
         _check(inputs.sweep(2048), per_head=24)
     finally:
         elsa.elsa_set_workspace(None)
+
+
+@pytest.mark.parametrize("fp16", [False, True])
+def test_decode_against_32k_keys_with_the_workspace_the_benchmark_lends(fp16):
+    """The decode workload of bench.py (B 2, H 40, one query, 32768 keys, d 128, 16 key chunks + combine):
+    every row checked (a row is one (batch, head))."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    B, H, d, nq, nk = 2, 40, 128, 1, 32768
+    q = inputs.normal(1007, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
+    k = inputs.normal(1007, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
+    v = inputs.normal(1007, 2, 0, B * H * nk * d).reshape(B, H, nk, d)
+    if fp16:
+        q, k, v = (t.astype(np.float16) for t in (q, k, v))
+    scale = float(np.float32(d ** -0.5))
+    f32 = lambda t: t.astype(np.float32)
+    ref, ref_lse = oracle.cross_rows(f32(q), f32(k), f32(v), scale, causal=True)
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    elsa.elsa_set_workspace(ws)
+    try:
+        out, lse = G.fwd_cross(q, k, v, scale, causal=True, want_lse=True)
+        assert elsa.elsa_last_kernel() == "fma_decode_q1" and elsa.elsa_last_splits() == 16
+    finally:
+        elsa.elsa_set_workspace(None)
+    assert_parity(out, ref, tolerance(nk, fp16), "decode_32k fp16=%d" % fp16)
+    assert np.max(np.abs(lse - ref_lse)) < (5e-3 if fp16 else 2e-5)
+
+
+@pytest.mark.parametrize("name", ["dv_192_128_8192", "dv_192_128_8192_causal_fp16", "dv_64_128_16384", "dv_128_64_16384_fp16"])
+def test_value_width_workloads_of_the_benchmark(name):
+    """bench.py's dv_<d>_<d_v>_<n> workloads (B 1, H 16) on sampled rows: first and last rows, the
+    neighbours of a tile boundary, and evenly spaced ones."""
+    parts = name.split("_")
+    d, dv, n = int(parts[1]), int(parts[2]), int(parts[3])
+    fp16, causal = "fp16" in parts[4:], "causal" in parts[4:]
+    B, H = 1, 16
+    q = inputs.normal(1012, 0, 0, B * H * n * d).reshape(B, H, n, d)
+    k = inputs.normal(1012, 1, 0, B * H * n * d).reshape(B, H, n, d)
+    v = inputs.normal(1012, 2, 0, B * H * n * dv).reshape(B, H, n, dv)
+    if fp16:
+        q, k, v = (t.astype(np.float16) for t in (q, k, v))
+    scale = float(np.float32(d ** -0.5))
+    per_head = np.unique(np.concatenate([[0, 1, 127, 128, 129, n - 2, n - 1], np.linspace(0, n - 1, 25).astype(np.int64)]))
+    rows = (np.arange(B * H)[:, None] * n + per_head[None, :]).reshape(-1).astype(np.int64)
+    f32 = lambda t: t.astype(np.float32)
+    ref, _ = oracle.dv_rows(f32(q), f32(k), f32(v), scale, causal=causal, rows=rows)
+    out = G.fwd_dv(q, k, v, scale, causal=causal)[rows]
+    assert_parity(out, ref, tolerance(n, fp16), name)
