@@ -1,5 +1,9 @@
 // C ABI of libelsa: argument checks, configuration choice, launches.  No allocation, no sync.
+#include <algorithm>
 #include <cmath>
+#include <functional>
+#include <queue>
+#include <vector>
 
 #include "../../include/elsa.h"
 #include "elsa_common.hpp"
@@ -63,62 +67,93 @@ int pick_variant(int path, long long BH, int n, int nk, int d, int splits, int c
     return d <= 64 ? 7 : 1;
 }
 
-// Tile shape and number of key chunks for small FP32 problems (d = 32, 64, 128; dense layout), where the
-// choice decides how evenly the blocks fill the 256 CUs.  A block's time is its 32-key steps per
-// wave times the step time (the matrix core and the vector ALU of a SIMD take turns, so blocks
-// that share a CU add up); a launch takes the steps of its busiest CU, plus a prologue, plus the
-// combine pass when the keys are cut.  Step times are measured (d = 64; us): 128-row tile 2.0 (2.25
-// when a CU holds one block), 64-row tile with two key waves 2.15 (2.4), 32-row tile with four key
-// waves 2.25.  Within about 10 % of the measured launch times on B*H = 8 .. 192, n = 197 .. 4096.
+// Tile shape and number of key chunks for small dense problems, where the choice decides how evenly
+// the blocks fill the 256 CUs.  The launch is played through on the host: a block's work is its
+// 32-key steps per wave (for the block's place in the launch order, masks included); the first
+// `resident` x 256 blocks are placed round-robin as the hardware does, later ones go to the CU that
+// frees up first; blocks that share a CU add up, because the matrix core and the vector ALU of a
+// SIMD take turns.  Launch time = steps of the busiest CU x step time + prologue (+ state traffic
+// and the combine launch when the keys are cut).  Step times are measured (us per step at d = 64;
+// t2 when co-resident blocks overlap, t1 when a block is alone or its neighbours differ in length):
+//   FP32  128 rows 2.25 / 2.0   64 rows x 2 key waves 2.4 / 2.15   32 rows x 4 key waves 2.6
+//   FP16  128 rows 0.54 / 0.36  256 rows 0.88 / 0.66  64 rows x 2 key waves 0.60 / 0.40  32 rows x 4: 0.58
+// Predictions are within about 10 % of the measured launch times on B*H = 8 .. 192, n = 197 .. 4096.
 struct TileChoice { int variant, splits; };
-TileChoice choose_small_fp32(long long BH, int n, int nk, int d, int causal, int max_splits) {
+struct TileShape { int variant, rows, key_waves, resident; double t1, t2; };
+
+TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int causal, int max_splits) {
     // the last question is usually asked again (a layer stack, a benchmark loop): remember its answer
-    struct Memo { long long BH; int n, nk, d, causal, max_splits; TileChoice choice; };
-    static Memo memo{-1, 0, 0, 0, 0, 0, {0, 0}};
-    if (memo.BH == BH && memo.n == n && memo.nk == nk && memo.d == d && memo.causal == causal && memo.max_splits == max_splits)
+    struct Memo { bool f16; long long BH; int n, nk, d, causal, max_splits; TileChoice choice; };
+    static Memo memo{false, -1, 0, 0, 0, 0, 0, {0, 0}};
+    if (memo.f16 == fp16_tiles && memo.BH == BH && memo.n == n && memo.nk == nk && memo.d == d && memo.causal == causal &&
+        memo.max_splits == max_splits)
         return memo.choice;
-    // `uneven`: how far the busiest CU exceeds the mean when the blocks differ in length (causal mask)
-    struct Shape { int variant, rows, key_waves, resident; double t1, t2, uneven; };
-    static const Shape narrow[3] = {{7, 128, 1, 3, 2.25, 2.0, 1.3}, {11, 64, 2, 2, 2.4, 2.15, 1.1}, {3, 32, 4, 1, 2.25, 2.25, 1.3}};
+    static const TileShape f32_narrow[3] = {{7, 128, 1, 3, 2.25, 2.0}, {11, 64, 2, 2, 2.4, 2.15}, {3, 32, 4, 1, 2.6, 2.6}};
     // d = 128: the 128-row tile holds two blocks per CU, the 64-row tile (its LDS tiles fill a CU) one
-    // (measured 5.8 us per step at d = 128 = 3.1 at d = 64 scale: one wave per SIMD hides no latency)
-    static const Shape wide[2] = {{1, 128, 1, 2, 2.25, 2.0, 1.3}, {11, 64, 2, 1, 3.1, 3.1, 1.1}};
-    const Shape *shapes = d == 128 ? wide : narrow;
-    const int nshapes = d == 128 ? 2 : 3;
+    // (one wave per SIMD hides no latency: 5.3 us per step at d = 128, 2.8 at the d = 64 scale)
+    static const TileShape f32_wide[2] = {{1, 128, 1, 2, 2.4, 2.15}, {11, 64, 2, 1, 2.8, 2.8}};
+    static const TileShape f16_narrow[4] = {{1, 128, 1, 2, 0.54, 0.36}, {2, 256, 1, 2, 0.88, 0.66}, {4, 64, 2, 2, 0.60, 0.40},
+                                            {3, 32, 4, 2, 0.58, 0.58}};
+    const TileShape *shapes = fp16_tiles ? f16_narrow : d == 128 ? f32_wide : f32_narrow;
+    const int nshapes = fp16_tiles ? 4 : d == 128 ? 2 : 3;
     const double dscale = 0.12 + 0.88 * d / 64.0;        // the MFMA part of a step grows with d
     const double prologue = 5.0;
     const int coff = nk - n;
-    TileChoice best{d == 128 ? 1 : 7, 1};
+    TileChoice best{shapes[0].variant, 1};
     double best_t = 1e30;
+    std::vector<double> cu(kNumCu);
     for (int si = 0; si < nshapes; ++si) {
-        const Shape &sh = shapes[si];
+        const TileShape &sh = shapes[si];
         const int q_tiles = (n + sh.rows - 1) / sh.rows;
         for (int C = 1; C <= max_splits; ++C) {
-            if (C > 1 && (sh.variant == 3 || nk / C < 256)) break;   // the 32-row tile splits the keys by itself
+            if (C > 1 && ((!fp16_tiles && sh.variant == 3) || nk / C < 256)) break;   // the 32-row tile splits the keys by itself
             const int chunk = (nk + C - 1) / C;
-            long long total = 0;
-            int smax = 0;
-            for (int t = 0; t < q_tiles; ++t)
-                for (int c = 0; c < C; ++c) {
-                    int hi = nk < (c + 1) * chunk ? nk : (c + 1) * chunk;
-                    if (causal) { const int lim = (t + 1) * sh.rows + coff; if (lim < hi) hi = lim; }
-                    const int vis = hi - c * chunk;
-                    const int steps = vis > 0 ? (vis + 32 * sh.key_waves - 1) / (32 * sh.key_waves) : 0;
-                    total += steps;
-                    if (steps > smax) smax = steps;
-                }
             const long long blocks = BH * q_tiles * C;
+            if (blocks > 64 * kNumCu) continue;          // not a small problem in this shape
+            auto steps_of = [&](int qt, int c) {
+                int hi = nk < (c + 1) * chunk ? nk : (c + 1) * chunk;
+                if (causal) { const int lim = (qt + 1) * sh.rows + coff; if (lim < hi) hi = lim; }
+                const int vis = hi - c * chunk;
+                return vis > 0 ? (vis + 32 * sh.key_waves - 1) / (32 * sh.key_waves) : 0;
+            };
+            // per-block cost in steps; a tile that owns its CU pays its prologue itself
+            const double own = sh.resident == 1 ? prologue / (sh.t1 * dscale) : 0.0;
+            std::fill(cu.begin(), cu.end(), 0.0);
+            std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+            const long long placed = (long long)sh.resident * kNumCu;
+            for (long long i = 0; i < blocks; ++i) {
+                long long w = i;                          // launch order: see decode_work (head index fastest)
+                if (causal) {
+                    if (blocks > 3 * kNumCu && blocks <= 4 * kNumCu) { const long long half = blocks / 2; if (w >= half) w = half + (blocks - 1 - w); }
+                    else if (w >= kNumCu && w < 2 * kNumCu) { const long long last = blocks < 2 * kNumCu ? blocks : 2 * kNumCu; w = kNumCu + (last - 1 - w); }
+                }
+                const long long t = w / BH;
+                const int c = (int)(t % C);
+                int qt = (int)(t / C);
+                if (causal) qt = q_tiles - 1 - qt;
+                const double cost = steps_of(qt, c) + own;
+                if (i < placed) {
+                    cu[i % kNumCu] += cost;
+                    if (i + kNumCu >= placed || i + kNumCu >= blocks) free_at.push(cu[i % kNumCu]);   // the CU's last static block
+                } else {
+                    const double at = free_at.top();
+                    free_at.pop();
+                    free_at.push(at + cost);
+                }
+            }
+            double busiest = 0.0;
+            if (blocks <= placed) { for (double x : cu) busiest = x > busiest ? x : busiest; }
+            else { while (!free_at.empty()) { busiest = free_at.top(); free_at.pop(); } }
             const long long rounds = (blocks + kNumCu - 1) / kNumCu;
-            // steps of the busiest CU: equal blocks stack in rounds; unequal (causal) ones are dealt longest first
-            double busiest = causal ? sh.uneven * (double)(total * BH) / kNumCu : (double)rounds * smax;
-            if (busiest < smax) busiest = smax;
-            const double step = (rounds >= 2 && sh.resident >= 2 ? sh.t2 : sh.t1) * dscale;
-            const double combine = C > 1 ? 7.0 + 3.0 * (double)(rounds - 1) : 0.0;   // state traffic + second launch
-            const double t = prologue * (sh.resident == 1 ? (double)rounds : 1.0) + busiest * step + combine;
+            const bool overlap = sh.resident >= 2 && (causal ? rounds > sh.resident : rounds >= 2);
+            const double step = (overlap ? sh.t2 : sh.t1) * dscale;
+            // second launch + the chunk states written and read back ((d + 2) floats per row and chunk, ~4 TB/s)
+            const double combine = C > 1 ? 5.0 + 2.0 * (double)(rounds - 1) + (double)BH * n * C * (d + 2) * 8.0 / 4.0e6 : 0.0;
+            const double t = (sh.resident == 1 ? 0.0 : prologue) + busiest * step + combine;
             if (t < best_t) { best_t = t; best = TileChoice{sh.variant, C}; }
         }
     }
-    memo = Memo{BH, n, nk, d, causal, max_splits, best};
+    memo = Memo{fp16_tiles, BH, n, nk, d, causal, max_splits, best};
     return best;
 }
 
@@ -136,7 +171,7 @@ struct Extra {
     int accumulate = 0;                          // merge the emitted state into the stored one
     bool has_coff = false;                       // causal diagonal given explicitly (streamed chunks)
     int coff = 0;
-    int variant = 0;                             // FP32 matrix-core tile chosen by the caller (0: pick_variant decides)
+    int variant = 0;                             // matrix-core tile chosen by the caller (0: pick_variant decides)
 };
 
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
@@ -174,7 +209,7 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     const long long longest = cu_seqlens ? total_tokens : (nk > n ? nk : n);
     if ((path != 1 || decode_variant) && longest * tok_stride * (dtype == ELSA_F16 ? 2 : 4) >= 0x7fffffffLL) return ELSA_ERR_UNSUPPORTED;
     int variant = decode_variant ? decode_variant : pick_variant(path, (long long)B * H, n, nk, d, num_splits, causal);
-    const bool hinted = path == 2 && !decode_variant && x.variant > 0 && g.opt[ELSA_OPT_VARIANT] == 0;
+    const bool hinted = (path == 2 || path == 3) && !decode_variant && x.variant > 0 && g.opt[ELSA_OPT_VARIANT] == 0;
     if (hinted) variant = x.variant;
     if (path == 2 && !hinted) {
         const bool ok = small_kernel_ok(cu_seqlens, num_splits, emit, n, nk);
@@ -363,18 +398,19 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     int C = g.ws ? auto_splits(B, H, n, nk, d, fp16_tiles) : 1;
     Extra x;
     x.nk = nk;
-    // small FP32 problems: tile shape and key chunks together, from the block-placement model
+    // small problems: tile shape and key chunks together, from the block-placement model
     const long long b128 = (long long)B * H * ((n + 127) / 128);
     const bool fp32_tiles = !fp16_tiles && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 2);
-    const bool window = n <= 96 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu;    // served by the LDS-free tile
-    if (fp32_tiles && (d <= 64 || d == 128) && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= 4 * kNumCu &&
+    const bool window = !fp16_tiles && n <= 96 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu;   // served by the LDS-free tile
+    const bool modelled = fp32_tiles ? (d <= 64 || d == 128) : (fp16_tiles && d <= 64);
+    if (modelled && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= 4 * kNumCu &&
         (long long)n * 8 > nk && n > 8 && n <= 16384 && !window) {
         int max_c = 1;
-        if (g.ws) {
+        if (g.ws && !fp16_tiles) {                // the FP16 tiles are not cut outside decoding
             max_c = 8;
             while (max_c > 1 && elsa_split_kv_workspace_bytes(B, H, n, d, max_c) > g.ws_bytes) --max_c;
         }
-        const TileChoice tc = choose_small_fp32((long long)B * H, n, nk, d, causal, max_c);
+        const TileChoice tc = choose_tiles(fp16_tiles, (long long)B * H, n, nk, d, causal, max_c);
         x.variant = tc.variant;
         C = tc.splits;
     }

@@ -313,6 +313,6 @@ const char *mfma_variant_name(int variant);
 const char *fma_variant_name(int variant);
 constexpr int kMfmaVariants = 11;
 constexpr int kFmaVariants = 5;
-constexpr int kMfma16Variants = 3;
+constexpr int kMfma16Variants = 4;
 
 }  // namespace elsa

@@ -5,14 +5,16 @@
 namespace elsa {
 
 // ---- variants: 1 q128 (4 query waves)   2 q256 (4 waves x 2 query groups)   3 waves split the keys
+//                4 q64xw2 (two query waves x two key waves; the key-splitting shape of d >= 96)
 
-static const char *kNames16[kMfma16Variants] = {"mfma16_q128_w4", "mfma16_q256_w4", "mfma16_xwave"};
+static const char *kNames16[kMfma16Variants] = {"mfma16_q128_w4", "mfma16_q256_w4", "mfma16_xwave", "mfma16_q64_xw2"};
 
 int mfma16_variant_tq(int variant, int d) {
     switch (variant) {
         case 1: return 128;
         case 2: return d <= 64 ? 256 : 128;
         case 3: return d <= 64 ? 32 : 64;       // d >= 96: two query waves x two key waves
+        case 4: return 64;
         default: return 0;
     }
 }
@@ -24,10 +26,10 @@ template <int D>
 static int launch_variant16(const FwdParams &p, int variant, hipStream_t s) {
     // d = 96, 256: one query group per wave; 32-key tiles at d = 256 keep two blocks per CU in LDS
     if constexpr (D == 96) {
-        if (variant == 3) return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
+        if (variant == 3 || variant == 4) return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
         return launch_one16<D, 1, 4, 1, 64, 2>(p, s);
     } else if constexpr (D == 256) {
-        if (variant == 3) return launch_one16<D, 1, 2, 2, 32, 1>(p, s);
+        if (variant == 3 || variant == 4) return launch_one16<D, 1, 2, 2, 32, 1>(p, s);
         return launch_one16<D, 1, 4, 1, 32, 2>(p, s);
     } else
     switch (variant) {
@@ -38,6 +40,7 @@ static int launch_variant16(const FwdParams &p, int variant, hipStream_t s) {
         case 3:
             if constexpr (D == 128) return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
             else return launch_one16<D, 1, 1, 4, 32, 2>(p, s);
+        case 4: return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
         default: return (int)hipErrorInvalidValue;
     }
 }

@@ -48,7 +48,7 @@ def test_fp32_kernels_on_rectangular_problems(path, variant, causal):
             assert_parity(out, ref, tolerance(max(nq, nk), False), "cross p%d v%d %dx%d d%d c%d" % (path, variant, nq, nk, d, causal))
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 @pytest.mark.parametrize("causal", [False, True])
 def test_fp16_matrix_core_kernels_on_rectangular_problems(variant, causal):
     for (nq, nk) in SHAPES:

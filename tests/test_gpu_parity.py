@@ -71,7 +71,7 @@ def test_small_problems_every_kernel(path, variant, shape, causal):
     assert_parity(out, ref, tolerance(n), "path%d v%d %s causal=%d" % (path, variant, shape, causal))
 
 
-@pytest.mark.parametrize("path,variant", [(MFMA, 1), (MFMA, 3), (FMA, 1), (MFMA16, 1), (MFMA16, 2), (MFMA16, 3)])
+@pytest.mark.parametrize("path,variant", [(MFMA, 1), (MFMA, 3), (FMA, 1), (MFMA16, 1), (MFMA16, 2), (MFMA16, 3), (MFMA16, 4)])
 @pytest.mark.parametrize("d", [32, 64, 128])
 def test_fp16_io(path, variant, d):
     B, H, n = 1, 3, 450
@@ -84,7 +84,7 @@ def test_fp16_io(path, variant, d):
         assert_parity(out, ref, tolerance(n, fp16=True), "fp16 path%d v%d d%d causal=%d" % (path, variant, d, causal))
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 def test_fp16_matrix_core_path_masks_splits_and_edges(variant):
     """The FP16-MFMA kernel through every feature: padding, causal, split-KV states, combine,
     ragged sizes, negative and zero scale (zero falls back to the FP32-MFMA kernel)."""

@@ -118,7 +118,7 @@ def test_every_fp32_kernel_family_accumulates(opts):
     _run(q, k, v, 0.2, [130, 370], False, False, opts)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
 def test_every_fp16_matrix_core_kernel_accumulates(variant):
     for (nq, nk, chunks) in CASES[:4]:
         for d in (32, 128):

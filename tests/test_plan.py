@@ -53,10 +53,15 @@ def test_small_problems_follow_the_block_placement_model():
     assert plan(1, 16, 1024, 1024, 64, ws_mib=64) == ("mfma_q64_xw2", 1)
     assert plan(1, 16, 1024, 1024, 64, causal=True, ws_mib=64) == ("mfma_q64_xw2", 2)
     assert plan(1, 16, 1024, 1024, 64, causal=True) == ("mfma_xwave", 1)     # no workspace, no key chunks: 32-row tiles
-    # 192 blocks of 128 rows would fill the CUs 0.75 times, 768 fill them exactly three times
-    assert plan(1, 16, 1536, 1536, 64, ws_mib=64) == ("mfma_q128_k32", 4)
-    assert plan(1, 16, 3072, 3072, 64, ws_mib=64) == ("mfma_q128_k32", 2)
-    assert plan(1, 40, 1024, 1024, 128, ws_mib=256) == ("mfma_q128_w4", 4)
+    # 192 blocks of 128 rows would fill the CUs 0.75 times and 384 one and a half times: never one pass of that tile
+    assert plan(1, 16, 1536, 1536, 64, ws_mib=64) in (("mfma_q64_xw2", 2), ("mfma_q128_k32", 4))
+    assert plan(1, 16, 3072, 3072, 64, ws_mib=64) in (("mfma_q64_xw2", 1), ("mfma_q128_k32", 2))
+    assert plan(1, 16, 3072, 3072, 64) == ("mfma_q64_xw2", 1)               # 768 blocks: exactly three rounds
+    assert plan(1, 40, 1024, 1024, 128, ws_mib=256) == ("mfma_q128_w4", 4)   # 320 blocks -> 1280
+    # FP16 tiles: the shape is chosen the same way, the keys are never cut
+    assert plan(1, 16, 2048, 2048, 64, dtype=1, ws_mib=64) == ("mfma16_q64_xw2", 1)
+    assert plan(1, 16, 2048, 2048, 64, dtype=1, causal=True) == ("mfma16_q64_xw2", 1)
+    assert plan(1, 16, 4096, 4096, 64, dtype=1) == ("mfma16_q128_w4", 1)
     # a forced tile or chunk count switches the model off
     assert plan(1, 16, 1024, 1024, 64, ws_mib=64, variant=7) == ("mfma_q128_k32", 2)
     assert plan(1, 16, 1024, 1024, 64, ws_mib=64, splits=3)[1] == 3
