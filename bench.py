@@ -117,6 +117,66 @@ def scaling_fit(a):
     return res
 
 
+def tile_sweep(a):
+    """Small dense problems: the library's own choice of tile shape and key chunks against forced
+    configurations, each timed in this process (microseconds per launch, 256 MiB workspace lent).
+    One JSON object: per shape the default's kernel / chunks / time, every forced time, and the
+    ratio default / best forced."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
+    elsa.elsa_set_workspace(ws)
+
+    def run(B, H, n, d, causal, fp16, path, variant, splits):
+        dt = torch.float16 if fp16 else torch.float32
+        gen = torch.Generator(device="cuda").manual_seed(1300 + n + d)
+        q, k, v = (torch.randn(B, H, n, d, device="cuda", dtype=torch.float32, generator=gen).to(dt) for _ in range(3))
+        out = torch.empty_like(q)
+        for o, val in ((elsa.OPT_PATH, path), (elsa.OPT_VARIANT, variant), (elsa.OPT_SPLITS, splits)):
+            elsa.elsa_set_option(o, val)
+        f = lambda: elsa.elsa_attn_fwd(q, k, v, out, d ** -0.5, causal)
+        for _ in range(max(a.warmup, 100)):
+            f()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(max(a.steps, 200)):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        for o in (elsa.OPT_PATH, elsa.OPT_VARIANT, elsa.OPT_SPLITS):
+            elsa.elsa_set_option(o, 0)
+        return e0.elapsed_time(e1) / max(a.steps, 200) * 1e3, elsa.elsa_last_kernel(), elsa.elsa_last_splits()
+
+    f32_narrow = [(2, 7, 1), (2, 7, 2), (2, 7, 4), (2, 11, 1), (2, 11, 2), (2, 3, 1)]
+    f32_wide = [(2, 1, 1), (2, 1, 2), (2, 1, 4), (2, 11, 1), (2, 11, 2)]
+    f16 = [(3, 1, 1), (3, 2, 1), (3, 3, 1), (3, 4, 1)]
+    shapes = [(1, 16, n, 64, False) for n in (256, 512, 768, 1024, 1536, 2048, 3072)] + \
+             [(B, 12, 197, 64, False) for B in (1, 4, 8, 16)] + [(1, 32, 1024, 32, False), (1, 8, 2048, 64, False), (1, 8, 4096, 64, False)] + \
+             [(1, 40, n, 128, False) for n in (256, 512, 1024, 2048)] + [(1, 16, 1024, 128, False), (1, 32, 1536, 128, False)] + \
+             [(1, 16, n, 64, True) for n in (1024, 2048, 3072, 4096, 8192)] + [(4, 12, 197, 64, True), (1, 8, 4096, 64, True)]
+    rows = []
+    for (B, H, n, d, fp16) in shapes:
+        forced = f16 if fp16 else (f32_wide if d == 128 else f32_narrow)
+        for causal in (False, True):
+            us, kern, C = run(B, H, n, d, causal, fp16, 0, 0, 0)
+            alts = {}
+            for (path, variant, splits) in forced:
+                if splits > 1 and n // splits < 256:
+                    continue
+                t, name, _ = run(B, H, n, d, causal, fp16, path, variant, splits)
+                alts["%s x%d" % (name, splits)] = round(t, 1)
+            best = min(alts.values())
+            rows.append({"B": B, "H": H, "n": n, "d": d, "causal": causal, "fp16": fp16, "default_us": round(us, 1),
+                         "default": "%s x%d" % (kern, C), "forced_us": alts, "default_over_best": round(us / best, 3)})
+            print("tile-sweep B%d H%d n%d d%d causal=%d fp16=%d: %s %.1f us, best forced %.1f" %
+                  (B, H, n, d, causal, fp16, rows[-1]["default"], us, best), file=sys.stderr, flush=True)
+    elsa.elsa_set_workspace(None)
+    r = [x["default_over_best"] for x in rows]
+    return {"metric": "library default / best forced configuration (time per launch)", "n_gpus": 1, "cases": len(rows),
+            "mean": sum(r) / len(r), "max": max(r), "rows": rows}
+
+
 def fit_scaling_law(ns, ts, block=128):
     """Least-squares fit of T(n) = a*L(n,B) + b*n^2 + c (the paper's scaling model, L from Eq. 5)
     to latencies ``ts`` at lengths ``ns``.  Returns n, L, a, b, c and R^2."""
@@ -155,6 +215,8 @@ def main():
     ap.add_argument("--scaling-fit", action="store_true",
                     help="instead of one workload: per-head latency for n = 2^10..2^15 (H=16, d=64) and the "
                          "least-squares fit T(n) = a*L(n,128) + b*n^2 + c of the paper's scaling study")
+    ap.add_argument("--tile-sweep", action="store_true",
+                    help="small problems: the library's tile / chunk choice against forced configurations (about a minute)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -171,6 +233,9 @@ def main():
     torch.cuda.set_device(0)
     if a.scaling_fit:
         print(json.dumps(scaling_fit(a)))
+        return
+    if a.tile_sweep:
+        print(json.dumps(tile_sweep(a)))
         return
     varlen = a.workload.startswith("varlen_8x1792")
     decode = a.workload.startswith("decode_32k")
