@@ -53,6 +53,8 @@ int variant_tq(int path, int variant, int d) {
 int pick_variant(int path, long long BH, int n, int nk, int d, int splits, int causal) {
     if (g.opt[ELSA_OPT_VARIANT] >= 1 && g.opt[ELSA_OPT_VARIANT] <= variant_count(path)) return g.opt[ELSA_OPT_VARIANT];
     // one query tile against a long key range: the waves of a block split the keys, not the queries
+    // (FP32, d = 128, up to 32 queries: four key waves on a single-buffered 128-key tile, so that no wave idles)
+    if (path == 2 && d == 128 && (long long)n * 8 <= nk && n <= 32) return 12;
     if (path != 1 && (long long)n * 8 <= nk && n <= variant_tq(path, 3, d)) return 3;
     if (path == 1) {
         const long long blocks = BH * ((n + 255) / 256) * splits;

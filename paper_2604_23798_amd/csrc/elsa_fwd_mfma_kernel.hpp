@@ -49,8 +49,11 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     static_assert(KS % 32 == 0, "a wave consumes keys 32 at a time");
 
     extern __shared__ __align__(16) float smem[];
-    float *Ks = smem;                       // [2][KBUF]
-    float *Vs = smem + 2 * KBUF;            // [2][VBUF]
+    // BUFL = 2: one LDS buffer instead of two, for tiles too large to double (the next tile waits in
+    // registers while the current one is consumed; two barriers per tile instead of one)
+    constexpr int NBUF = BUFL == 2 ? 1 : 2;
+    float *Ks = smem;                       // [NBUF][KBUF]
+    float *Vs = smem + NBUF * KBUF;         // [NBUF][VBUF]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -203,7 +206,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     // first key that no lane of this wave can see
     const int wave_lim = p.causal ? min(kend, wrow0 + NQ * 32 + coff) : kend;
     for (int t = 0; t < ntiles; ++t) {
-        const int buf = t & 1;
+        const int buf = NBUF == 2 ? (t & 1) : 0;
         if (t + 1 < ntiles) gload(t + 1);
         const float *Kb = Ks + buf * KBUF;
         const float *Vb = Vs + buf * VBUF;
@@ -344,7 +347,10 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                 }
             }
         }
-        if (t + 1 < ntiles) lstore(buf ^ 1);
+        if (t + 1 < ntiles) {
+            if constexpr (NBUF == 1) __syncthreads();   // every wave is done reading the only buffer
+            lstore(NBUF == 2 ? (buf ^ 1) : 0);
+        }
         __syncthreads();
     }
 
@@ -469,7 +475,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int BUFL, int DV = D>
 static int launch_one(const FwdParams &p, hipStream_t s) {
     constexpr int TKB = KS * WK;
-    constexpr size_t kv_bytes = (size_t)2 * (TKB * (D + 4) + TKB * DV) * sizeof(float);
+    constexpr size_t kv_bytes = (size_t)(BUFL == 2 ? 1 : 2) * (TKB * (D + 4) + TKB * DV) * sizeof(float);
     constexpr size_t xw_bytes = WK > 1 ? (size_t)(WK / 2) * WQ * NQ * (2 + DV / 2) * 64 * sizeof(float) : 0;
     constexpr size_t smem = kv_bytes > xw_bytes ? kv_bytes : xw_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");

@@ -220,3 +220,40 @@ def test_eight_query_decode_kernel_masks_and_chunks():
     q, k, v = _rect(1, 1, 8, 64, 128, 5, fp16=True)
     with G.Options(path=1, variant=5), pytest.raises(elsa.ElsaError):
         G.fwd_cross(q, k, v, 0.1)
+
+
+@pytest.mark.parametrize("fp16", [False, True])
+def test_single_buffered_key_splitting_tile_at_d128(fp16):
+    """mfma_xwave32: 32 query rows, four key waves on one 128-key LDS tile that is not doubled (the next
+    tile waits in registers): key ranges of one and of many tiles, masks, chunks, more than one query tile."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    d = 128
+    ws = torch.empty(32 << 20, dtype=torch.uint8, device="cuda")
+    for nq, nk in [(9, 100), (16, 128), (32, 129), (20, 1000), (32, 4100), (70, 300), (5, 3)]:
+        q, k, v = _rect(2, 3, nq, nk, d, 900 + nq + nk, fp16=fp16)
+        kv_len = np.array([nk, max(0, nk // 3)], np.int32)
+        for causal in (False, True):
+            for kl in (None, kv_len):
+                ref, ref_lse = _ref(q, k, v, d ** -0.5, causal=causal, kv_len=kl)
+                vis = np.isfinite(ref_lse)
+                for splits in (0, 3):
+                    if splits > nk:
+                        continue
+                    elsa.elsa_set_workspace(ws if splits else None)
+                    try:
+                        with G.Options(path=2, variant=12, splits=splits):
+                            out, lse = G.fwd_cross(q, k, v, d ** -0.5, causal=causal, kv_len=kl, want_lse=True)
+                            assert elsa.elsa_last_kernel() == "mfma_xwave32"
+                    finally:
+                        elsa.elsa_set_workspace(None)
+                    what = "xwave32 %dx%d c%d pad%d s%d fp16=%d" % (nq, nk, causal, kl is not None, splits, fp16)
+                    assert_parity(out, ref, tolerance(nk, fp16), what)
+                    assert np.all(out[~vis] == 0) and np.all(np.isneginf(lse[~vis])), what
+    # the default for 9 .. 32 FP32 queries against a long cache at d = 128; other head dimensions do not have it
+    q, k, v = _rect(1, 4, 16, 3000, d, 950)
+    G.fwd_cross(q, k, v, d ** -0.5, causal=True)
+    assert elsa.elsa_last_kernel() == "mfma_xwave32"
+    q, k, v = _rect(1, 1, 16, 64, 64, 5)
+    with G.Options(path=2, variant=12), pytest.raises(elsa.ElsaError):
+        G.fwd_cross(q, k, v, 0.125)

@@ -83,6 +83,7 @@ def test_decoding_streams_the_cache_with_the_vector_kernel():
     assert plan(2, 40, 8, 32768, 128, ws_mib=256)[0] == "fma_decode_q8"                  # FP32, d = 128: up to eight
     assert plan(2, 40, 8, 32768, 128, dtype=1, ws_mib=256)[0] == "mfma16_xwave"
     assert plan(2, 40, 16, 32768, 64, ws_mib=256)[0] == "mfma_xwave"
+    assert plan(2, 40, 16, 32768, 128, ws_mib=256)[0] == "mfma_xwave32" and plan(2, 40, 40, 32768, 128, ws_mib=256)[0] == "mfma_xwave"
     assert plan(2, 40, 1, 32768, 256)[0] == "fma_decode_q1" and plan(2, 40, 3, 32768, 96)[0] == "fma_decode_q1"
     name, C = plan(1, 1, 1, 1 << 20, 64, ws_mib=256)
     assert name == "fma_decode_q1" and C == 64                                            # at most 64 chunks
