@@ -2,8 +2,6 @@
 #include <algorithm>
 #include <cmath>
 #include <functional>
-#include <queue>
-#include <vector>
 
 #include "../../include/elsa.h"
 #include "elsa_common.hpp"
@@ -103,7 +101,8 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
     const int coff = nk - n;
     TileChoice best{shapes[0].variant, 1};
     double best_t = 1e30;
-    std::vector<double> cu(kNumCu);
+    double cu[kNumCu];                       // work placed on each CU (steps)
+    double free_at[kNumCu];                  // min-heap: when a CU takes its next block (no host allocation)
     for (int si = 0; si < nshapes; ++si) {
         const TileShape &sh = shapes[si];
         const int q_tiles = (n + sh.rows - 1) / sh.rows;
@@ -120,8 +119,8 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
             };
             // per-block cost in steps; a tile that owns its CU pays its prologue itself
             const double own = sh.resident == 1 ? prologue / (sh.t1 * dscale) : 0.0;
-            std::fill(cu.begin(), cu.end(), 0.0);
-            std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+            std::fill(cu, cu + kNumCu, 0.0);
+            int heap_n = 0;
             const long long placed = (long long)sh.resident * kNumCu;
             for (long long i = 0; i < blocks; ++i) {
                 long long w = i;                          // launch order: see decode_work (head index fastest)
@@ -136,16 +135,19 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
                 const double cost = steps_of(qt, c) + own;
                 if (i < placed) {
                     cu[i % kNumCu] += cost;
-                    if (i + kNumCu >= placed || i + kNumCu >= blocks) free_at.push(cu[i % kNumCu]);   // the CU's last static block
+                    if (i + kNumCu >= placed || i + kNumCu >= blocks) {   // the CU's last static block
+                        free_at[heap_n++] = cu[i % kNumCu];
+                        std::push_heap(free_at, free_at + heap_n, std::greater<double>());
+                    }
                 } else {
-                    const double at = free_at.top();
-                    free_at.pop();
-                    free_at.push(at + cost);
+                    std::pop_heap(free_at, free_at + heap_n, std::greater<double>());   // earliest CU to the back
+                    free_at[heap_n - 1] += cost;
+                    std::push_heap(free_at, free_at + heap_n, std::greater<double>());
                 }
             }
             double busiest = 0.0;
-            if (blocks <= placed) { for (double x : cu) busiest = x > busiest ? x : busiest; }
-            else { while (!free_at.empty()) { busiest = free_at.top(); free_at.pop(); } }
+            if (blocks <= placed) busiest = *std::max_element(cu, cu + kNumCu);
+            else busiest = *std::max_element(free_at, free_at + heap_n);
             const long long rounds = (blocks + kNumCu - 1) / kNumCu;
             const bool overlap = sh.resident >= 2 && (causal ? rounds > sh.resident : rounds >= 2);
             const double step = (overlap ? sh.t2 : sh.t1) * dscale;
