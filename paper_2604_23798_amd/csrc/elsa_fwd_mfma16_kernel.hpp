@@ -204,12 +204,18 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
             for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sacc[nq][i] = 0.f;
+            // every K fragment of the step is requested before the first MFMA: the reads then overlap
+            // the MFMA chain instead of being waited for one by one
+            f16x8 kf[KC];
 #pragma unroll
-            for (int cc = 0; cc < KC; ++cc) {
-                const f16x8 kf = *reinterpret_cast<const f16x8 *>(Kb + (kl + j) * KROWB + 32 * cc + 16 * h);
+            for (int cc = 0; cc < KC; ++cc)
+                kf[cc] = *reinterpret_cast<const f16x8 *>(Kb + (kl + j) * KROWB + 32 * cc + 16 * h);
 #pragma unroll
-                for (int nq = 0; nq < NQ; ++nq) sacc[nq] = mfma16(kf, qf[nq][cc], sacc[nq]);
-            }
+            for (int cc = 0; cc < KC; ++cc)
+#pragma unroll
+                for (int nq = 0; nq < NQ; ++nq) sacc[nq] = mfma16(kf[cc], qf[nq][cc], sacc[nq]);
+            __builtin_amdgcn_sched_group_barrier(0x100, KC, 0);          // KC LDS reads
+            __builtin_amdgcn_sched_group_barrier(0x008, KC * NQ, 0);     // then the MFMAs
 
             // ---- (a2) masks
             const bool need_mask = (kg + 32 > kend) || (p.causal && kg + 31 > wrow0 + coff);
