@@ -21,9 +21,10 @@
  *     as operands of the PV product.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     only enqueue work on it; they never synchronise and never allocate.
- *     The first launch of a tile configuration raises that kernel's dynamic-LDS limit with
- *     hipFuncSetAttribute, which a stream capture does not record: call an entry point once
- *     with the shapes of interest before capturing it into a HIP graph.
+ *     The first launch of a tile configuration on a device raises that kernel's dynamic-LDS limit
+ *     with hipFuncSetAttribute (once per kernel and device), which a stream capture does not
+ *     record: call an entry point once with the shapes of interest before capturing it into a HIP
+ *     graph.  Work goes to the device that is current when the entry point is called.
  *   - Return ELSA_OK or an error code; nothing aborts, throws or prints.
  *     Arguments are validated before anything is launched.
  *   - Results are deterministic: no atomics; two calls on the same inputs with

@@ -293,6 +293,20 @@ template <> struct Io<_Float16> {
     }
 };
 
+// Raises a kernel's dynamic-LDS limit once per device (the attribute belongs to the device's copy of the
+// code object).  `done` is one flag array per kernel instantiation; setting it twice is harmless.
+constexpr int kMaxDevices = 64;
+template <typename Kern>
+inline hipError_t allow_dynamic_lds(Kern kern, size_t bytes, bool (&done)[kMaxDevices]) {
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev >= 0 && dev < kMaxDevices && done[dev]) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+    if (e == hipSuccess && dev >= 0 && dev < kMaxDevices) done[dev] = true;
+    return e;
+}
+
 // Launchers implemented in the kernel translation units.  Each returns a hipError_t as int.
 int launch_fwd_mfma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name);
 int launch_fwd_fma(const FwdParams &p, int d, int f16, int variant, hipStream_t s, const char **name);

@@ -170,12 +170,9 @@ template <int D, typename T, int WQ, int WK, int WPE>
 static int launch_one(const FwdParams &p, hipStream_t s) {
     constexpr size_t smem = WK > 1 ? (size_t)(WK / 2) * WQ * (D + 2) * 64 * sizeof(float) : 0;
     auto kern = fwd_fma_kernel<D, T, WQ, WK, WPE>;
-    static bool attr_done = false;
-    if (!attr_done && smem > 0) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return (int)e;
-        attr_done = true;
+    static bool attr_done[kMaxDevices] = {};   // per instantiation and device
+    if (smem > 0) {
+        if (hipError_t e = allow_dynamic_lds(kern, smem, attr_done); e != hipSuccess) return (int)e;
     }
     const long long total = p.cu_seqlens ? (long long)p.var_tiles * p.H : (long long)p.q_tiles * p.B * p.H * p.num_splits;
     long long blocks = total;

@@ -480,13 +480,8 @@ static int launch_one(const FwdParams &p, hipStream_t s) {
     constexpr size_t smem = kv_bytes > xw_bytes ? kv_bytes : xw_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");
     auto kern = fwd_mfma_kernel<D, T, NQ, WQ, WK, KS, WPE, NACC, BUFL, DV>;
-    static bool attr_done = false;          // per instantiation; idempotent, so a race is harmless
-    if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
-        if (e != hipSuccess) return (int)e;
-        attr_done = true;
-    }
+    static bool attr_done[kMaxDevices] = {};   // per instantiation and device
+    if (hipError_t e = allow_dynamic_lds(kern, smem, attr_done); e != hipSuccess) return (int)e;
     const long long total = p.cu_seqlens ? (long long)p.var_tiles * p.H : (long long)p.q_tiles * p.B * p.H * p.num_splits;
     long long blocks = total;
     if (p.xcd_map == 2 && !p.cu_seqlens) blocks = (total + kNumXcd - 1) / kNumXcd * kNumXcd;
