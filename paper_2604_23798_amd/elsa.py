@@ -73,10 +73,20 @@ def _ptr(t):
     return None if t is None else ctypes.c_void_p(t.data_ptr())
 
 
-def _stream(stream):
+_raw_stream = None      # torch's fast accessor of the current raw stream, looked up once
+
+
+def _stream(stream, like=None):
+    """hipStream_t of ``stream`` (a torch stream), or of torch's current stream on the device of ``like``."""
+    global _raw_stream
+    if stream is not None:
+        return ctypes.c_void_p(stream.cuda_stream)
     import torch
-    s = torch.cuda.current_stream() if stream is None else stream
-    return ctypes.c_void_p(s.cuda_stream)
+    if _raw_stream is None:
+        _raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", False)
+    if _raw_stream and like is not None:
+        return ctypes.c_void_p(_raw_stream(like.device.index))
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
 def _dtype_code(t):
@@ -99,7 +109,7 @@ def elsa_attn_fwd(q, k, v, out, scale, causal=False, stream=None):
     B, H, n, d = _shape(q, k, v)
     assert out.is_contiguous() and out.shape == q.shape and out.dtype == q.dtype
     _check(_lib.elsa_attn_fwd(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, n, d, float(scale), int(bool(causal)),
-                              _dtype_code(q), _stream(stream)))
+                              _dtype_code(q), _stream(stream, q)))
     return out
 
 
@@ -110,7 +120,7 @@ def elsa_attn_fwd_masked(q, k, v, out, scale, causal=False, kv_len=None, stream=
     if kv_len is not None:
         assert kv_len.is_cuda and kv_len.dtype == torch.int32 and kv_len.shape == (B,) and kv_len.is_contiguous()
     _check(_lib.elsa_attn_fwd_masked(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, n, d, float(scale),
-                                     int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
+                                     int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream, q)))
     return out
 
 
@@ -120,7 +130,7 @@ def elsa_attn_fwd_lse(q, k, v, out, lse, scale, causal=False, kv_len=None, strea
     assert out.is_contiguous() and out.shape == q.shape and out.dtype == q.dtype
     assert lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, H, n)
     _check(_lib.elsa_attn_fwd_lse(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, n, d, float(scale),
-                                  int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
+                                  int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream, q)))
     return out, lse
 
 
@@ -138,7 +148,7 @@ def elsa_attn_fwd_cross(q, k, v, out, scale, causal=False, kv_len=None, lse=None
     if lse is not None:
         assert lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, H, nq)
     _check(_lib.elsa_attn_fwd_cross(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, nq, nk, d, float(scale),
-                                    int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
+                                    int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream, q)))
     return out
 
 
@@ -156,7 +166,7 @@ def elsa_attn_fwd_dv(q, k, v, out, scale, causal=False, kv_len=None, lse=None, s
     if lse is not None:
         assert lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, H, nq)
     _check(_lib.elsa_attn_fwd_dv(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(lse), B, H, nq, nk, d, dv, float(scale),
-                                 int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream)))
+                                 int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream, q)))
     return out
 
 
@@ -179,7 +189,7 @@ def elsa_attn_stream_step(q, k_chunk, v_chunk, state, scale, first, causal=False
         assert kv_len.is_cuda and kv_len.dtype == torch.int32 and tuple(kv_len.shape) == (B,)
     _check(_lib.elsa_attn_stream_step(_ptr(q), _ptr(k_chunk), _ptr(v_chunk), _ptr(state), B, H, nq, nc, d, float(scale),
                                       int(bool(causal)), int(causal_shift), _ptr(kv_len), int(bool(first)),
-                                      _dtype_code(q), _stream(stream)))
+                                      _dtype_code(q), _stream(stream, q)))
 
 
 def elsa_attn_stream_finish(state, out, lse=None, stream=None):
@@ -189,7 +199,7 @@ def elsa_attn_stream_finish(state, out, lse=None, stream=None):
     if lse is not None:
         assert lse.is_cuda and lse.is_contiguous() and lse.dtype == torch.float32 and tuple(lse.shape) == (B, H, nq)
     _check(_lib.elsa_attn_stream_finish(_ptr(state), _ptr(out), _ptr(lse), B, H, nq, d, _dtype_code(out),
-                                        _stream(stream)))
+                                        _stream(stream, out)))
     return out
 
 
@@ -203,7 +213,7 @@ def elsa_attn_fwd_varlen(q, k, v, out, cu_seqlens, max_seqlen, scale, causal=Fal
     T, H, d = (int(x) for x in q.shape)
     _check(_lib.elsa_attn_fwd_varlen(_ptr(q), _ptr(k), _ptr(v), _ptr(out), _ptr(cu_seqlens),
                                      int(cu_seqlens.numel()) - 1, T, int(max_seqlen), H, d, float(scale),
-                                     int(bool(causal)), _dtype_code(q), _stream(stream)))
+                                     int(bool(causal)), _dtype_code(q), _stream(stream, q)))
     return out
 
 
@@ -216,7 +226,7 @@ def elsa_attn_fwd_split_kv(q, k, v, part_m, part_S, part_W, scale, num_splits, c
         assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32 and tuple(t.shape) == shp
     _check(_lib.elsa_attn_fwd_split_kv(_ptr(q), _ptr(k), _ptr(v), _ptr(part_m), _ptr(part_S), _ptr(part_W),
                                        B, H, n, d, float(scale), int(bool(causal)), _ptr(kv_len), C,
-                                       _dtype_code(q), _stream(stream)))
+                                       _dtype_code(q), _stream(stream, q)))
     return part_m, part_S, part_W
 
 
@@ -228,7 +238,7 @@ def elsa_combine(part_m, part_S, part_W, out, stream=None):
         assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32
     assert out.is_cuda and out.is_contiguous() and tuple(out.shape) == (B, H, n, d)
     _check(_lib.elsa_combine(_ptr(part_m), _ptr(part_S), _ptr(part_W), _ptr(out), B, H, n, d, C,
-                             _dtype_code(out), _stream(stream)))
+                             _dtype_code(out), _stream(stream, out)))
     return out
 
 
@@ -269,7 +279,7 @@ def elsa_last_splits() -> int:
 
 
 def elsa_debug_layout_probe(out, stream=None):
-    _check(_lib.elsa_debug_layout_probe(_ptr(out), _stream(stream)))
+    _check(_lib.elsa_debug_layout_probe(_ptr(out), _stream(stream, out)))
     return out
 
 
