@@ -37,7 +37,8 @@ struct FwdParams {
                                      //    into the one already stored at part_m/S/W (streamed key chunks)
     int sort_batches;                // 1: dense, key padding, B <= 32, non-causal or a single query tile: batch entries in
                                      //    descending kv_len order
-    int snake;                       // causal work order: 1 = second run of blocks reversed (see decode_work), 0 = plain
+    int snake;                       // causal work order: 0 = plain, 1 = second run of blocks reversed (see decode_work),
+                                     //    2 = also the four-run rule (kernels that keep three blocks per CU resident)
     int coff;                        // dense layout, causal: key j is visible to query i iff j <= i + coff
     int m_natural;                   // 1: part_m in natural-log units, 0: log2 units (internal)
     int xcd_map;                     // block -> work item order, see decode_work
@@ -191,9 +192,11 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
             // over the CUs, with no dynamic balancing among them: the second run of kNumCu blocks is
             // walked backwards, so that the k-th longest tile shares its CU with the k-th shortest of
             // the two runs; later blocks fill slots as they free up, in descending order.  A launch of
-            // exactly four runs does best with its whole second half reversed (the fourth block of a
-            // CU then lands where the shortest resident one finishes first, and all sums are equal).
-            if (total > 3 * kNumCu && total <= 4 * kNumCu) {
+            // exactly four runs does best with its whole second half reversed when three blocks per CU are
+            // resident (the fourth block of a CU then lands where the shortest resident one finishes
+            // first, and all sums are equal); with two resident blocks per CU that order would hand out
+            // the last two runs shortest first (measured 5-15 % slower), so the rule is not applied there.
+            if (p.snake == 2 && total > 3 * kNumCu && total <= 4 * kNumCu) {
                 const long long half = total / 2;
                 if (w >= half) w = half + (total - 1 - w);
             } else if (w >= kNumCu && w < 2 * kNumCu) {
