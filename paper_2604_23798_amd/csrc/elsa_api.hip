@@ -247,12 +247,12 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     // every sequence wastes at most one partly filled tile
     p.var_tiles = cu_seqlens ? (int)(((long long)total_tokens + tq - 1) / tq + num_seqs) : 0;
     p.xcd_map = g.opt[ELSA_OPT_XCD_MAP];
-    // FP16 tiles on a K/V set far beyond the caches (> 512 MB, thousands of blocks, heads a multiple of the
+    // FP16 tiles on a K/V set beyond the 256 MB of last-level cache (>= 320 MB, thousands of blocks, heads a multiple of the
     // 8 XCDs): consecutive query tiles of one head per XCD, so that the 64 resident blocks of an XCD
     // share one K/V stream (LLaMA-13B shape at 32K: 12.6 -> 11.7 ms causal, 25.7 -> 23.1 ms non-causal;
     // smaller launches lose more to the coarser balance than they gain, the FP32 tiles gain nothing)
     if (p.xcd_map == 0 && path == 3 && !cu_seqlens && ((long long)B * H) % elsa::kNumXcd == 0 &&
-        4.0 * B * H * nk * d >= 512.0 * 1048576.0 && (long long)p.q_tiles * B * H * num_splits >= 16 * kNumCu)
+        4.0 * B * H * nk * d >= 320.0 * 1048576.0 && (long long)p.q_tiles * B * H * num_splits >= 16 * kNumCu)
         p.xcd_map = 2;
     p.snake = g.opt[ELSA_OPT_SNAKE] == 1 ? 0 : 1;
     if (p.snake && path == 2 && variant == 7 && d <= 64) p.snake = 2;   // three resident blocks per CU: four-run rule
