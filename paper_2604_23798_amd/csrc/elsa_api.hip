@@ -108,6 +108,9 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
         const int q_tiles = (n + sh.rows - 1) / sh.rows;
         for (int C = 1; C <= max_splits; ++C) {
             if (C > 1 && ((!fp16_tiles && sh.variant == 3) || nk / C < 256)) break;   // the 32-row tile splits the keys by itself
+            // under a causal mask key chunks only pay while the 128-row blocks do not fill the CUs twice: measured
+            // 20-45 % slower than one pass from two runs of blocks up (H = 8, n = 16384: 2.6 against 2.1 ms)
+            if (C > 1 && causal && BH * ((n + 127) / 128) >= 2 * kNumCu) break;
             const int chunk = (nk + C - 1) / C;
             const long long blocks = BH * q_tiles * C;
             if (blocks > 64 * kNumCu) continue;          // not a small problem in this shape
@@ -129,8 +132,8 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
                     else if (w >= kNumCu && w < 2 * kNumCu) { const long long last = blocks < 2 * kNumCu ? blocks : 2 * kNumCu; w = kNumCu + (last - 1 - w); }
                 }
                 const long long t = w / BH;
-                const int c = (int)(t % C);
-                int qt = (int)(t / C);
+                int qt = (int)(t % q_tiles);
+                const int c = (int)(t / q_tiles);
                 if (causal) qt = q_tiles - 1 - qt;
                 const double cost = steps_of(qt, c) + own;
                 if (i < placed) {
@@ -415,11 +418,12 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     const bool fp32_tiles = !fp16_tiles && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 2);
     const bool window = !fp16_tiles && n <= 96 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu;   // served by the LDS-free tile
     const bool modelled = fp32_tiles ? (d <= 64 || d == 128) : (fp16_tiles && d <= 64);
-    if (modelled && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= 4 * kNumCu &&
+    // (the FP16 step times were fitted on launches of up to four runs of 128-row blocks only)
+    if (modelled && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= (fp16_tiles ? 4 : 12) * kNumCu &&
         (long long)n * 8 > nk && n > 8 && n <= 16384 && !window) {
         int max_c = 1;
         if (g.ws && !fp16_tiles) {                // the FP16 tiles are not cut outside decoding
-            max_c = 8;
+            max_c = 4;                           // more chunks were never the best measured choice outside decoding
             while (max_c > 1 && elsa_split_kv_workspace_bytes(B, H, n, d, max_c) > g.ws_bytes) --max_c;
         }
         const TileChoice tc = choose_tiles(fp16_tiles, (long long)B * H, n, nk, d, causal, max_c);

@@ -94,10 +94,12 @@ __device__ __forceinline__ float merge_factors(float ma, float mb, float &fa, fl
 
 // Work item (query tile, key chunk, head) of this block.  Blocks are dealt round-robin to the
 // 8 XCDs, each with a private L2.
-//   order 0 (default): the head index runs fastest, the query tile slowest.  With B*H a
-//     multiple of 8 every XCD then serves a fixed subset of heads (their K and V stay in its
-//     L2), and a causal launch starts the longest query tiles of ALL heads first, which is
-//     what balances the triangular work over the CUs.
+//   order 0 (default): the head index runs fastest, then the query tile, the key chunk
+//     slowest.  With B*H a multiple of 8 every XCD then serves a fixed subset of heads (their
+//     K and V stay in its L2), and a causal launch starts the longest query tiles of ALL heads
+//     first, which is what balances the triangular work over the CUs.  (A chunk index between
+//     head and tile would hand the long and the short chunk of a causal tile to fixed,
+//     alternating CUs.)
 //   order 1: the query tile runs fastest (consecutive blocks share a head).
 //   order 2: as order 1, with consecutive work items steered to the same XCD.
 struct Work {
@@ -232,10 +234,15 @@ __device__ __forceinline__ Work decode_work(const FwdParams &p) {
             r.c = (int)(t % p.num_splits);
             r.qt = (int)(t / p.num_splits);
         } else {
+            // head fastest, then the query tile, the key chunk slowest: blocks that run together work on
+            // the same chunk of K and V, and the chunk index never lines up with the CU a block lands on
+            // (with the chunk between head and tile, every second block of an XCD was a chunk-0 block: under a
+            // causal mask the long blocks then piled up on every second CU -- 2.99 against 2.08 ms unsplit at
+            // H = 8, n = 16384)
             r.bh = w % BH;
             const long long t = w / BH;
-            r.c = (int)(t % p.num_splits);
-            r.qt = (int)(t / p.num_splits);
+            r.qt = (int)(t % p.q_tiles);
+            r.c = (int)(t / p.q_tiles);
         }
     } else {
         r.qt = (int)(w % p.q_tiles);
