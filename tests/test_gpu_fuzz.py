@@ -40,7 +40,7 @@ def _case(rng):
     wide = d in (96, 256)
     r = rng.integers(0, 4)
     if r == 1:
-        opts = dict(path=2, variant=int(rng.choice([1, 3] if wide else [1, 2, 3, 4, 7, 8])))
+        opts = dict(path=2, variant=int(rng.choice([1, 3] if wide else [1, 2, 3, 4, 7, 8, 11] + ([12] if d == 128 else []))))
     elif r == 2 and fp16:
         opts = dict(path=3, variant=int(rng.choice([1, 2, 3, 4])))
     elif r == 3 and not wide:
@@ -163,3 +163,52 @@ def test_random_cases_with_a_value_width_of_their_own(block):
         assert np.all(np.isneginf(lse[~vis])), what
         assert np.max(np.abs(lse[vis] - ref_lse[vis]), initial=0.0) < (5e-3 if fp16 else 3e-5), what
         assert_parity(out, ref, tolerance(max(nq, nk), fp16), what)
+
+
+@pytest.mark.parametrize("block", range(4))
+def test_random_cases_with_the_library_choosing_tile_and_key_chunks(block):
+    """Nothing forced and a workspace lent: tile shape and number of key chunks come from the library's
+    own play-through of the launch, at the sizes where that model is active."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    rng = np.random.default_rng(9800 + block)
+    ws = torch.empty(128 << 20, dtype=torch.uint8, device="cuda")
+    seen = set()
+    for i in range(10):
+        d = int(rng.choice([32, 64, 64, 128]))
+        fp16 = bool(rng.integers(0, 2)) and d <= 64
+        B = int(rng.integers(1, 4))
+        H = int(rng.choice([1, 3, 8, 12, 16]))
+        nk = int(rng.choice([197, 300, 512, 640, 1000, 1536, 2048, 2500]))
+        nq = nk if rng.integers(0, 3) else int(rng.choice([64, 130, 300]))
+        if nq > nk:
+            nq = nk
+        causal = bool(rng.integers(0, 2))
+        kv_len = rng.integers(nk // 2, nk + 1, size=B).astype(np.int32) if rng.integers(0, 3) == 0 else None
+        seed = 9900 + 100 * block + i
+        q = inputs.normal(seed, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
+        k = inputs.normal(seed, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
+        v = inputs.normal(seed, 2, 0, B * H * nk * d).reshape(B, H, nk, d)
+        if fp16:
+            q, k, v = (t.astype(np.float16) for t in (q, k, v))
+        scale = float(np.float32(d ** -0.5))
+        # the oracle on a sample of rows (all of them would take a minute at the larger sizes)
+        per_head = np.unique(np.concatenate([[0, nq - 1], rng.integers(0, nq, size=48)])).astype(np.int64)
+        rows = (np.arange(B * H, dtype=np.int64)[:, None] * nq + per_head[None, :]).reshape(-1)
+        ref, ref_lse = oracle.dv_rows(f32(q), f32(k), f32(v), scale, causal=causal, kv_len=kv_len, rows=rows)
+        try:
+            elsa.elsa_set_workspace(ws)
+            out, lse = G.fwd_cross(q, k, v, scale, causal=causal, kv_len=kv_len, want_lse=True)
+            plan = (elsa.elsa_last_kernel(), elsa.elsa_last_splits())
+        finally:
+            elsa.elsa_set_workspace(None)
+        seen.add(plan)
+        what = "fuzz auto %d/%d d=%d fp16=%d B=%d H=%d nq=%d nk=%d causal=%d len=%s plan=%s" % (
+            block, i, d, fp16, B, H, nq, nk, causal, kv_len is not None, plan)
+        print(what, flush=True)
+        out, lse = out[rows], lse[rows]
+        vis = np.isfinite(ref_lse)
+        assert np.all(np.isneginf(lse[~vis])), what
+        assert np.max(np.abs(lse[vis] - ref_lse[vis]), initial=0.0) < (5e-3 if fp16 else 3e-5), what
+        assert_parity(out, ref, tolerance(max(nq, nk), fp16), what)
+    assert len(seen) >= 3, seen                 # the sweep does exercise several plans
