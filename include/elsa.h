@@ -215,8 +215,8 @@ int elsa_set_workspace(void *dev_ptr, size_t bytes);
  *   ELSA_OPT_VARIANT  0 = auto, otherwise a tile configuration id (see elsa_variant_name)
  *   ELSA_OPT_SPLITS   0 = auto, otherwise the number of key chunks elsa_attn_fwd uses
  *                     when a workspace is registered
- *   ELSA_OPT_XCD_MAP  block -> work order: 0 = head index fastest, longest causal tiles of all
- *                     heads first (default); 1 = query tile fastest; 2 = as 1, consecutive work
+ *   ELSA_OPT_XCD_MAP  block -> work order: 0 = head index fastest, key chunk slowest, longest causal
+ *                     tiles of all heads first (default); 1 = query tile fastest; 2 = as 1, consecutive work
  *                     items steered to the same XCD
  *   ELSA_OPT_SNAKE    work order 0 of causal, key-padded or packed launches: 0 = longest work first
  *                     (padded batch entries by descending kv_len when 2 <= B <= 32, packed sequences

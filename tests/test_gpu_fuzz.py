@@ -31,9 +31,9 @@ def _case(rng):
     if kind == "square":
         nq = nk
     elif kind == "decode":
-        nq = int(rng.integers(1, 5))
+        nq = int(rng.integers(1, 9))
     else:
-        nq = int(rng.choice([1, 5, 33, 64, 130, 300]))
+        nq = int(rng.choice([1, 5, 9, 17, 32, 33, 64, 130, 300]))
     use_len = bool(rng.integers(0, 2)) and kind in ("square", "cross", "decode")
     kv_len = rng.integers(0, nk + 1, size=B).astype(np.int32) if use_len else None
     opts = {}
