@@ -70,6 +70,21 @@ def test_small_problems_follow_the_block_placement_model():
     assert plan(1, 16, 1024, 1024, 64, dtype=1, ws_mib=64) == ("mfma16_xwave", 1)
 
 
+def test_key_chunks_stay_few_and_causal_launches_of_two_runs_are_not_cut():
+    # a causal launch whose 128-row blocks fill the CUs twice brings blocks of every length: one pass
+    for H, n in ((8, 16384), (8, 12288), (16, 8192), (24, 6144)):
+        assert plan(1, H, n, n, 64, causal=True, ws_mib=256)[1] == 1
+        assert plan(1, H, n, n, 128, causal=True, ws_mib=256)[1] == 1
+    # outside decoding the model never asks for more than four chunks
+    for H in (1, 3, 8, 12, 16, 24):
+        for n in (512, 1000, 1536, 2500, 3072, 6144):
+            for d in (32, 64, 128):
+                for causal in (False, True):
+                    assert 1 <= plan(1, H, n, n, d, causal=causal, ws_mib=256)[1] <= 4
+    # mid-sized launches that fill the last run badly are repaired (a smaller tile or two chunks)
+    assert plan(1, 12, 12288, 12288, 64, ws_mib=256) != ("mfma_q128_k32", 1)
+
+
 def test_window_attention_takes_the_lds_free_tile():
     assert plan(512, 3, 49, 49, 32) == ("mfma_small_q32", 1)
     assert plan(392, 3, 64, 64, 32) == ("mfma_small_q32", 1)
