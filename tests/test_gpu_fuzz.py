@@ -1,6 +1,8 @@
 """Seeded random sweep over shapes, masks, options and entry points (all inputs valid), every case
 checked against the FP64 oracle.  Meant to catch interactions that the structured tests do not
 enumerate: work orders x key chunks x masks x tile shapes x head dimensions."""
+import os
+
 import numpy as np
 import pytest
 
@@ -11,6 +13,8 @@ from tests.parity import assert_parity, tolerance
 
 pytestmark = pytest.mark.gpu
 f32 = lambda t: t.astype(np.float32)
+# ELSA_FUZZ_OFFSET=k shifts every generator seed by k: other cases of the same distributions (default 0)
+OFFSET = 100000 * int(os.environ.get("ELSA_FUZZ_OFFSET", "0"))
 
 
 @pytest.fixture(scope="module", autouse=True)
@@ -67,11 +71,11 @@ def _tensors(c, seed):
 def test_random_cases(block):
     import torch
     from paper_2604_23798_amd import elsa
-    rng = np.random.default_rng(9000 + block)
+    rng = np.random.default_rng(9000 + block + OFFSET)
     ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     for i in range(20):
         c = _case(rng)
-        seed = 9100 + 100 * block + i
+        seed = 9100 + 100 * block + i + OFFSET
         d, scale = c["d"], float(np.float32(c["d"] ** -0.5))
         what = "fuzz %d/%d %s" % (block, i, {k_: v_ for k_, v_ in c.items() if k_ != "kv_len"})
         tol = tolerance(max(c["nq"], c["nk"]), c["fp16"])
@@ -122,7 +126,7 @@ def test_random_cases_with_a_value_width_of_their_own(block):
     """The same sweep for elsa_attn_fwd_dv: pairs, shapes, masks, tiles, work orders, key chunks."""
     import torch
     from paper_2604_23798_amd import elsa
-    rng = np.random.default_rng(9500 + block)
+    rng = np.random.default_rng(9500 + block + OFFSET)
     ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     pairs = [(32, 64), (32, 128), (64, 32), (64, 128), (128, 32), (128, 64), (192, 128)]
     for i in range(20):
@@ -142,7 +146,7 @@ def test_random_cases_with_a_value_width_of_their_own(block):
             opts["path"] = 2
         if variant == 3 and d == 192 and (not fp16 or opts.get("path") == 2):
             opts["variant"] = 0                  # the FP32 tiles have no key-splitting shape at d = 192
-        seed = 9600 + 100 * block + i
+        seed = 9600 + 100 * block + i + OFFSET
         what = "fuzz dv %d/%d d=%d dv=%d fp16=%d B=%d H=%d nq=%d nk=%d causal=%d len=%s %s" % (
             block, i, d, dv, fp16, B, H, nq, nk, causal, kv_len is not None, opts)
         print(what, flush=True)
@@ -171,7 +175,7 @@ def test_random_cases_with_the_library_choosing_tile_and_key_chunks(block):
     own play-through of the launch, at the sizes where that model is active."""
     import torch
     from paper_2604_23798_amd import elsa
-    rng = np.random.default_rng(9800 + block)
+    rng = np.random.default_rng(9800 + block + OFFSET)
     ws = torch.empty(128 << 20, dtype=torch.uint8, device="cuda")
     seen = set()
     for i in range(10):
@@ -185,7 +189,7 @@ def test_random_cases_with_the_library_choosing_tile_and_key_chunks(block):
             nq = nk
         causal = bool(rng.integers(0, 2))
         kv_len = rng.integers(nk // 2, nk + 1, size=B).astype(np.int32) if rng.integers(0, 3) == 0 else None
-        seed = 9900 + 100 * block + i
+        seed = 9900 + 100 * block + i + OFFSET
         q = inputs.normal(seed, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
         k = inputs.normal(seed, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
         v = inputs.normal(seed, 2, 0, B * H * nk * d).reshape(B, H, nk, d)
