@@ -149,11 +149,11 @@ def tile_sweep(a):
         return e0.elapsed_time(e1) / max(a.steps, 200) * 1e3, elsa.elsa_last_kernel(), elsa.elsa_last_splits()
 
     f32_narrow = [(2, 7, 1), (2, 7, 2), (2, 7, 4), (2, 11, 1), (2, 11, 2), (2, 3, 1)]
-    f32_wide = [(2, 1, 1), (2, 1, 2), (2, 1, 4), (2, 11, 1), (2, 11, 2)]
+    f32_wide = [(2, 1, 1), (2, 1, 2), (2, 1, 4), (2, 11, 1), (2, 11, 2), (2, 13, 1)]
     f16 = [(3, 1, 1), (3, 2, 1), (3, 3, 1), (3, 4, 1)]
     shapes = [(1, 16, n, 64, False) for n in (256, 512, 768, 1024, 1536, 2048, 3072)] + \
              [(B, 12, 197, 64, False) for B in (1, 4, 8, 16)] + [(1, 32, 1024, 32, False), (1, 8, 2048, 64, False), (1, 8, 4096, 64, False)] + \
-             [(1, 40, n, 128, False) for n in (256, 512, 1024, 2048)] + [(1, 16, 1024, 128, False), (1, 32, 1536, 128, False)] + \
+             [(1, 40, n, 128, False) for n in (256, 512, 1024, 2048)] + [(1, 16, 1024, 128, False), (1, 32, 1536, 128, False), (1, 16, 3072, 128, False), (1, 24, 2048, 128, False)] + \
              [(1, 16, n, 64, True) for n in (1024, 2048, 3072, 4096, 8192)] + [(4, 12, 197, 64, True), (1, 8, 4096, 64, True)]
     rows = []
     for (B, H, n, d, fp16) in shapes:

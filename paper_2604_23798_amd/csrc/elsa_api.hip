@@ -91,11 +91,12 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
     static const TileShape f32_narrow[3] = {{7, 128, 1, 3, 2.25, 2.0}, {11, 64, 2, 2, 2.4, 2.15}, {3, 32, 4, 1, 2.6, 2.6}};
     // d = 128: the 128-row tile holds two blocks per CU, the 64-row tile (its LDS tiles fill a CU) one
     // (one wave per SIMD hides no latency: 5.3 us per step at d = 128, 2.8 at the d = 64 scale)
-    static const TileShape f32_wide[2] = {{1, 128, 1, 2, 2.4, 2.15}, {11, 64, 2, 1, 2.8, 2.8}};
+    // the same 64-row tile single-buffered [13]: half the LDS, two blocks per CU; slower alone (2.9), faster in pairs (2.5); never cut (measured 10-20 % behind the cut 128-row tile)
+    static const TileShape f32_wide[3] = {{1, 128, 1, 2, 2.4, 2.15}, {11, 64, 2, 1, 2.8, 2.8}, {13, 64, 2, 2, 2.9, 2.5}};
     static const TileShape f16_narrow[4] = {{1, 128, 1, 2, 0.54, 0.36}, {2, 256, 1, 2, 0.88, 0.66}, {4, 64, 2, 2, 0.60, 0.40},
                                             {3, 32, 4, 2, 0.58, 0.58}};
     const TileShape *shapes = fp16_tiles ? f16_narrow : d == 128 ? f32_wide : f32_narrow;
-    const int nshapes = fp16_tiles ? 4 : d == 128 ? 2 : 3;
+    const int nshapes = fp16_tiles ? 4 : 3;
     const double dscale = 0.12 + 0.88 * d / 64.0;        // the MFMA part of a step grows with d
     const double prologue = 5.0;
     const int coff = nk - n;
@@ -107,7 +108,7 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
         const TileShape &sh = shapes[si];
         const int q_tiles = (n + sh.rows - 1) / sh.rows;
         for (int C = 1; C <= max_splits; ++C) {
-            if (C > 1 && ((!fp16_tiles && sh.variant == 3) || nk / C < 256)) break;   // the 32-row tile splits the keys by itself
+            if (C > 1 && ((!fp16_tiles && (sh.variant == 3 || sh.variant == 13)) || nk / C < 256)) break;   // the 32-row tile splits the keys by itself
             // under a causal mask key chunks only pay while the 128-row blocks do not fill the CUs twice: measured
             // 20-45 % slower than one pass from two runs of blocks up (H = 8, n = 16384: 2.6 against 2.1 ms)
             if (C > 1 && causal && BH * ((n + 127) / 128) >= 2 * kNumCu) break;

@@ -335,7 +335,7 @@ int mfma16_variant_tq(int variant, int d);
 const char *mfma16_variant_name(int variant);
 const char *mfma_variant_name(int variant);
 const char *fma_variant_name(int variant);
-constexpr int kMfmaVariants = 12;
+constexpr int kMfmaVariants = 13;
 constexpr int kFmaVariants = 5;
 constexpr int kMfma16Variants = 4;
 

@@ -12,10 +12,12 @@ namespace elsa {
 //     9/10 small: one wave per 64 / 32 query rows, operands straight from memory (elsa_fwd_small.hip)
 //     11 q64xw2: 64 query rows, two query waves x two key waves (the key-splitting shape of d >= 96)
 //     12 xwave32: d = 128 only: 32 query rows, four key waves on one 128-key LDS tile (single buffer)
+//     13 q64xw2sb: d = 128 only: shape 11 with a single LDS buffer (67 KB), so that two blocks share a CU
 
 static const char *kNames[kMfmaVariants] = {"mfma_q128_w4",   "mfma_q256_w4",   "mfma_xwave",    "mfma_q256_w8",
                                             "mfma_q128_acc1", "mfma_q128_acc4", "mfma_q128_k32", "mfma_q128_gld",
-                                            "mfma_small_q64", "mfma_small_q32", "mfma_q64_xw2", "mfma_xwave32"};
+                                            "mfma_small_q64", "mfma_small_q32", "mfma_q64_xw2", "mfma_xwave32",
+                                            "mfma_q64_xw2_sb"};
 
 int mfma_variant_tq(int variant, int d) {
     switch (variant) {
@@ -27,6 +29,7 @@ int mfma_variant_tq(int variant, int d) {
         case 10: return 32;
         case 11: return d == 256 ? 128 : 64;
         case 12: return d == 128 ? 32 : 0;
+        case 13: return d == 128 ? 64 : 0;
         default: return 0;
     }
 }
@@ -74,6 +77,9 @@ static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
             else return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
         case 12:
             if constexpr (D == 128) return launch_one<D, T, 1, 1, 4, 32, 1, 2, 2>(p, s);
+            else return (int)hipErrorInvalidValue;
+        case 13:
+            if constexpr (D == 128) return launch_one<D, T, 1, 2, 2, 32, 2, 2, 2>(p, s);
             else return (int)hipErrorInvalidValue;
         default: return (int)hipErrorInvalidValue;
     }

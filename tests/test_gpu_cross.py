@@ -257,3 +257,43 @@ def test_single_buffered_key_splitting_tile_at_d128(fp16):
     q, k, v = _rect(1, 1, 16, 64, 64, 5)
     with G.Options(path=2, variant=12), pytest.raises(elsa.ElsaError):
         G.fwd_cross(q, k, v, 0.125)
+
+
+@pytest.mark.parametrize("fp16", [False, True])
+def test_single_buffered_64_row_tile_at_d128(fp16):
+    """mfma_q64_xw2_sb: the 64-row tile of two query waves x two key waves with one LDS buffer instead of two
+    (two blocks per CU at d = 128): square and rectangular problems, masks, chunks, ragged tails."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    d = 128
+    ws = torch.empty(32 << 20, dtype=torch.uint8, device="cuda")
+    for nq, nk in [(64, 64), (65, 65), (300, 300), (130, 1000), (1, 70), (200, 63)]:
+        q, k, v = _rect(2, 3, nq, nk, d, 1900 + nq + nk, fp16=fp16)
+        kv_len = np.array([nk, max(0, nk // 3)], np.int32)
+        for causal in (False, True):
+            for kl in (None, kv_len):
+                ref, ref_lse = _ref(q, k, v, d ** -0.5, causal=causal, kv_len=kl)
+                vis = np.isfinite(ref_lse)
+                for splits in (0, 3):
+                    if splits > nk:
+                        continue
+                    elsa.elsa_set_workspace(ws if splits else None)
+                    try:
+                        with G.Options(path=2, variant=13, splits=splits):
+                            out, lse = G.fwd_cross(q, k, v, d ** -0.5, causal=causal, kv_len=kl, want_lse=True)
+                            assert elsa.elsa_last_kernel() == "mfma_q64_xw2_sb"
+                    finally:
+                        elsa.elsa_set_workspace(None)
+                    what = "q64_xw2_sb %dx%d c%d pad%d s%d fp16=%d" % (nq, nk, causal, kl is not None, splits, fp16)
+                    assert_parity(out, ref, tolerance(nk, fp16), what)
+                    assert np.all(out[~vis] == 0) and np.all(np.isneginf(lse[~vis])), what
+    # the library's own choice for a causal launch of a few runs of blocks at d = 128; other head dimensions do not have the tile
+    q, k, v = _rect(1, 40, 1024, 1024, d, 1950)
+    rows = np.arange(0, 40 * 1024, 97, dtype=np.int64)
+    ref, _ = oracle.dv_rows(q, k, v, d ** -0.5, causal=True, rows=rows)
+    out = G.fwd_cross(q, k, v, d ** -0.5, causal=True)
+    assert elsa.elsa_last_kernel() == "mfma_q64_xw2_sb"
+    assert_parity(out[rows], ref, tolerance(1024), "q64_xw2_sb as the default")
+    q, k, v = _rect(1, 1, 16, 64, 64, 5)
+    with G.Options(path=2, variant=13), pytest.raises(elsa.ElsaError):
+        G.fwd_cross(q, k, v, 0.125)

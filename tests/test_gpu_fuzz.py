@@ -44,7 +44,7 @@ def _case(rng):
     wide = d in (96, 256)
     r = rng.integers(0, 4)
     if r == 1:
-        opts = dict(path=2, variant=int(rng.choice([1, 3] if wide else [1, 2, 3, 4, 7, 8, 11] + ([12] if d == 128 else []))))
+        opts = dict(path=2, variant=int(rng.choice([1, 3] if wide else [1, 2, 3, 4, 7, 8, 11] + ([12, 13] if d == 128 else []))))
     elif r == 2 and fp16:
         opts = dict(path=3, variant=int(rng.choice([1, 2, 3, 4])))
     elif r == 3 and not wide:

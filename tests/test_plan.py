@@ -58,6 +58,10 @@ def test_small_problems_follow_the_block_placement_model():
     assert plan(1, 16, 3072, 3072, 64, ws_mib=64) in (("mfma_q64_xw2", 1), ("mfma_q128_k32", 2))
     assert plan(1, 16, 3072, 3072, 64) == ("mfma_q64_xw2", 1)               # 768 blocks: exactly three rounds
     assert plan(1, 40, 1024, 1024, 128, ws_mib=256) == ("mfma_q128_w4", 4)   # 320 blocks -> 1280
+    # d = 128, causal, a few runs of blocks: the single-buffered 64-row tile (two blocks per CU), never cut
+    assert plan(1, 40, 1024, 1024, 128, causal=True, ws_mib=256) == ("mfma_q64_xw2_sb", 1)
+    assert plan(1, 16, 3072, 3072, 128, causal=True, ws_mib=256) == ("mfma_q64_xw2_sb", 1)
+    assert plan(1, 16, 3072, 3072, 64, causal=True, ws_mib=256)[0] != "mfma_q64_xw2_sb"       # d = 128 only
     # FP16 tiles: the shape is chosen the same way, the keys are never cut
     assert plan(1, 16, 2048, 2048, 64, dtype=1, ws_mib=64) == ("mfma16_q64_xw2", 1)
     assert plan(1, 16, 2048, 2048, 64, dtype=1, causal=True) in (("mfma16_q64_xw2", 1), ("mfma16_xwave", 1))   # 25.3 / 25.8 us
