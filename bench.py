@@ -154,7 +154,7 @@ def tile_sweep(a):
     shapes = [(1, 16, n, 64, False) for n in (256, 512, 768, 1024, 1536, 2048, 3072)] + \
              [(B, 12, 197, 64, False) for B in (1, 4, 8, 16)] + [(1, 32, 1024, 32, False), (1, 8, 2048, 64, False), (1, 8, 4096, 64, False)] + \
              [(1, 40, n, 128, False) for n in (256, 512, 1024, 2048)] + [(1, 16, 1024, 128, False), (1, 32, 1536, 128, False), (1, 16, 3072, 128, False), (1, 24, 2048, 128, False)] + \
-             [(1, 16, n, 64, True) for n in (1024, 2048, 3072, 4096, 8192)] + [(4, 12, 197, 64, True), (1, 8, 4096, 64, True)]
+             [(1, 16, n, 64, True) for n in (1024, 2048, 3072, 4096, 8192)] + [(4, 12, 197, 64, True), (1, 8, 4096, 64, True), (1, 16, 2048, 128, True), (1, 8, 4096, 128, True), (1, 40, 1024, 128, True)]
     rows = []
     for (B, H, n, d, fp16) in shapes:
         forced = f16 if fp16 else (f32_wide if d == 128 else f32_narrow)

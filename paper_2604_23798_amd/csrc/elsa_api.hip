@@ -95,9 +95,11 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
     static const TileShape f32_wide[3] = {{1, 128, 1, 2, 2.4, 2.15}, {11, 64, 2, 1, 2.8, 2.8}, {13, 64, 2, 2, 2.9, 2.5}};
     static const TileShape f16_narrow[4] = {{1, 128, 1, 2, 0.54, 0.36}, {2, 256, 1, 2, 0.88, 0.66}, {4, 64, 2, 2, 0.60, 0.40},
                                             {3, 32, 4, 2, 0.58, 0.58}};
-    const TileShape *shapes = fp16_tiles ? f16_narrow : d == 128 ? f32_wide : f32_narrow;
-    const int nshapes = fp16_tiles ? 4 : 3;
-    const double dscale = 0.12 + 0.88 * d / 64.0;        // the MFMA part of a step grows with d
+    // FP16 tiles at d = 128 (us per step as measured there, not scaled): 128 rows 0.78 / 0.64; 64 rows x 2 key waves 1.0 / 0.75
+    static const TileShape f16_wide[2] = {{1, 128, 1, 2, 0.78, 0.64}, {4, 64, 2, 2, 1.0, 0.75}};
+    const TileShape *shapes = fp16_tiles ? (d == 128 ? f16_wide : f16_narrow) : d == 128 ? f32_wide : f32_narrow;
+    const int nshapes = fp16_tiles ? (d == 128 ? 2 : 4) : 3;
+    const double dscale = (fp16_tiles && d == 128) ? 1.0 : 0.12 + 0.88 * d / 64.0;        // the MFMA part of a step grows with d
     const double prologue = 5.0;
     const int coff = nk - n;
     TileChoice best{shapes[0].variant, 1};
@@ -418,7 +420,7 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     const long long b128 = (long long)B * H * ((n + 127) / 128);
     const bool fp32_tiles = !fp16_tiles && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 2);
     const bool window = !fp16_tiles && n <= 96 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu;   // served by the LDS-free tile
-    const bool modelled = fp32_tiles ? (d <= 64 || d == 128) : (fp16_tiles && d <= 64);
+    const bool modelled = (fp32_tiles || fp16_tiles) && (d <= 64 || d == 128);
     // (the FP16 step times were fitted on launches of up to four runs of 128-row blocks only)
     if (modelled && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= (fp16_tiles ? 4 : 12) * kNumCu &&
         (long long)n * 8 > nk && n > 8 && n <= 16384 && !window) {

@@ -67,6 +67,11 @@ def test_small_problems_follow_the_block_placement_model():
     assert plan(1, 16, 2048, 2048, 64, dtype=1, causal=True) in (("mfma16_q64_xw2", 1), ("mfma16_xwave", 1))   # 25.3 / 25.8 us
     assert plan(1, 16, 4096, 4096, 64, dtype=1, causal=True) == ("mfma16_q64_xw2", 1)
     assert plan(1, 16, 4096, 4096, 64, dtype=1) == ("mfma16_q128_w4", 1)
+    # FP16 tiles at d = 128: causal launches of one or two runs of 128-row blocks take the 64-row tile (measured 25-36 % faster)
+    assert plan(1, 16, 2048, 2048, 128, dtype=1, causal=True) == ("mfma16_q64_xw2", 1)
+    assert plan(1, 8, 4096, 4096, 128, dtype=1, causal=True) == ("mfma16_q64_xw2", 1)
+    assert plan(1, 40, 4096, 4096, 128, dtype=1, causal=True) == ("mfma16_q128_w4", 1)
+    assert plan(1, 40, 4096, 4096, 128, dtype=1) == ("mfma16_q128_w4", 1)
     # a forced tile or chunk count switches the model off
     assert plan(1, 16, 1024, 1024, 64, ws_mib=64, variant=7) == ("mfma_q128_k32", 2)
     assert plan(1, 16, 1024, 1024, 64, ws_mib=64, splits=3)[1] == 3
