@@ -204,18 +204,24 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
             for (int nq = 0; nq < NQ; ++nq)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) sacc[nq][i] = 0.f;
-            // every K fragment of the step is requested before the first MFMA: the reads then overlap
-            // the MFMA chain instead of being waited for one by one
-            f16x8 kf[KC];
+            // the K fragments of the step are requested before the first MFMA that needs them: all of them,
+            // or two at a time at d = 256 under the register cap of two waves per SIMD (sixteen fragments
+            // there spilled 50 registers more and ran 2.9 times slower: 16.9 against 5.8 ms at H = 16,
+            // n = 16384); the reads then overlap the MFMA chain instead of being waited for one by one
+            constexpr int PF = (KC <= 12 || WPE == 1) ? KC : 2;
 #pragma unroll
-            for (int cc = 0; cc < KC; ++cc)
-                kf[cc] = *reinterpret_cast<const f16x8 *>(Kb + (kl + j) * KROWB + 32 * cc + 16 * h);
+            for (int c0 = 0; c0 < KC; c0 += PF) {
+                f16x8 kf[PF];
 #pragma unroll
-            for (int cc = 0; cc < KC; ++cc)
+                for (int cc = 0; cc < PF; ++cc)
+                    kf[cc] = *reinterpret_cast<const f16x8 *>(Kb + (kl + j) * KROWB + 32 * (c0 + cc) + 16 * h);
 #pragma unroll
-                for (int nq = 0; nq < NQ; ++nq) sacc[nq] = mfma16(kf[cc], qf[nq][cc], sacc[nq]);
-            __builtin_amdgcn_sched_group_barrier(0x100, KC, 0);          // KC LDS reads
-            __builtin_amdgcn_sched_group_barrier(0x008, KC * NQ, 0);     // then the MFMAs
+                for (int cc = 0; cc < PF; ++cc)
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq) sacc[nq] = mfma16(kf[cc], qf[nq][c0 + cc], sacc[nq]);
+                __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);          // PF LDS reads
+                __builtin_amdgcn_sched_group_barrier(0x008, PF * NQ, 0);     // then the MFMAs
+            }
 
             // ---- (a2) masks
             const bool need_mask = (kg + 32 > kend) || (p.causal && kg + 31 > wrow0 + coff);
