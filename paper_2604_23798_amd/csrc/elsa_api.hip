@@ -97,9 +97,17 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
                                             {3, 32, 4, 2, 0.58, 0.58}};
     // FP16 tiles at d = 128 (us per step as measured there, not scaled): 128 rows 0.78 / 0.64; 64 rows x 2 key waves 1.0 / 0.75
     static const TileShape f16_wide[2] = {{1, 128, 1, 2, 0.78, 0.64}, {4, 64, 2, 2, 1.0, 0.75}};
-    const TileShape *shapes = fp16_tiles ? (d == 128 ? f16_wide : f16_narrow) : d == 128 ? f32_wide : f32_narrow;
-    const int nshapes = fp16_tiles ? (d == 128 ? 2 : 4) : 3;
-    const double dscale = (fp16_tiles && d == 128) ? 1.0 : 0.12 + 0.88 * d / 64.0;        // the MFMA part of a step grows with d
+    // d = 96: the FP32 128-row tile behaves as at d = 128; its 64-row tile (two query x two key waves) owns the CU (100 KB of LDS);
+    // d = 256: one FP32 shape, one wave per SIMD.  FP16 at d = 96, unscaled: 128 rows 0.71 / 0.53, 64 rows x 2 key waves 0.80 / 0.60.
+    static const TileShape f32_d96[2] = {{1, 128, 1, 2, 2.4, 2.15}, {3, 64, 2, 1, 2.66, 2.66}};
+    static const TileShape f32_d256[1] = {{1, 128, 1, 1, 2.75, 2.62}};
+    static const TileShape f16_d96[2] = {{1, 128, 1, 2, 0.71, 0.53}, {4, 64, 2, 2, 0.80, 0.60}};
+    // FP16 at d = 256: the 128-row tile (register-capped, two blocks per CU) is slow alone: 2.8 / 1.41; 64 rows x 2 key waves own the CU: 2.3 / 2.0
+    static const TileShape f16_d256[2] = {{1, 128, 1, 2, 2.8, 1.41}, {4, 64, 2, 1, 2.3, 2.0}};
+    const TileShape *shapes = fp16_tiles ? (d == 128 ? f16_wide : d == 96 ? f16_d96 : d == 256 ? f16_d256 : f16_narrow)
+                                         : d == 128 ? f32_wide : d == 96 ? f32_d96 : d == 256 ? f32_d256 : f32_narrow;
+    const int nshapes = fp16_tiles ? (d >= 96 ? 2 : 4) : d == 96 ? 2 : d == 256 ? 1 : 3;
+    const double dscale = (fp16_tiles && d >= 96) ? 1.0 : 0.12 + 0.88 * d / 64.0;        // the MFMA part of a step grows with d
     const double prologue = 5.0;
     const int coff = nk - n;
     TileChoice best{shapes[0].variant, 1};
@@ -110,10 +118,10 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
         const TileShape &sh = shapes[si];
         const int q_tiles = (n + sh.rows - 1) / sh.rows;
         for (int C = 1; C <= max_splits; ++C) {
-            if (C > 1 && ((!fp16_tiles && (sh.variant == 3 || sh.variant == 13)) || nk / C < 256)) break;   // the 32-row tile splits the keys by itself
+            if (C > 1 && ((!fp16_tiles && ((sh.variant == 3 && sh.key_waves == 4) || sh.variant == 13)) || nk / C < 256)) break;   // the 32-row tile splits the keys by itself
             // under a causal mask key chunks only pay while the 128-row blocks do not fill the CUs twice: measured
             // 20-45 % slower than one pass from two runs of blocks up (H = 8, n = 16384: 2.6 against 2.1 ms)
-            if (C > 1 && causal && BH * ((n + 127) / 128) >= 2 * kNumCu) break;
+            if (C > 1 && causal && sh.resident >= 2 && BH * ((n + 127) / 128) >= 2 * kNumCu) break;
             const int chunk = (nk + C - 1) / C;
             const long long blocks = BH * q_tiles * C;
             if (blocks > 64 * kNumCu) continue;          // not a small problem in this shape
@@ -420,7 +428,7 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     const long long b128 = (long long)B * H * ((n + 127) / 128);
     const bool fp32_tiles = !fp16_tiles && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 2);
     const bool window = !fp16_tiles && n <= 96 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu;   // served by the LDS-free tile
-    const bool modelled = (fp32_tiles || fp16_tiles) && (d <= 64 || d == 128);
+    const bool modelled = fp32_tiles || fp16_tiles;
     // (the FP16 step times were fitted on launches of up to four runs of 128-row blocks only)
     if (modelled && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= (fp16_tiles ? 4 : 12) * kNumCu &&
         (long long)n * 8 > nk && n > 8 && n <= 16384 && !window) {

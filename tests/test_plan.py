@@ -72,6 +72,12 @@ def test_small_problems_follow_the_block_placement_model():
     assert plan(1, 8, 4096, 4096, 128, dtype=1, causal=True) == ("mfma16_q64_xw2", 1)
     assert plan(1, 40, 4096, 4096, 128, dtype=1, causal=True) == ("mfma16_q128_w4", 1)
     assert plan(1, 40, 4096, 4096, 128, dtype=1) == ("mfma16_q128_w4", 1)
+    # d = 96 and d = 256 are played through as well (own step times; at d = 256 the FP32 tile owns its CU and may be cut under a causal mask)
+    assert plan(1, 8, 2048, 2048, 96, causal=True, ws_mib=256) == ("mfma_q128_w4", 4)            # 84 against 118 us with two chunks
+    assert plan(1, 16, 4096, 4096, 256, causal=True, ws_mib=256) == ("mfma_q128_w4", 2)          # 1.37 against 1.63 ms in one pass
+    assert plan(1, 16, 2048, 2048, 96, dtype=1, causal=True) == ("mfma16_q64_xw2", 1)           # 33 against 48 us
+    assert plan(1, 16, 2048, 2048, 256, dtype=1, causal=True) == ("mfma16_q64_xw2", 1)          # 114 against 167 us
+    assert plan(1, 16, 16384, 16384, 256, dtype=1) == ("mfma16_q128_w4", 1)
     # a forced tile or chunk count switches the model off
     assert plan(1, 16, 1024, 1024, 64, ws_mib=64, variant=7) == ("mfma_q128_k32", 2)
     assert plan(1, 16, 1024, 1024, 64, ws_mib=64, splits=3)[1] == 3
