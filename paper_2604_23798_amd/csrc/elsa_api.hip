@@ -116,6 +116,7 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
     double free_at[kNumCu];                  // min-heap: when a CU takes its next block (no host allocation)
     for (int si = 0; si < nshapes; ++si) {
         const TileShape &sh = shapes[si];
+        if (fp16_tiles && sh.rows == 256 && causal) continue;   // its diagonal tiles waste twice as much (measured: never the best under a causal mask)
         const int q_tiles = (n + sh.rows - 1) / sh.rows;
         for (int C = 1; C <= max_splits; ++C) {
             if (C > 1 && ((!fp16_tiles && ((sh.variant == 3 && sh.key_waves == 4) || sh.variant == 13)) || nk / C < 256)) break;   // the 32-row tile splits the keys by itself
@@ -429,8 +430,7 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     const bool fp32_tiles = !fp16_tiles && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 2);
     const bool window = !fp16_tiles && n <= 96 && (long long)B * H * ((n + 31) / 32) >= 4 * kNumCu;   // served by the LDS-free tile
     const bool modelled = fp32_tiles || fp16_tiles;
-    // (the FP16 step times were fitted on launches of up to four runs of 128-row blocks only)
-    if (modelled && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= (fp16_tiles ? 4 : 12) * kNumCu &&
+    if (modelled && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= 12 * kNumCu &&
         (long long)n * 8 > nk && n > 8 && n <= 16384 && !window) {
         int max_c = 1;
         if (g.ws && !fp16_tiles) {                // the FP16 tiles are not cut outside decoding
