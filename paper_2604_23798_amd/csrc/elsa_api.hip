@@ -81,33 +81,10 @@ int pick_variant(int path, long long BH, int n, int nk, int d, int splits, int c
 struct TileChoice { int variant, splits; };
 struct TileShape { int variant, rows, key_waves, resident; double t1, t2; };
 
-TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int causal, int max_splits) {
-    // the last question is usually asked again (a layer stack, a benchmark loop): remember its answer
-    struct Memo { bool f16; long long BH; int n, nk, d, causal, max_splits; TileChoice choice; };
-    static Memo memo{false, -1, 0, 0, 0, 0, 0, {0, 0}};
-    if (memo.f16 == fp16_tiles && memo.BH == BH && memo.n == n && memo.nk == nk && memo.d == d && memo.causal == causal &&
-        memo.max_splits == max_splits)
-        return memo.choice;
-    static const TileShape f32_narrow[3] = {{7, 128, 1, 3, 2.25, 2.0}, {11, 64, 2, 2, 2.4, 2.15}, {3, 32, 4, 1, 2.6, 2.6}};
-    // d = 128: the 128-row tile holds two blocks per CU, the 64-row tile (its LDS tiles fill a CU) one
-    // (one wave per SIMD hides no latency: 5.3 us per step at d = 128, 2.8 at the d = 64 scale)
-    // the same 64-row tile single-buffered [13]: half the LDS, two blocks per CU; slower alone (2.9), faster in pairs (2.5); never cut (measured 10-20 % behind the cut 128-row tile)
-    static const TileShape f32_wide[3] = {{1, 128, 1, 2, 2.4, 2.15}, {11, 64, 2, 1, 2.8, 2.8}, {13, 64, 2, 2, 2.9, 2.5}};
-    static const TileShape f16_narrow[4] = {{1, 128, 1, 2, 0.54, 0.36}, {2, 256, 1, 2, 0.88, 0.66}, {4, 64, 2, 2, 0.60, 0.40},
-                                            {3, 32, 4, 2, 0.58, 0.58}};
-    // FP16 tiles at d = 128 (us per step as measured there, not scaled): 128 rows 0.78 / 0.64; 64 rows x 2 key waves 1.0 / 0.75
-    static const TileShape f16_wide[2] = {{1, 128, 1, 2, 0.78, 0.64}, {4, 64, 2, 2, 1.0, 0.75}};
-    // d = 96: the FP32 128-row tile behaves as at d = 128; its 64-row tile (two query x two key waves) owns the CU (100 KB of LDS);
-    // d = 256: one FP32 shape, one wave per SIMD.  FP16 at d = 96, unscaled: 128 rows 0.71 / 0.53, 64 rows x 2 key waves 0.80 / 0.60.
-    static const TileShape f32_d96[2] = {{1, 128, 1, 2, 2.4, 2.15}, {3, 64, 2, 1, 2.66, 2.66}};
-    static const TileShape f32_d256[1] = {{1, 128, 1, 1, 2.75, 2.62}};
-    static const TileShape f16_d96[2] = {{1, 128, 1, 2, 0.71, 0.53}, {4, 64, 2, 2, 0.80, 0.60}};
-    // FP16 at d = 256: the 128-row tile (register-capped, two blocks per CU) is slow alone: 2.8 / 1.41; 64 rows x 2 key waves own the CU: 2.3 / 2.0
-    static const TileShape f16_d256[2] = {{1, 128, 1, 2, 2.8, 1.41}, {4, 64, 2, 1, 2.3, 2.0}};
-    const TileShape *shapes = fp16_tiles ? (d == 128 ? f16_wide : d == 96 ? f16_d96 : d == 256 ? f16_d256 : f16_narrow)
-                                         : d == 128 ? f32_wide : d == 96 ? f32_d96 : d == 256 ? f32_d256 : f32_narrow;
-    const int nshapes = fp16_tiles ? (d >= 96 ? 2 : 4) : d == 96 ? 2 : d == 256 ? 1 : 3;
-    const double dscale = (fp16_tiles && d >= 96) ? 1.0 : 0.12 + 0.88 * d / 64.0;        // the MFMA part of a step grows with d
+// The play-through itself, for a table of tile shapes.  `dw` is the width of a chunk state's W (d, or d_v when the
+// values have a width of their own); `no_cut` marks shapes that are never cut (bit i = shape i).
+TileChoice play_through(const TileShape *shapes, int nshapes, double dscale, unsigned no_cut, bool fp16_tiles, long long BH, int n,
+                        int nk, int dw, int causal, int max_splits) {
     const double prologue = 5.0;
     const int coff = nk - n;
     TileChoice best{shapes[0].variant, 1};
@@ -119,7 +96,7 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
         if (fp16_tiles && sh.rows == 256 && causal) continue;   // its diagonal tiles waste twice as much (measured: never the best under a causal mask)
         const int q_tiles = (n + sh.rows - 1) / sh.rows;
         for (int C = 1; C <= max_splits; ++C) {
-            if (C > 1 && ((!fp16_tiles && ((sh.variant == 3 && sh.key_waves == 4) || sh.variant == 13)) || nk / C < 256)) break;   // the 32-row tile splits the keys by itself
+            if (C > 1 && (((no_cut >> si) & 1u) || nk / C < 256)) break;
             // under a causal mask key chunks only pay while the 128-row blocks do not fill the CUs twice: measured
             // 20-45 % slower than one pass from two runs of blocks up (H = 8, n = 16384: 2.6 against 2.1 ms)
             if (C > 1 && causal && sh.resident >= 2 && BH * ((n + 127) / 128) >= 2 * kNumCu) break;
@@ -167,12 +144,78 @@ TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int
             const bool overlap = sh.resident >= 2 && (causal ? rounds > sh.resident : rounds >= 2);
             const double step = (overlap ? sh.t2 : sh.t1) * dscale;
             // second launch + the chunk states written and read back ((d + 2) floats per row and chunk, ~4 TB/s)
-            const double combine = C > 1 ? 5.0 + 2.0 * (double)(rounds - 1) + (double)BH * n * C * (d + 2) * 8.0 / 4.0e6 : 0.0;
+            const double combine = C > 1 ? 5.0 + 2.0 * (double)(rounds - 1) + (double)BH * n * C * (dw + 2) * 8.0 / 4.0e6 : 0.0;
             const double t = (sh.resident == 1 ? 0.0 : prologue) + busiest * step + combine;
             if (t < best_t) { best_t = t; best = TileChoice{sh.variant, C}; }
         }
     }
+    return best;
+}
+
+TileChoice choose_tiles(bool fp16_tiles, long long BH, int n, int nk, int d, int causal, int max_splits) {
+    // the last question is usually asked again (a layer stack, a benchmark loop): remember its answer
+    struct Memo { bool f16; long long BH; int n, nk, d, causal, max_splits; TileChoice choice; };
+    static Memo memo{false, -1, 0, 0, 0, 0, 0, {0, 0}};
+    if (memo.f16 == fp16_tiles && memo.BH == BH && memo.n == n && memo.nk == nk && memo.d == d && memo.causal == causal &&
+        memo.max_splits == max_splits)
+        return memo.choice;
+    static const TileShape f32_narrow[3] = {{7, 128, 1, 3, 2.25, 2.0}, {11, 64, 2, 2, 2.4, 2.15}, {3, 32, 4, 1, 2.6, 2.6}};
+    // d = 128: the 128-row tile holds two blocks per CU, the 64-row tile (its LDS tiles fill a CU) one
+    // (one wave per SIMD hides no latency: 5.3 us per step at d = 128, 2.8 at the d = 64 scale)
+    // the same 64-row tile single-buffered [13]: half the LDS, two blocks per CU; slower alone (2.9), faster in pairs (2.5); never cut (measured 10-20 % behind the cut 128-row tile)
+    static const TileShape f32_wide[3] = {{1, 128, 1, 2, 2.4, 2.15}, {11, 64, 2, 1, 2.8, 2.8}, {13, 64, 2, 2, 2.9, 2.5}};
+    static const TileShape f16_narrow[4] = {{1, 128, 1, 2, 0.54, 0.36}, {2, 256, 1, 2, 0.88, 0.66}, {4, 64, 2, 2, 0.60, 0.40},
+                                            {3, 32, 4, 2, 0.58, 0.58}};
+    // FP16 tiles at d = 128 (us per step as measured there, not scaled): 128 rows 0.78 / 0.64; 64 rows x 2 key waves 1.0 / 0.75
+    static const TileShape f16_wide[2] = {{1, 128, 1, 2, 0.78, 0.64}, {4, 64, 2, 2, 1.0, 0.75}};
+    // d = 96: the FP32 128-row tile behaves as at d = 128; its 64-row tile (two query x two key waves) owns the CU (100 KB of LDS);
+    // d = 256: one FP32 shape, one wave per SIMD.  FP16 at d = 96, unscaled: 128 rows 0.71 / 0.53, 64 rows x 2 key waves 0.80 / 0.60.
+    static const TileShape f32_d96[2] = {{1, 128, 1, 2, 2.4, 2.15}, {3, 64, 2, 1, 2.66, 2.66}};
+    static const TileShape f32_d256[1] = {{1, 128, 1, 1, 2.75, 2.62}};
+    static const TileShape f16_d96[2] = {{1, 128, 1, 2, 0.71, 0.53}, {4, 64, 2, 2, 0.80, 0.60}};
+    // FP16 at d = 256: the 128-row tile (register-capped, two blocks per CU) is slow alone: 2.8 / 1.41; 64 rows x 2 key waves own the CU: 2.3 / 2.0
+    static const TileShape f16_d256[2] = {{1, 128, 1, 2, 2.8, 1.41}, {4, 64, 2, 1, 2.3, 2.0}};
+    const TileShape *shapes = fp16_tiles ? (d == 128 ? f16_wide : d == 96 ? f16_d96 : d == 256 ? f16_d256 : f16_narrow)
+                                         : d == 128 ? f32_wide : d == 96 ? f32_d96 : d == 256 ? f32_d256 : f32_narrow;
+    const int nshapes = fp16_tiles ? (d >= 96 ? 2 : 4) : d == 96 ? 2 : d == 256 ? 1 : 3;
+    const double dscale = (fp16_tiles && d >= 96) ? 1.0 : 0.12 + 0.88 * d / 64.0;        // the MFMA part of a step grows with d
+    // never cut: the FP32 32-row tile (its four waves split the keys already) and the single-buffered 64-row tile
+    unsigned no_cut = 0;
+    for (int si = 0; si < nshapes; ++si)
+        if (!fp16_tiles && ((shapes[si].variant == 3 && shapes[si].key_waves == 4) || shapes[si].variant == 13)) no_cut |= 1u << si;
+    const TileChoice best = play_through(shapes, nshapes, dscale, no_cut, fp16_tiles, BH, n, nk, d, causal, max_splits);
     memo = Memo{fp16_tiles, BH, n, nk, d, causal, max_splits, best};
+    return best;
+}
+
+// The same choice when the values have a width of their own: tiles 1 (128 rows) and 3 (the waves split the keys: 32 rows x four
+// key waves when d, d_v <= 64, else 64 rows x two).  A step costs what the d_v = d tiles cost at the mean width (d + d_v) / 2
+// (scores contract over d, W^T has d_v rows); FP16 step times interpolate the measured ones of d = 64, 96, 128.
+TileChoice choose_tiles_dv(bool fp16_tiles, long long BH, int n, int nk, int d, int dv, int causal, int max_splits) {
+    struct Memo { bool f16; long long BH; int n, nk, d, dv, causal, max_splits; TileChoice choice; };
+    static Memo memo{false, -1, 0, 0, 0, 0, 0, 0, {0, 0}};
+    if (memo.f16 == fp16_tiles && memo.BH == BH && memo.n == n && memo.nk == nk && memo.d == d && memo.dv == dv &&
+        memo.causal == causal && memo.max_splits == max_splits)
+        return memo.choice;
+    const double x = 0.5 * (d + dv) / 64.0;
+    const bool narrow = d <= 64 && dv <= 64;
+    TileShape shapes[2];
+    int nshapes = 2;
+    double dscale = 1.0;
+    if (fp16_tiles) {
+        shapes[0] = TileShape{1, 128, 1, 2, 0.30 + 0.24 * x, 0.08 + 0.28 * x};
+        if (narrow) shapes[1] = TileShape{3, 32, 4, 2, 0.1 + 0.48 * x, 0.1 + 0.48 * x};
+        else if (d == 192) shapes[1] = TileShape{3, 64, 2, 2, 1.5, 1.26};     // measured: slower than the interpolation at this width
+        else shapes[1] = TileShape{3, 64, 2, 2, 0.20 + 0.40 * x, 0.05 + 0.35 * x};
+    } else {
+        dscale = 0.12 + 0.88 * x;
+        if (d == 192) { shapes[0] = TileShape{1, 128, 1, 1, 2.75, 2.62}; nshapes = 1; }
+        else if (narrow) { shapes[0] = TileShape{1, 128, 1, 3, 2.25, 2.0}; shapes[1] = TileShape{3, 32, 4, 1, 2.6, 2.6}; }
+        else { shapes[0] = TileShape{1, 128, 1, 2, 2.4, 2.15}; shapes[1] = TileShape{3, 64, 2, 1, 2.8, 2.8}; }
+    }
+    const unsigned no_cut = (!fp16_tiles && narrow) ? 2u : 0u;
+    const TileChoice best = play_through(shapes, nshapes, dscale, no_cut, fp16_tiles, BH, n, nk, dv, causal, max_splits);
+    memo = Memo{fp16_tiles, BH, n, nk, d, dv, causal, max_splits, best};
     return best;
 }
 
@@ -303,7 +346,7 @@ bool dv_pair_ok(int d, int dv) {
 // (128 query rows) otherwise.
 int run_forward_dv(const void *q, const void *k, const void *v, void *out, float *lse, float *pm, float *pS, float *pW,
                    int B, int H, int n, int nk, int d, int dv, float scale, int causal, const int32_t *kv_len,
-                   int num_splits, int emit, int dtype, void *stream) {
+                   int num_splits, int emit, int dtype, void *stream, int chosen_variant = 0) {
     int path = g.opt[ELSA_OPT_PATH];
     if (path == 0) path = (dtype == ELSA_F16 && scale != 0.f) ? 3 : 2;
     if (path == 1) return ELSA_ERR_UNSUPPORTED;
@@ -314,6 +357,7 @@ int run_forward_dv(const void *q, const void *k, const void *v, void *out, float
     int variant = g.opt[ELSA_OPT_VARIANT];
     if (variant != 0 && variant != 1 && variant != 3) return ELSA_ERR_UNSUPPORTED;
     const int tq3 = elsa::dv_variant_tq(fp16_tiles, 3, d, dv);
+    if (variant == 0 && chosen_variant != 0) variant = chosen_variant;    // from the block-placement model
     if (variant == 0) {
         const long long b128 = (long long)B * H * ((n + 127) / 128) * num_splits;
         variant = 1;
@@ -489,14 +533,29 @@ int elsa_attn_fwd_dv(const void *q, const void *k, const void *v, void *out, flo
     if (!dv_pair_ok(d, d_v)) return ELSA_ERR_UNSUPPORTED;
     const bool fp16_tiles = dtype == ELSA_F16 && scale != 0.f && (g.opt[ELSA_OPT_PATH] == 0 || g.opt[ELSA_OPT_PATH] == 3);
     // the states of a key split hold d_v columns: the workspace is sized by d_v
-    const int C = g.ws ? auto_splits(B, H, n_q, n_k, d_v, fp16_tiles) : 1;
+    int C = g.ws ? auto_splits(B, H, n_q, n_k, d_v, fp16_tiles) : 1;
+    // small problems: tile shape and key chunks together, from the block-placement model (as for d_v = d)
+    int chosen = 0;
+    const long long b128 = (long long)B * H * ((n_q + 127) / 128);
+    const bool tiles_free = g.opt[ELSA_OPT_PATH] == 0 || (g.opt[ELSA_OPT_PATH] == 3 && fp16_tiles) || (g.opt[ELSA_OPT_PATH] == 2 && !fp16_tiles);
+    if (tiles_free && g.opt[ELSA_OPT_VARIANT] == 0 && g.opt[ELSA_OPT_SPLITS] == 0 && b128 <= 12 * kNumCu &&
+        (long long)n_q * 8 > n_k && n_q > 8 && n_q <= 16384) {
+        int max_c = 1;
+        if (g.ws && !fp16_tiles) {                // the FP16 tiles are not cut outside decoding
+            max_c = 4;
+            while (max_c > 1 && elsa_split_kv_workspace_bytes(B, H, n_q, d_v, max_c) > g.ws_bytes) --max_c;
+        }
+        const TileChoice tc = choose_tiles_dv(fp16_tiles, (long long)B * H, n_q, n_k, d, d_v, causal, max_c);
+        chosen = tc.variant;
+        C = tc.splits;
+    }
     if (C == 1)
         return run_forward_dv(q, k, v, out, lse, nullptr, nullptr, nullptr, B, H, n_q, n_k, d, d_v, scale, causal, kv_len,
-                              1, 0, dtype, stream);
+                              1, 0, dtype, stream, chosen);
     float *pm, *pS, *pW;
     carve(g.ws, B, H, n_q, d_v, C, &pm, &pS, &pW);
     const int rc = run_forward_dv(q, k, v, nullptr, nullptr, pm, pS, pW, B, H, n_q, n_k, d, d_v, scale, causal, kv_len,
-                                  C, 1, dtype, stream);
+                                  C, 1, dtype, stream, chosen);
     if (rc != ELSA_OK) return rc;
     if (g.opt[ELSA_OPT_DRY_RUN]) return ELSA_OK;
     elsa::CombineParams cp{pm, pS, pW, out, lse, (long long)B * H * n_q, n_q, C, 0, dtype == ELSA_F16};

@@ -100,6 +100,16 @@ def test_key_chunks_stay_few_and_causal_launches_of_two_runs_are_not_cut():
     assert plan(1, 12, 12288, 12288, 64, ws_mib=256) != ("mfma_q128_k32", 1)
 
 
+def test_value_width_entry_point_uses_the_same_model():
+    # (measured before -> after, us)  FP16 d = 64, d_v = 128, H = 8, n = 4096 causal: 98.7 -> 57.9; FP32 d = 64, d_v = 128, H = 40, n = 2048: 600 -> 534
+    assert plan(1, 8, 4096, 4096, 64, dv=128, dtype=1, causal=True) == ("mfma16_dv_xwave", 1)
+    assert plan(1, 40, 2048, 2048, 64, dv=128, ws_mib=256) == ("mfma_dv_q128", 2)
+    assert plan(1, 16, 16384, 16384, 64, dv=128, ws_mib=256) == ("mfma_dv_q128", 1)
+    assert plan(1, 16, 8192, 8192, 192, dv=128, dtype=1, causal=True) == ("mfma16_dv_q128", 1)
+    assert plan(1, 40, 2048, 2048, 192, dv=128, dtype=1) == ("mfma16_dv_q128", 1)
+    assert plan(1, 16, 2048, 2048, 64, dv=128, ws_mib=256, variant=1, splits=1) == ("mfma_dv_q128", 1)   # forced: no model
+
+
 def test_window_attention_takes_the_lds_free_tile():
     assert plan(512, 3, 49, 49, 32) == ("mfma_small_q32", 1)
     assert plan(392, 3, 64, 64, 32) == ("mfma_small_q32", 1)
