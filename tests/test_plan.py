@@ -110,6 +110,22 @@ def test_value_width_entry_point_uses_the_same_model():
     assert plan(1, 16, 2048, 2048, 64, dv=128, ws_mib=256, variant=1, splits=1) == ("mfma_dv_q128", 1)   # forced: no model
 
 
+def plan_varlen(num_seqs, total, max_len, H, d, causal=False, dtype=0):
+    rc = elsa.raw().elsa_attn_fwd_varlen(P, P, P, P, P, num_seqs, total, max_len, H, d, 0.125, int(causal), dtype, None)
+    assert rc == 0, elsa.status_string(rc)
+    return elsa.elsa_last_kernel(), elsa.elsa_last_splits()
+
+
+def test_packed_batches_take_the_64_row_tile_only_when_causal_and_long_enough():
+    # the paper's padding-free workload: 8 sequences, lengths U[256,1792] (about 8 x 1024 tokens), H = 12, d = 64
+    assert plan_varlen(8, 8192, 1792, 12, 64) == ("mfma_q128_k32", 1)
+    assert plan_varlen(8, 8192, 1792, 12, 64, causal=True) == ("mfma_q64_xw2", 1)
+    assert plan_varlen(8, 8192, 1792, 12, 64, causal=True, dtype=1) == ("mfma16_q64_xw2", 1)
+    assert plan_varlen(32, 9000, 512, 12, 64, causal=True) == ("mfma_q128_k32", 1)          # short sequences
+    assert plan_varlen(8, 8192, 1792, 32, 128, causal=True) == ("mfma_q128_w4", 1)          # d = 128
+    assert plan_varlen(8, 65536, 16384, 16, 64, causal=True) == ("mfma_q128_k32", 1)        # many runs of blocks
+
+
 def test_window_attention_takes_the_lds_free_tile():
     assert plan(512, 3, 49, 49, 32) == ("mfma_small_q32", 1)
     assert plan(392, 3, 64, 64, 32) == ("mfma_small_q32", 1)
