@@ -94,6 +94,7 @@ TileChoice play_through(const TileShape *shapes, int nshapes, double dscale, uns
     for (int si = 0; si < nshapes; ++si) {
         const TileShape &sh = shapes[si];
         if (fp16_tiles && sh.rows == 256 && causal) continue;   // its diagonal tiles waste twice as much (measured: never the best under a causal mask)
+        if (!fp16_tiles && sh.variant == 13 && nk < 1024) continue;   // the single-buffered tile pays from about sixteen 64-key tiles per block up
         const int q_tiles = (n + sh.rows - 1) / sh.rows;
         for (int C = 1; C <= max_splits; ++C) {
             if (C > 1 && (((no_cut >> si) & 1u) || nk / C < 256)) break;
@@ -109,8 +110,11 @@ TileChoice play_through(const TileShape *shapes, int nshapes, double dscale, uns
                 const int vis = hi - c * chunk;
                 return vis > 0 ? (vis + 32 * sh.key_waves - 1) / (32 * sh.key_waves) : 0;
             };
-            // per-block cost in steps; a tile that owns its CU pays its prologue itself
-            const double own = sh.resident == 1 ? prologue / (sh.t1 * dscale) : 0.0;
+            // per-block cost in steps: a tile that owns its CU pays its prologue itself; co-resident blocks hide most of each
+            // other's, what is left (Q fragments, first tile, epilogue; the merge of the key waves' states) was measured on
+            // batches of short sequences: about 0.9 us per block at d = 64, 1.3 us when the waves split the keys, growing with d
+            const double own = sh.resident == 1 ? prologue / (sh.t1 * dscale)
+                                                : (sh.key_waves > 1 ? 1.3 : 0.9) * (0.5 + dw / 128.0) / (sh.t2 * dscale);
             std::fill(cu, cu + kNumCu, 0.0);
             int heap_n = 0;
             const long long placed = (long long)sh.resident * kNumCu;

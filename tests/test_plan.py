@@ -82,7 +82,7 @@ def test_small_problems_follow_the_block_placement_model():
     assert plan(1, 16, 1024, 1024, 64, ws_mib=64, variant=7) == ("mfma_q128_k32", 2)
     assert plan(1, 16, 1024, 1024, 64, ws_mib=64, splits=3)[1] == 3
     # FP16 tiles are not cut outside decoding
-    assert plan(1, 16, 1024, 1024, 64, dtype=1, ws_mib=64) == ("mfma16_xwave", 1)
+    assert plan(1, 16, 1024, 1024, 64, dtype=1, ws_mib=64) in (("mfma16_xwave", 1), ("mfma16_q64_xw2", 1))   # 14.8 / 15.3 us
 
 
 def test_key_chunks_stay_few_and_causal_launches_of_two_runs_are_not_cut():
