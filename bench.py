@@ -151,13 +151,16 @@ def tile_sweep(a):
     f32_narrow = [(2, 7, 1), (2, 7, 2), (2, 7, 4), (2, 11, 1), (2, 11, 2), (2, 3, 1)]
     f32_wide = [(2, 1, 1), (2, 1, 2), (2, 1, 4), (2, 11, 1), (2, 11, 2), (2, 13, 1)]
     f16 = [(3, 1, 1), (3, 2, 1), (3, 3, 1), (3, 4, 1)]
+    f32_other = [(2, 1, 1), (2, 1, 2), (2, 1, 4), (2, 3, 1), (2, 3, 2)]       # d = 96, 256: the 128-row tile and (d = 96) the key-splitting one
     shapes = [(1, 16, n, 64, False) for n in (256, 512, 768, 1024, 1536, 2048, 3072)] + \
              [(B, 12, 197, 64, False) for B in (1, 4, 8, 16)] + [(1, 32, 1024, 32, False), (1, 8, 2048, 64, False), (1, 8, 4096, 64, False)] + \
              [(1, 40, n, 128, False) for n in (256, 512, 1024, 2048)] + [(1, 16, 1024, 128, False), (1, 32, 1536, 128, False), (1, 16, 3072, 128, False), (1, 24, 2048, 128, False)] + \
-             [(1, 16, n, 64, True) for n in (1024, 2048, 3072, 4096, 8192)] + [(4, 12, 197, 64, True), (1, 8, 4096, 64, True), (1, 16, 2048, 128, True), (1, 8, 4096, 128, True), (1, 40, 1024, 128, True)]
+             [(1, 16, n, 64, True) for n in (1024, 2048, 3072, 4096, 8192)] + [(4, 12, 197, 64, True), (1, 8, 4096, 64, True), (1, 16, 2048, 128, True), (1, 8, 4096, 128, True), (1, 40, 1024, 128, True)] + \
+             [(1, H, n, d, f) for f in (False, True) for d in (96, 256) for (H, n) in ((16, 2048), (32, 1024), (8, 2048))] + \
+             [(B, 12, n, 64, f) for f in (False, True) for (B, n) in ((16, 128), (16, 512), (64, 128), (8, 512))]   # batches of short sequences
     rows = []
     for (B, H, n, d, fp16) in shapes:
-        forced = f16 if fp16 else (f32_wide if d == 128 else f32_narrow)
+        forced = f16 if fp16 else (f32_wide if d == 128 else f32_other if d in (96, 256) else f32_narrow)
         for causal in (False, True):
             us, kern, C = run(B, H, n, d, causal, fp16, 0, 0, 0)
             alts = {}
