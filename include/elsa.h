@@ -29,9 +29,12 @@
  *     Arguments are validated before anything is launched.
  *   - Results are deterministic: no atomics; two calls on the same inputs with
  *     the same options are bit-identical.
- *   - Host threads.  Options, the lent workspace, the record of the last launch and the cache of
- *     the last tile choice are process-wide and unguarded: calls from different host threads must
- *     be serialised by the caller.  (Streams are the unit of concurrency on the device.)
+ *   - Host threads.  Options (elsa_set_option), the lent workspace (elsa_set_workspace), the record
+ *     of the last launch (elsa_last_kernel, elsa_last_splits) and the cache of the last tile choice
+ *     are kept PER HOST THREAD: a new thread starts from the defaults with no workspace, and nothing
+ *     one thread sets is seen by another, so threads that drive their own streams need no lock.
+ *     The entry points are reentrant apart from that state.  Two calls that may run at the same time
+ *     on the device (different streams) must not use the same workspace: lend one per thread.
  *   - Masks.  causal != 0: key j is visible to query i iff j <= i.  kv_len
  *     (device int32 [B], may be NULL): key j of batch b is visible iff
  *     j < kv_len[b]; values are clamped to [0, n]; query rows beyond kv_len are
@@ -200,13 +203,15 @@ size_t elsa_split_kv_workspace_bytes(int B, int H, int n, int d, int num_splits)
 /*
  * Lend the library a device buffer (256-byte aligned) that elsa_attn_fwd[_masked]
  * may use to split the key range when B*H*ceil(n/T_q) is too small to fill the
- * GPU.  Pass (NULL, 0) to withdraw it.  The buffer is shared by all later calls:
- * calls that overlap on different streams must not both use it.
+ * GPU.  Pass (NULL, 0) to withdraw it.  The buffer belongs to the calling host thread's
+ * later calls (other threads do not see it) and to the device that is current now: calls made
+ * while another device is current run without it.  Calls of this thread that overlap on
+ * different streams must not both use it.
  */
 int elsa_set_workspace(void *dev_ptr, size_t bytes);
 
 /*
- * Measurement / tuning knobs (process-wide, not thread-safe).  Defaults are 0.
+ * Measurement / tuning knobs (per host thread).  Defaults are 0.
  *   ELSA_OPT_PATH     0 = auto (FP32 I/O: FP32 MFMA; FP16 I/O: FP16 MFMA with FP32 state; one to
  *                     four queries per (batch, head), eight for FP32 at d >= 128: the FP32 vector
  *                     kernel that streams K and V),

@@ -124,11 +124,17 @@ int elsa_oracle_lse_rows(const float *q, const float *k,
     return 0;
 }
 
+/* Eq. 3, declared here for the fold below; defined with the other merge forms further down. */
+void elsa_oracle_merge_case(double ma, double Sa, const double *Wa,
+                            double mb, double Sb, const double *Wb, int d,
+                            double *mo, double *So, double *Wo);
+
 /*
- * Per-query sequential formulation (Alg. 1): start from the identity
- * (-inf, 0, 0); for each key either keep the maximum and add exp(s - m) (max
- * unchanged), or move the maximum to s, rescale the past by exp(m_old - s) and
- * add weight 1 (new maximum); finish with y = W_n / S_n.
+ * Per-query sequential evaluation (Alg. 1) as what it is in the monoid's terms: the running
+ * state starts at the identity e = (-inf, 0, 0) and absorbs the keys one at a time,
+ *     u <- u (+) (s_j, 1, v_j),
+ * each key lifted to its one-element state (Sec. 3.2) and merged with the operator of Eq. 3;
+ * the output is W / S of the final state (zeros for a row that saw no key).
  */
 int elsa_oracle_fold_rows(const float *q, const float *k, const float *v,
                           int B, int H, int n, int d, double scale, int causal,
@@ -136,35 +142,31 @@ int elsa_oracle_fold_rows(const float *q, const float *k, const float *v,
                           const int64_t *rows, int64_t nrows, double *out)
 {
     (void)B;
-    double *W = (double *)malloc(sizeof(double) * (size_t)(d > 0 ? d : 1));
-    if (!W) return -1;
+    size_t dd = (size_t)(d > 0 ? d : 1);
+    double *buf = (double *)malloc(sizeof(double) * dd * 3);
+    if (!buf) return -1;
+    double *Wrun = buf, *Wkey = buf + dd, *Wnext = buf + 2 * dd;
     for (int64_t r = 0; r < nrows; ++r) {
         int64_t row = rows[r];
         int64_t i = row % n, bh = row / n, b = bh / H;
         const float *qi = q + (size_t)row * d;
-        const float *kb = k + (size_t)bh * n * d;
-        const float *vb = v + (size_t)bh * n * d;
-        double *o = out + (size_t)r * d;
+        const float *keys = k + (size_t)bh * n * d;
+        const float *vals = v + (size_t)bh * n * d;
         int64_t L = visible_keys(i, n, causal, kv_len, b);
-        double m = -INFINITY, S = 0.0;
-        for (int t = 0; t < d; ++t) W[t] = 0.0;
+        double m_run = -INFINITY, S_run = 0.0;                 /* u = e */
+        for (int t = 0; t < d; ++t) Wrun[t] = 0.0;
         for (int64_t j = 0; j < L; ++j) {
-            double sj = score(qi, kb + (size_t)j * d, d, scale);
-            const float *vj = vb + (size_t)j * d;
-            if (m >= sj) {
-                double alpha = exp(sj - m);
-                S += alpha;
-                for (int t = 0; t < d; ++t) W[t] += alpha * (double)vj[t];
-            } else {
-                double beta = exp(m - sj);  /* exp(-inf) = 0 on the first key */
-                m = sj;
-                S = S * beta + 1.0;
-                for (int t = 0; t < d; ++t) W[t] = W[t] * beta + (double)vj[t];
-            }
+            double m_next, S_next;
+            for (int t = 0; t < d; ++t) Wkey[t] = (double)vals[(size_t)j * d + t];
+            elsa_oracle_merge_case(m_run, S_run, Wrun,
+                                   score(qi, keys + (size_t)j * d, d, scale), 1.0, Wkey, d,
+                                   &m_next, &S_next, Wnext);
+            m_run = m_next; S_run = S_next;
+            memcpy(Wrun, Wnext, sizeof(double) * (size_t)d);
         }
-        for (int t = 0; t < d; ++t) o[t] = (L > 0) ? W[t] / S : 0.0;
+        for (int t = 0; t < d; ++t) out[(size_t)r * d + t] = (S_run > 0.0) ? Wrun[t] / S_run : 0.0;
     }
-    free(W);
+    free(buf);
     return 0;
 }
 
@@ -402,12 +404,31 @@ int elsa_oracle_dv_rows(const float *q, const float *k, const float *v,
 }
 
 /*
- * FP32 ladder (diagnostic only): the sequential fold of Alg. 1 carried out
- * entirely in IEEE single precision (float products, float sums, expf).  It
- * shows what error any FP32-accumulating evaluation carries on a given input,
- * so that a tolerance violation can be attributed to the conditioning of the
- * metric rather than to a kernel defect.  out: [nrows][d] floats.
+ * FP32 ladder (diagnostic only): the same key-by-key absorption u <- u (+) (s_j, 1, v_j) of
+ * Alg. 1 with every product, sum and exponential in IEEE single precision.  It shows what error
+ * any FP32-accumulating evaluation carries on a given input, so that a tolerance violation can be
+ * attributed to the conditioning of the metric rather than to a kernel defect.
+ * out: [nrows][d] floats.
  */
+static float f32_mul(float a, float b) { volatile float p = a * b; return p; }   /* volatile: one rounding, no contraction */
+static float f32_add(float a, float b) { volatile float p = a + b; return p; }
+
+/* Eq. 3 in single precision, in place on the running state (m, S, W); the other operand is (mk, Sk, Wk). */
+static void merge_case_f32(float *m, float *S, float *W, float mk, float Sk, const float *Wk, int d)
+{
+    if (*m == -INFINITY && mk == -INFINITY) return;            /* e (+) e = e */
+    if (*m >= mk) {
+        float f = expf(mk - *m);
+        *S = f32_add(*S, f32_mul(Sk, f));
+        for (int t = 0; t < d; ++t) W[t] = f32_add(W[t], f32_mul(Wk[t], f));
+    } else {
+        float f = expf(*m - mk);
+        *S = f32_add(Sk, f32_mul(*S, f));
+        for (int t = 0; t < d; ++t) W[t] = f32_add(Wk[t], f32_mul(W[t], f));
+        *m = mk;
+    }
+}
+
 int elsa_ladder_f32_fold_rows(const float *q, const float *k, const float *v,
                               int B, int H, int n, int d, float scale, int causal,
                               const int32_t *kv_len,
@@ -420,30 +441,17 @@ int elsa_ladder_f32_fold_rows(const float *q, const float *k, const float *v,
         int64_t row = rows[r];
         int64_t i = row % n, bh = row / n, b = bh / H;
         const float *qi = q + (size_t)row * d;
-        const float *kb = k + (size_t)bh * n * d;
-        const float *vb = v + (size_t)bh * n * d;
-        float *o = out + (size_t)r * d;
+        const float *keys = k + (size_t)bh * n * d;
+        const float *vals = v + (size_t)bh * n * d;
         int64_t L = visible_keys(i, n, causal, kv_len, b);
         float m = -INFINITY, S = 0.0f;
         for (int t = 0; t < d; ++t) W[t] = 0.0f;
         for (int64_t j = 0; j < L; ++j) {
-            const float *kj = kb + (size_t)j * d;
-            const float *vj = vb + (size_t)j * d;
-            volatile float acc = 0.0f;          /* volatile: forbid FMA contraction / widening */
-            for (int t = 0; t < d; ++t) { volatile float p = qi[t] * kj[t]; acc = acc + p; }
-            float sj = scale * acc;
-            if (m >= sj) {
-                float alpha = expf(sj - m);
-                S += alpha;
-                for (int t = 0; t < d; ++t) { volatile float p = alpha * vj[t]; W[t] = W[t] + p; }
-            } else {
-                float beta = expf(m - sj);
-                m = sj;
-                S = S * beta + 1.0f;
-                for (int t = 0; t < d; ++t) { volatile float p = W[t] * beta; W[t] = p + vj[t]; }
-            }
+            float dot = 0.0f;
+            for (int t = 0; t < d; ++t) dot = f32_add(dot, f32_mul(qi[t], keys[(size_t)j * d + t]));
+            merge_case_f32(&m, &S, W, f32_mul(scale, dot), 1.0f, vals + (size_t)j * d, d);
         }
-        for (int t = 0; t < d; ++t) o[t] = (L > 0) ? W[t] / S : 0.0f;
+        for (int t = 0; t < d; ++t) out[(size_t)r * d + t] = (L > 0) ? W[t] / S : 0.0f;
     }
     free(W);
     return 0;

@@ -11,6 +11,8 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libelsa.so")
 SOURCES = ["elsa_api.hip", "elsa_fwd_mfma.hip", "elsa_fwd_mfma_f16.hip", "elsa_fwd_fma.hip", "elsa_fwd_small.hip", "elsa_fwd_decode.hip", "elsa_combine.hip",
            "elsa_fwd_dv.hip", "elsa_fwd_dv_f16.hip"]
+HOST_SOURCES = ["elsa_plan.cpp"]       # plain C++ (launch planning): also built under sanitizers by a CPU test
+HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-Wextra"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument",
@@ -50,8 +52,8 @@ def build_library(verbose: bool = False) -> str:
     hipcc = _hipcc()
 
     def compile_one(src):
-        obj = os.path.join(objdir, src.replace(".hip", ".o"))
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        obj = os.path.join(objdir, src.replace(".hip", ".o").replace(".cpp", ".o"))
+        cmd = [hipcc, *(HOST_FLAGS if src in HOST_SOURCES else FLAGS), "-c", os.path.join(CSRC, src), "-o", obj]
         r = subprocess.run(cmd, capture_output=True, text=True)
         remarks = [l for l in r.stderr.splitlines() if "kernel-resource-usage" in l]
         err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l and "kernel-resource-usage" not in l)
@@ -64,7 +66,7 @@ def build_library(verbose: bool = False) -> str:
 
     usage = {}
     with ThreadPoolExecutor(max_workers=8) as ex:
-        objs = list(ex.map(compile_one, SOURCES))
+        objs = list(ex.map(compile_one, SOURCES + HOST_SOURCES))
     with open(RESOURCES, "w") as f:            # one line per kernel: source, mangled name, VGPRs, AGPRs, scratch bytes per lane, waves per SIMD
         for src in SOURCES:
             for row in usage[src]:

@@ -116,8 +116,10 @@ MUTATIONS = [
     ("padding ignored", "int64_t lim = kv_len ? (int64_t)kv_len[b] : n;", "int64_t lim = n;"),
     ("values read from the wrong key", "            const float *vj = vb + (size_t)j * d;\n            for (int t = 0; t < d; ++t) o[t] += e",
      "            const float *vj = vb + (size_t)(L - 1 - j) * d;\n            for (int t = 0; t < d; ++t) o[t] += e"),
-    ("fold: past not rescaled", "S = S * beta + 1.0;", "S = S + 1.0;"),
-    ("fold: weight of an old maximum", "double alpha = exp(sj - m);", "double alpha = exp(m - sj);"),
+    ("fold: running maximum not carried", "m_run = m_next; S_run = S_next;", "S_run = S_next;"),
+    ("fold: key lifted with weight 0", "d, scale), 1.0, Wkey, d,", "d, scale), 0.0, Wkey, d,"),
+    ("fold: key lifted with the wrong value row", "Wkey[t] = (double)vals[(size_t)j * d + t];", "Wkey[t] = (double)vals[(size_t)i * d + t];"),
+    ("merge: past not rescaled when the maximum moves", "*mo = mb; *So = Sb + Sa * f;", "*mo = mb; *So = Sb + Sa;"),
     ("merge: factor inverted", "double f = exp(mb - ma);", "double f = exp(ma - mb);"),
     ("merge: un-sum without renorm", "*So = (Sa * ea + Sb * eb) * em;", "*So = (Sa * ea + Sb * eb);"),
     ("chunk bound shifted", "int64_t lo = (int64_t)c * chunk, hi = lo + chunk;", "int64_t lo = (int64_t)c * chunk + 1, hi = lo + chunk;"),
@@ -136,7 +138,7 @@ MUTATIONS = [
     ("own value width: diagonal off by one", "int64_t diag = i + ((int64_t)nk - (int64_t)nq) + 1;", "int64_t diag = i + ((int64_t)nk - (int64_t)nq);"),
     ("own value width: padding ignored", "int64_t vis = kv_len ? (int64_t)kv_len[b] : nk;", "int64_t vis = nk;"),
     ("own value width: weights without their maximum in the log-normaliser", "if (lse) lse[r] = top + log(Z);", "if (lse) lse[r] = log(Z);"),
-    ("single-precision ladder: past not rescaled", "S = S * beta + 1.0f;", "S = S + 1.0f;"),
+    ("single-precision ladder: past not rescaled", "*S = f32_add(Sk, f32_mul(*S, f));", "*S = f32_add(Sk, *S);"),
 ]
 
 
