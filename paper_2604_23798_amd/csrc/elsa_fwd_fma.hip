@@ -94,8 +94,10 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
         for (int t = 0; t < D; ++t) W[t] *= alpha;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const int key = min(j0 + g, wi.nk - 1);
-            const T *__restrict__ vj = vp + (long long)key * ts;
+            // a key at or beyond the wave's range is the identity for every row: it is skipped, not multiplied
+            // by a zero weight (its value row may be padding that holds anything, NaN and Inf included)
+            if (j0 + g >= wend) break;
+            const T *__restrict__ vj = vp + (long long)(j0 + g) * ts;
 #pragma unroll
             for (int t = 0; t < D; ++t) W[t] = fmaf(e[g], ld_uniform(vj, t), W[t]);
         }
