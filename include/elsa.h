@@ -211,6 +211,28 @@ size_t elsa_split_kv_workspace_bytes(int B, int H, int n, int d, int num_splits)
 int elsa_set_workspace(void *dev_ptr, size_t bytes);
 
 /*
+ * For callers that cannot allocate or lend device memory (code under HIP-graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): elsa_attn_fwd_masked with the internal key split, the chunk
+ * states of which live in a device array that is part of the library itself
+ * (ELSA_STATIC_SCRATCH_BYTES, one copy per GPU, held until the process ends) instead of a lent
+ * workspace.  Tensors, masks, dtype, stream and results as elsa_attn_fwd_masked.
+ *   num_splits  0: the library chooses tile and key chunks exactly as it does for a lent workspace of
+ *               that size (a single pass for problems that fill the GPU by themselves);
+ *               1: single pass;  > 1: that many key chunks, ELSA_ERR_WORKSPACE if
+ *               elsa_split_kv_workspace_bytes(B, H, n, d, num_splits) exceeds the array.
+ * Calls nothing that allocates.  The array's device address is looked up on the first call on a device
+ * (hipGetSymbolAddress), so call once before a stream capture.  All calls on one GPU share the array:
+ * calls that may overlap on the device (different streams, different host threads) race on it and must
+ * be ordered by the caller.  Nothing needs clearing between calls (every state read was written by the
+ * same call).  Errors otherwise as elsa_attn_fwd_masked; ELSA_ERR_INVALID_ARG for num_splits < 0 or > n.
+ */
+#define ELSA_STATIC_SCRATCH_BYTES (64u << 20)
+size_t elsa_static_scratch_bytes(void);
+int elsa_attn_fwd_static(const void *q, const void *k, const void *v, void *out,
+                         int B, int H, int n, int d, float scale, int causal,
+                         const int32_t *kv_len, int num_splits, int dtype, void *stream);
+
+/*
  * Measurement / tuning knobs (per host thread).  Defaults are 0.
  *   ELSA_OPT_PATH     0 = auto (FP32 I/O: FP32 MFMA; FP16 I/O: FP16 MFMA with FP32 state; one to
  *                     four queries per (batch, head), eight for FP32 at d >= 128: the FP32 vector

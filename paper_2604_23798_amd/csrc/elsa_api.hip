@@ -1,9 +1,15 @@
 // C ABI of libelsa: argument checks, configuration choice, launches.  No allocation, no sync.
+#include <atomic>
 #include <cmath>
 
 #include "../../include/elsa.h"
 #include "elsa_common.hpp"
 #include "elsa_plan.hpp"
+
+// Scratch of elsa_attn_fwd_static: the chunk states (part_m | part_S | part_W) of one call at a time.
+// Every GPU the library runs on holds its own copy of the array, at its own address, until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress.
+static __device__ __align__(256) unsigned char scratch[ELSA_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -276,6 +282,28 @@ void carve(void *ws, int B, int H, int n, int d, int C, float **pm, float **pS, 
     (void)d;
 }
 
+// ---- the static scratch array (declared at file scope above): its address is looked up once per device,
+// with that device current, and kept; kernels and copies take that address, never the array's name.
+std::atomic<void *> scratch_ptr[elsa::kMaxDevices];    // zero-initialised; a lost race stores the same address twice
+
+int static_scratch(void **ptr) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= elsa::kMaxDevices) {
+        (void)hipGetLastError();
+        return ELSA_ERR_HIP;
+    }
+    void *p = scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return ELSA_ERR_HIP;
+        }
+        scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return ELSA_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -350,6 +378,28 @@ int elsa_attn_fwd_masked(const void *q, const void *k, const void *v, void *out,
                          const int32_t *kv_len, int dtype, void *stream) {
     const size_t wb = usable_ws_bytes();
     return attn_fwd_impl(q, k, v, out, nullptr, B, H, n, d, scale, causal, kv_len, dtype, stream, 0, wb ? g.ws : nullptr, wb);
+}
+
+size_t elsa_static_scratch_bytes(void) { return (size_t)ELSA_STATIC_SCRATCH_BYTES; }
+
+int elsa_attn_fwd_static(const void *q, const void *k, const void *v, void *out,
+                         int B, int H, int n, int d, float scale, int causal,
+                         const int32_t *kv_len, int num_splits, int dtype, void *stream) {
+    if (!q || !k || !v || !out) return ELSA_ERR_INVALID_ARG;
+    if (!std::isfinite(scale)) return ELSA_ERR_INVALID_ARG;
+    const int rc = check_common(B, H, n, d, dtype);
+    if (rc != ELSA_OK) return rc;
+    if (num_splits < 0 || num_splits > n || num_splits > kMaxSplits) return ELSA_ERR_INVALID_ARG;
+    // a requested chunk count whose states do not fit the array is an error, never a silent fallback
+    if (num_splits > 1 && elsa_split_kv_workspace_bytes(B, H, n, d, num_splits) > (size_t)ELSA_STATIC_SCRATCH_BYTES)
+        return ELSA_ERR_WORKSPACE;
+    void *ws = nullptr;
+    if (g.opt[ELSA_OPT_DRY_RUN]) ws = reinterpret_cast<void *>(256);    // a plan touches no memory
+    else if (const int e = static_scratch(&ws); e != ELSA_OK) return e;
+    // Nothing in the array has to start at zero: the first pass writes the state of every (row, chunk),
+    // the identity for chunks that a mask empties, before the combine pass reads it.
+    return attn_fwd_impl(q, k, v, out, nullptr, B, H, n, d, scale, causal, kv_len, dtype, stream, 0, ws,
+                         (size_t)ELSA_STATIC_SCRATCH_BYTES, num_splits);
 }
 
 int elsa_attn_fwd_lse(const void *q, const void *k, const void *v, void *out, float *lse,

@@ -18,7 +18,7 @@ OPT_PATH, OPT_VARIANT, OPT_SPLITS, OPT_XCD_MAP, OPT_SNAKE, OPT_DRY_RUN = 0, 1, 2
 PATH_AUTO, PATH_FMA, PATH_MFMA, PATH_MFMA16 = 0, 1, 2, 3
 OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 
-EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_lse", "elsa_attn_fwd_cross", "elsa_attn_fwd_dv", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
+EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_static", "elsa_static_scratch_bytes", "elsa_attn_fwd_lse", "elsa_attn_fwd_cross", "elsa_attn_fwd_dv", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
            "elsa_stream_state_bytes", "elsa_attn_stream_step", "elsa_attn_stream_finish",
            "elsa_split_kv_workspace_bytes", "elsa_set_workspace", "elsa_set_option", "elsa_get_option",
            "elsa_variant_name", "elsa_last_kernel", "elsa_last_splits", "elsa_status_string", "elsa_debug_layout_probe")
@@ -31,6 +31,8 @@ _lib = ctypes.CDLL(LIB_PATH)
 _vp, _i, _f = ctypes.c_void_p, ctypes.c_int, ctypes.c_float
 _lib.elsa_attn_fwd.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _i, _vp]
 _lib.elsa_attn_fwd_masked.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
+_lib.elsa_attn_fwd_static.argtypes = [_vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _i, _vp]
+_lib.elsa_static_scratch_bytes.restype = ctypes.c_size_t
 _lib.elsa_attn_fwd_lse.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
 _lib.elsa_attn_fwd_cross.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
 _lib.elsa_attn_fwd_dv.argtypes = [_vp, _vp, _vp, _vp, _vp, _i, _i, _i, _i, _i, _i, _f, _i, _vp, _i, _vp]
@@ -122,6 +124,22 @@ def elsa_attn_fwd_masked(q, k, v, out, scale, causal=False, kv_len=None, stream=
     _check(_lib.elsa_attn_fwd_masked(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, n, d, float(scale),
                                      int(bool(causal)), _ptr(kv_len), _dtype_code(q), _stream(stream, q)))
     return out
+
+
+def elsa_attn_fwd_static(q, k, v, out, scale, causal=False, kv_len=None, num_splits=0, stream=None):
+    """elsa_attn_fwd_masked whose key split keeps its chunk states in the library's own device array."""
+    import torch
+    B, H, n, d = _shape(q, k, v)
+    assert out.is_contiguous() and out.shape == q.shape and out.dtype == q.dtype
+    if kv_len is not None:
+        assert kv_len.is_cuda and kv_len.dtype == torch.int32 and kv_len.shape == (B,) and kv_len.is_contiguous()
+    _check(_lib.elsa_attn_fwd_static(_ptr(q), _ptr(k), _ptr(v), _ptr(out), B, H, n, d, float(scale), int(bool(causal)),
+                                     _ptr(kv_len), int(num_splits), _dtype_code(q), _stream(stream, q)))
+    return out
+
+
+def elsa_static_scratch_bytes() -> int:
+    return int(_lib.elsa_static_scratch_bytes())
 
 
 def elsa_attn_fwd_lse(q, k, v, out, lse, scale, causal=False, kv_len=None, stream=None):
