@@ -27,37 +27,143 @@ PEAK_FP32_VALU_UNPACKED = 78.6  # plain v_fma_f32 (packed FP32 is disabled in th
 PEAK_FP16_TFLOPS = 2500.0       # MI355X dense FP16 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for a plain copy of known size in the same run (profiles/*_counters.md).
-MEASURED_TRAFFIC = {("sweep_n16384", "mfma_q128_k32"): 1.156e9, ("sweep_n16384", "mfma_q256_w4"): 6.606e8,
-                    ("decode_32k", "fma_decode_q1"): 2.685e9}
+# Keyed by (workload, kernel actually launched); the value names the summary the figure comes from.
+MEASURED_TRAFFIC = {("sweep_n16384", "mfma_q128_k32"): (1.156e9, "profiles/fwd_mfma_sweep_n16384_counters.md"),
+                    ("sweep_n16384", "mfma_q256_w4"): (6.606e8, "profiles/fwd_mfma_sweep_n16384_counters.md"),
+                    ("decode_32k", "fma_decode_q1"): (2.685e9, "profiles/fwd_decode_decode_32k.md")}
+# the other workloads, appended to the default run's JSON line as `configs` (each timed briefly after the headline)
+CONFIG_WORKLOADS = ["vit_b16_224", "bert_base", "bert_base_padded", "sweep_n1024", "sweep_n2048", "sweep_n4096", "sweep_n8192",
+                    "sweep_n1024_fp16", "sweep_n2048_fp16", "sweep_n4096_fp16", "sweep_n8192_fp16", "sweep_n16384_fp16",
+                    "llama13b_32k", "llama13b_32k_fp16", "hires_vit_64k"]
+
+
+def host_cores():
+    """(logical cores of the box, cores this process may run on)."""
+    try:
+        usable = len(os.sched_getaffinity(0))
+    except AttributeError:
+        usable = os.cpu_count() or 1
+    return os.cpu_count() or 1, usable
+
+
+def traffic_of(name, kernel):
+    t = MEASURED_TRAFFIC.get((name, kernel))
+    return (t[0], t[1]) if t else (None, None)
+
+
+def roof_of(kernel):
+    if kernel.startswith("fma"):
+        return "alu", PEAK_FP32_VALU_UNPACKED
+    if kernel.startswith("mfma16"):
+        return "mfma", PEAK_FP16_TFLOPS
+    return "mfma", PEAK_FP32_TFLOPS
+
+
+def spot_parity(w, q, k, v, kv_len, gpu_out, per_head):
+    """Oracle and CPU ladder on a seeded row sample of the workload; error measures of the GPU output against
+    the oracle, plus the literal-tolerance violations of the ladder on the same rows.  Returns (parity, seconds
+    the FP64 oracle took, visible-key flops of the sample)."""
+    import numpy as np
+    import oracle
+    from paper_2604_23798_amd import inputs
+    from paper_2604_23798_amd.metrics import ladder_check, metrics, passes, tolerance
+    rows = inputs.sample_rows(w, per_head=per_head)
+    f32 = lambda t: t.astype(np.float32)
+    qq, kk, vv = f32(q), f32(k), f32(v)
+    oracle.attn_rows(qq, kk, vv, w.scale, causal=w.causal, kv_len=kv_len, rows=rows[:2])   # page in
+    t0 = time.perf_counter()
+    ref = oracle.attn_rows(qq, kk, vv, w.scale, causal=w.causal, kv_len=kv_len, rows=rows)
+    dt = time.perf_counter() - t0
+    if w.fp16:
+        lad = oracle.ladder_f16_rows(qq, kk, vv, w.scale, causal=w.causal, kv_len=kv_len, rows=rows)
+    else:
+        lad = oracle.ladder_f32_fold_rows(qq, kk, vv, w.scale, causal=w.causal, kv_len=kv_len, rows=rows).astype(np.float64)
+    tol = tolerance(w.n, w.fp16)
+    par = metrics(gpu_out.reshape(-1, w.d)[rows], ref, tol)
+    ml = metrics(lad, ref, tol)
+    par.update({"tol": tol, "rows": int(rows.size), "pass": passes(par, tol), "e_elem_wellcond": par["e_well"],
+                "ladder": "fp16 weights and output" if w.fp16 else "fp32 fold", "ladder_frac_elem_viol": ml["frac_elem_viol"],
+                "ladder_e_elem": ml["e_elem"], "literal_form_as_ladder": ladder_check(par, ml)})
+    i = rows % w.n
+    vis = np.minimum(i + 1, w.n) if w.causal else np.full(rows.shape, w.n)
+    if kv_len is not None:
+        vis = np.minimum(vis, kv_len[rows // (w.n * w.H)])
+    return par, dt, float(4 * w.d * vis.sum())
+
+
+def bench_configs(names, launches, per_head):
+    """Time each workload briefly (library defaults, 256 MiB workspace lent, inputs resident) and spot-check it."""
+    import numpy as np
+    import torch
+    from paper_2604_23798_amd import elsa, inputs
+    out_rows = []
+    cache = {}
+    for name in names:
+        w = inputs.WORKLOADS[name]
+        base = name[:-5] if name.endswith("_fp16") else name
+        if base not in cache:                      # the FP16 variant is the same draw, rounded
+            cache.clear()
+            wb = inputs.WORKLOADS[base]
+            cache[base] = inputs.make(wb)
+        q, k, v, kv_len = cache[base]
+        if w.fp16:
+            q, k, v = (t.astype(np.float16) for t in (q, k, v))
+        tq, tk, tv = (torch.from_numpy(t).cuda() for t in (q, k, v))
+        tl = None if kv_len is None else torch.from_numpy(kv_len).cuda()
+        out = torch.full_like(tq, float("nan"))
+        step = lambda: elsa.elsa_attn_fwd_masked(tq, tk, tv, out, w.scale, w.causal, tl)
+        step()
+        torch.cuda.synchronize()
+        kernel, splits = elsa.elsa_last_kernel(), elsa.elsa_last_splits()
+        # short workloads: enough launches for 20 ms of work, so that one launch's latency is not the figure
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(); step(); e1.record(); torch.cuda.synchronize()
+        reps = max(launches, min(2000, int(20.0 / max(e0.elapsed_time(e1), 1e-3))))
+        for _ in range(min(reps, 50)):
+            step()
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            step()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        exec_flops = float(w.flops)
+        if w.causal:
+            exec_flops = 4.0 * w.B * w.H * w.d * (w.n * (w.n + 1) / 2)
+        elif kv_len is not None:
+            exec_flops = 4.0 * w.H * w.n * w.d * float(np.minimum(kv_len, w.n).sum())
+        bound, peak = roof_of(kernel)
+        achieved = exec_flops / (ms * 1e-3) / 1e12
+        rec = {"workload": name, "B": w.B, "H": w.H, "n": w.n, "d": w.d, "causal": bool(w.causal), "padded": bool(w.padded),
+               "dtype": "f16 io / f32 state" if w.fp16 else "f32", "kernel": kernel, "splits": splits, "launches": reps,
+               "ms": ms, "tflops": w.flops / (ms * 1e-3) / 1e12,
+               "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                            "flops_counted": "visible keys only" if (w.causal or kv_len is not None) else "4*B*H*n^2*d"}}
+        if per_head > 0:
+            assert bool(torch.isfinite(out).all()), name
+            par, _, _ = spot_parity(w, q, k, v, kv_len, out.double().cpu().numpy(), min(per_head, w.n))
+            rec["parity"] = par
+        out_rows.append(rec)
+        print("config %s: %s x%d %.4f ms %.1f TFLOP/s (%.3f of the %s roof)%s" % (
+            name, kernel, splits, ms, rec["tflops"], achieved / peak, bound,
+            "" if per_head <= 0 else " parity pass=%s" % rec["parity"]["pass"]), file=sys.stderr, flush=True)
+        del tq, tk, tv, out
+    return out_rows
+
+
 
 
 def cpu_baseline(w, q, k, v, kv_len, gpu_out, budget_rows):
     """Time the FP64 oracle (single thread, as it stands) on a bounded row sample of the same
     workload, and use the same rows as a parity spot check of the timed GPU output."""
-    import numpy as np
-    import oracle
-    from paper_2604_23798_amd import inputs
-    from tests.parity import metrics, tolerance
     per_head = max(2, budget_rows // (w.B * w.H))
-    rows = inputs.sample_rows(w, per_head=per_head)
-    f32 = lambda t: t.astype(np.float32)
-    qq, kk, vv = f32(q), f32(k), f32(v)
-    oracle.attn_rows(qq, kk, vv, w.scale, causal=w.causal, kv_len=kv_len, rows=rows[:4])   # page in
-    t0 = time.perf_counter()
-    ref = oracle.attn_rows(qq, kk, vv, w.scale, causal=w.causal, kv_len=kv_len, rows=rows)
-    dt = time.perf_counter() - t0
-    i = rows % w.n
-    vis = np.minimum(i + 1, w.n) if w.causal else np.full(rows.shape, w.n)
-    if kv_len is not None:
-        vis = np.minimum(vis, kv_len[rows // (w.n * w.H)])
-    flops = float(4 * w.d * vis.sum())
-    tol = tolerance(w.n, w.fp16)
-    par = metrics(gpu_out.reshape(-1, w.d)[rows], ref, tol)
-    par["tol"] = tol
-    par["pass"] = bool(par["e_row"] <= tol and par["e_mix"] <= tol)
-    base = {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
-            "sample": "%d query rows (%d per head: first, last, tile-boundary neighbours, random) of %s, "
-                      "all their keys, FP64 single thread, %.1f s" % (rows.size, per_head, w.name, dt)}
+    par, dt, flops = spot_parity(w, q, k, v, kv_len, gpu_out, per_head)
+    box, usable = host_cores()
+    base = {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "host_cores": box, "host_cores_usable": usable,
+            "kind": "oracle",
+            "sample": "%d query rows (%d per head: first, last, neighbours of 32/64/128/256-row boundaries, random) of %s, "
+                      "all their keys, FP64 single thread, %.1f s" % (par["rows"], per_head, w.name, dt)}
     return base, par
 
 
@@ -65,7 +171,7 @@ def cpu_baseline_varlen(q, k, v, cu, scale, gpu_out, fp16):
     """Oracle on the first heads of the packed batch (bounded), timed; parity on the same slice."""
     import numpy as np
     import oracle
-    from tests.parity import metrics
+    from paper_2604_23798_amd.metrics import metrics, passes
     hs = 2
     f32 = lambda t: np.ascontiguousarray(t[:, :hs].astype(np.float32))
     t0 = time.perf_counter()
@@ -76,8 +182,9 @@ def cpu_baseline_varlen(q, k, v, cu, scale, gpu_out, fp16):
     tol = 2e-3 if fp16 else 2e-5
     par = metrics(gpu_out[:, :hs].reshape(-1, q.shape[2]), ref.reshape(-1, q.shape[2]), tol)
     par["tol"] = tol
-    par["pass"] = bool(par["e_row"] <= tol and par["e_mix"] <= tol)
-    base = {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+    par["pass"] = passes(par, tol)
+    box, usable = host_cores()
+    base = {"value": flops / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "host_cores": box, "host_cores_usable": usable, "kind": "oracle",
             "sample": "all rows of the first %d heads of the packed batch, FP64 single thread, %.1f s" % (hs, dt)}
     return base, par
 
@@ -123,14 +230,14 @@ def tile_sweep(a):
     One JSON object: per shape the default's kernel / chunks / time, every forced time, and the
     ratio default / best forced."""
     import torch
-    from paper_2604_23798_amd import elsa
+    from paper_2604_23798_amd import elsa, inputs
     ws = torch.empty(256 << 20, dtype=torch.uint8, device="cuda")
     elsa.elsa_set_workspace(ws)
 
     def run(B, H, n, d, causal, fp16, path, variant, splits):
         dt = torch.float16 if fp16 else torch.float32
-        gen = torch.Generator(device="cuda").manual_seed(1300 + n + d)
-        q, k, v = (torch.randn(B, H, n, d, device="cuda", dtype=torch.float32, generator=gen).to(dt) for _ in range(3))
+        q, k, v = (torch.from_numpy(inputs.normal(1300 + n + d, st, 0, B * H * n * d).reshape(B, H, n, d)).cuda().to(dt)
+                   for st in (inputs.STREAM_Q, inputs.STREAM_K, inputs.STREAM_V))
         out = torch.empty_like(q)
         for o, val in ((elsa.OPT_PATH, path), (elsa.OPT_VARIANT, variant), (elsa.OPT_SPLITS, splits)):
             elsa.elsa_set_option(o, val)
@@ -220,6 +327,10 @@ def main():
                          "least-squares fit T(n) = a*L(n,128) + b*n^2 + c of the paper's scaling study")
     ap.add_argument("--tile-sweep", action="store_true",
                     help="small problems: the library's tile / chunk choice against forced configurations (about a minute)")
+    ap.add_argument("--configs", default="auto",
+                    help="after the headline, time the other workloads briefly and append them as `configs`: auto = all of "
+                         "them in the default run (no --workload / --path / --variant given), none, or a comma-separated list")
+    ap.add_argument("--config-rows", type=int, default=8, help="oracle rows per head of each `configs` entry (0 = no parity)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -368,6 +479,7 @@ def main():
     ms_step = wall * 1e3 / a.steps
     ms_kernel = ev0.elapsed_time(ev1) / a.steps
     kernel = elsa.elsa_last_kernel()
+    splits_used = elsa.elsa_last_splits()
     # per-launch spread, from a second pass with one event pair per step (not part of the figure above)
     n_lat = max(a.steps, 20)
     evs = [torch.cuda.Event(enable_timing=True) for _ in range(n_lat + 1)]
@@ -383,13 +495,9 @@ def main():
     # flops: 4 B H n^2 d, the square count the metric is defined on (sum of len^2 for packed batches)
     value = flops / (ms_step * 1e-3) / 1e12
     achieved = exec_flops / (ms_kernel * 1e-3) / 1e12
-    if kernel.startswith("fma"):
-        bound, peak = "alu", PEAK_FP32_VALU_UNPACKED
-    elif kernel.startswith("mfma16"):
-        bound, peak = "mfma", PEAK_FP16_TFLOPS
-    else:
-        bound, peak = "mfma", PEAK_FP32_TFLOPS
+    bound, peak = roof_of(kernel)
     name = a.workload
+    traffic, traffic_src = traffic_of(name, kernel)
     rec = {
         "metric": "FP32 attention TFLOP/s at n=16K, d=64 (4*B*H*n^2*d / time)" if name == "sweep_n16384"
         else "attention TFLOP/s (4*B*H*n^2*d / time)",
@@ -398,9 +506,9 @@ def main():
         "dtype": "f16 io / f32 state" if fp16 else "f32", "data": "synthetic",
         "pct_of_fp32_peak": 100.0 * value / PEAK_FP32_TFLOPS,
         "config": {"workload": name, "causal": bool(causal), "kernel": kernel, "path": a.path, "graph": bool(a.graph),
-                   "stream_chunks": a.stream_chunks, "splits": a.splits},
+                   "stream_chunks": a.stream_chunks, "splits": splits_used, "splits_requested": a.splits},
         "roofline": {"bound": bound, "achieved": achieved, "peak": peak, "unit": "TFLOP/s",
-                     "frac": achieved / peak, "traffic": MEASURED_TRAFFIC.get((name, kernel)),
+                     "frac": achieved / peak, "traffic": traffic, "traffic_source": traffic_src,
                      "kernel_ms": ms_kernel},
         "latency_ms": latency,
     }
@@ -411,7 +519,7 @@ def main():
         rec["value"], rec["unit"] = kv_bytes / (ms_step * 1e-3) / 1e9, "GB/s"
         rec["roofline"] = {"bound": "hbm", "achieved": kv_bytes / (ms_kernel * 1e-3) / 1e9, "peak": 8000.0,
                            "unit": "GB/s", "frac": kv_bytes / (ms_kernel * 1e-3) / 1e9 / 8000.0,
-                           "traffic": MEASURED_TRAFFIC.get((name, kernel)),
+                           "traffic": traffic, "traffic_source": traffic_src,
                            "kernel_ms": ms_kernel}
         rec["config"].update({"B": B, "H": H, "n_q": nq, "n_k": nk, "d": d})
         rec["tokens_per_s"] = B * nq / (ms_step * 1e-3)
@@ -441,7 +549,7 @@ def main():
             dt = time.perf_counter() - t0
             err = np.linalg.norm(host.reshape(-1, d)[rows] - ref, axis=1) / np.linalg.norm(ref, axis=1)
             base = {"value": rows.size * 2.0 * nk * d * (2 if fp16 else 4) / dt / 1e9, "unit": "GB/s", "cores": 1,
-                    "kind": "oracle", "sample": "%d of %d (batch, head) rows, all %d keys" % (rows.size, B * H, nk)}
+                    "host_cores": host_cores()[0], "kind": "oracle", "sample": "%d of %d (batch, head) rows, all %d keys" % (rows.size, B * H, nk)}
             par = {"rows": int(rows.size), "e_row": float(err.max())}
         elif dvw:
             import oracle
@@ -452,7 +560,7 @@ def main():
             dt = time.perf_counter() - t0
             err = np.linalg.norm(host.reshape(-1, dv)[rows] - ref, axis=1) / np.linalg.norm(ref, axis=1)
             vis = (rows % nq + 1).sum() if causal else rows.size * nk
-            base = {"value": 2.0 * (d + dv) * float(vis) / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "kind": "oracle",
+            base = {"value": 2.0 * (d + dv) * float(vis) / dt / 1e12, "unit": "TFLOP/s", "cores": 1, "host_cores": host_cores()[0], "kind": "oracle",
                     "sample": "%d of %d rows (evenly spaced), visible keys only" % (rows.size, B * H * nq)}
             par = {"rows": int(rows.size), "e_row": float(err.max())}
         elif varlen:
@@ -461,6 +569,15 @@ def main():
             base, par = cpu_baseline(w, q, k, v, kv_len, host, a.oracle_rows)
         rec["cpu_baseline"] = base
         rec["parity"] = par
+    default_run = (a.workload == "sweep_n16384" and a.path == "auto" and a.variant == 0 and a.splits == 0 and a.xcd_map == 0 and
+                   a.stream_chunks == 0 and not a.graph)
+    names = CONFIG_WORKLOADS if (a.configs == "auto" and default_run) else \
+        [] if a.configs in ("auto", "none", "") else [x for x in a.configs.split(",") if x]
+    if names:
+        del tq, tk, tv, out
+        for o in (elsa.OPT_PATH, elsa.OPT_VARIANT, elsa.OPT_XCD_MAP, elsa.OPT_SPLITS):
+            elsa.elsa_set_option(o, 0)
+        rec["configs"] = bench_configs(names, 5, a.config_rows)
     elsa.elsa_set_workspace(None)
     print(json.dumps(rec))
 

@@ -56,6 +56,9 @@ def _load():
         lib.elsa_oracle_cross_rows.argtypes = [fp, fp, fp, I, I, I, I, I, D, I, ip, lp, L, dp, dp]
         lib.elsa_oracle_dv_rows.argtypes = [fp, fp, fp, I, I, I, I, I, I, D, I, ip, lp, L, dp, dp]
         lib.elsa_ladder_f32_fold_rows.argtypes = [fp, fp, fp, I, I, I, I, ctypes.c_float, I, ip, lp, L, fp]
+        lib.elsa_ladder_f16_rows.argtypes = rows_sig
+        lib.elsa_oracle_round_f16.argtypes = [D]
+        lib.elsa_oracle_round_f16.restype = D
         _lib = lib
     return _lib
 
@@ -277,5 +280,22 @@ def ladder_f32_fold_rows(q, k, v, scale, causal=False, kv_len=None, rows=None):
     out = np.empty((rows.size, d), dtype=np.float32)
     rc = _load().elsa_ladder_f32_fold_rows(qp, kp, vp, B, H, n, d, float(scale), int(bool(causal)), klp,
                                            rp, rows.size, out.ctypes.data_as(ctypes.POINTER(ctypes.c_float)))
+    assert rc == 0
+    return out
+
+
+def round_f16(x: float) -> float:
+    """``x`` rounded to the nearest IEEE binary16 value (ties to even), as a Python float."""
+    return float(_load().elsa_oracle_round_f16(float(x)))
+
+
+def ladder_f16_rows(q, k, v, scale, causal=False, kv_len=None, rows=None):
+    """The definition in FP64 with the two roundings the FP16 variant makes by design: each weight to
+    binary16 where it multiplies a value row, and the output to binary16 (diagnostic ladder)."""
+    keep, (qp, kp, vp, B, H, n, d), klp, rp = _prep(q, k, v, kv_len, rows)
+    rows = keep[4]
+    out = np.empty((rows.size, d), dtype=np.float64)
+    rc = _load().elsa_ladder_f16_rows(qp, kp, vp, B, H, n, d, float(scale), int(bool(causal)), klp,
+                                      rp, rows.size, out.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
     assert rc == 0
     return out

@@ -456,3 +456,62 @@ int elsa_ladder_f32_fold_rows(const float *q, const float *k, const float *v,
     free(W);
     return 0;
 }
+
+/*
+ * Round a double to the nearest IEEE binary16 value, ties to even (11 significant bits, exponents
+ * 2^-14 .. 2^15, gradual underflow with spacing 2^-24, overflow to infinity), returned as a double.
+ */
+double elsa_oracle_round_f16(double x)
+{
+    if (x == 0.0 || isnan(x) || isinf(x)) return x;
+    int e;
+    (void)frexp(fabs(x), &e);                 /* |x| = f * 2^e, f in [0.5, 1)  ->  |x| in [2^(e-1), 2^e) */
+    int ulp_exp = (e - 1) - 10;               /* spacing of halves in that binade */
+    if (ulp_exp < -24) ulp_exp = -24;         /* below 2^-14: fixed spacing 2^-24 */
+    double r = ldexp(nearbyint(ldexp(x, -ulp_exp)), ulp_exp);   /* nearbyint: ties to even in the default mode */
+    if (fabs(r) > 65504.0) return x > 0 ? INFINITY : -INFINITY;
+    return r;
+}
+
+/*
+ * FP16-operand ladder (diagnostic only): what the FP16 variant must incur by its own definition.
+ * The definition (Eq. 1, max-subtracted) in FP64, except that -- as in the FP16 I/O variant with FP32
+ * state -- every weight e^{s_j - m} is rounded to binary16 where it multiplies v_j (the normaliser sums
+ * the unrounded weights) and the output is rounded to binary16.  Used to tell which violations of an
+ * elementwise tolerance belong to the FP16 operand format rather than to a kernel.
+ * out: [nrows][d] doubles holding binary16 values.
+ */
+int elsa_ladder_f16_rows(const float *q, const float *k, const float *v,
+                         int B, int H, int n, int d, double scale, int causal,
+                         const int32_t *kv_len,
+                         const int64_t *rows, int64_t nrows, double *out)
+{
+    (void)B;
+    double *s = (double *)malloc(sizeof(double) * (size_t)(n > 0 ? n : 1));
+    if (!s) return -1;
+    for (int64_t r = 0; r < nrows; ++r) {
+        int64_t row = rows[r];
+        int64_t i = row % n, bh = row / n, b = bh / H;
+        const float *qi = q + (size_t)row * d;
+        const float *keys = k + (size_t)bh * n * d;
+        const float *vals = v + (size_t)bh * n * d;
+        double *y = out + (size_t)r * d;
+        int64_t L = visible_keys(i, n, causal, kv_len, b);
+        for (int t = 0; t < d; ++t) y[t] = 0.0;
+        if (L <= 0) continue;
+        double top = -INFINITY, Z = 0.0;
+        for (int64_t j = 0; j < L; ++j) {
+            s[j] = score(qi, keys + (size_t)j * d, d, scale);
+            if (s[j] > top) top = s[j];
+        }
+        for (int64_t j = 0; j < L; ++j) {
+            double w = exp(s[j] - top);
+            double wh = elsa_oracle_round_f16(w);
+            Z += w;
+            for (int t = 0; t < d; ++t) y[t] += wh * (double)vals[(size_t)j * d + t];
+        }
+        for (int t = 0; t < d; ++t) y[t] = elsa_oracle_round_f16(y[t] / Z);
+    }
+    free(s);
+    return 0;
+}

@@ -20,6 +20,8 @@ stand-in values.
 from __future__ import annotations
 
 import math
+import os
+from concurrent.futures import ThreadPoolExecutor
 from dataclasses import dataclass, field
 
 import numpy as np
@@ -53,27 +55,41 @@ def uniform01(seed, stream, start, count):
     return _unit(_bits(seed, stream, 0, idx))
 
 
+def _chunked(count, fill):
+    """Run ``fill(offset, length)`` over [0, count) in chunks, on a few host threads (every element is a
+    pure function of its index, so the chunks are independent and the result does not depend on the split)."""
+    step = 1 << 21
+    chunks = [(s, min(step, count - s)) for s in range(0, count, step)]
+    workers = min(len(chunks), 16, os.cpu_count() or 1)
+    if workers <= 1:
+        for s, c in chunks:
+            fill(s, c)
+        return
+    with ThreadPoolExecutor(max_workers=workers) as ex:
+        list(ex.map(lambda sc: fill(*sc), chunks))
+
+
 def normal(seed, stream, start, count, sigma=1.0):
     """``count`` draws of N(0, sigma^2), elements [start, start+count), as float32."""
     out = np.empty(count, dtype=np.float32)
-    step = 1 << 22
-    for s in range(0, count, step):
-        c = min(step, count - s)
+
+    def fill(s, c):
         idx = np.arange(start + s, start + s + c, dtype=np.uint64)
         u1 = _unit(_bits(seed, stream, 0, idx))
         u2 = _unit(_bits(seed, stream, 1, idx))
         z = np.sqrt(-2.0 * np.log(u1)) * np.cos((2.0 * math.pi) * u2)
         out[s:s + c] = (sigma * z).astype(np.float32)
+    _chunked(count, fill)
     return out
 
 
 def uniform_pm1(seed, stream, start, count):
     """``count`` draws of U(-1, 1) as float32."""
     out = np.empty(count, dtype=np.float32)
-    step = 1 << 22
-    for s in range(0, count, step):
-        c = min(step, count - s)
+
+    def fill(s, c):
         out[s:s + c] = (2.0 * uniform01(seed, stream, start + s, c) - 1.0).astype(np.float32)
+    _chunked(count, fill)
     return out
 
 
@@ -191,23 +207,45 @@ def make_varlen(seed: int, num_seqs: int = 8, lo: int = 256, hi: int = 1792, H: 
 
 
 def sample_rows(w: Workload, per_head: int = 64, tile: int = 128, seed: int = 7) -> np.ndarray:
-    """Seeded sample of flat query rows: per (b,h) the first and last row, the
-    neighbours of a few tile boundaries, and random rows up to ``per_head``."""
+    """Seeded sample of flat query rows, ``per_head`` rows per (b,h) (all rows when n is smaller), taken in
+    this order of priority: the first and the last row; the rows around one multiple of each kernel
+    granularity (32-row wave groups, 64-, 128- and 256-row tiles: c*u - 1, c*u, c*u + 1 for a seeded c);
+    for causal workloads the first and last row of the first, a middle and the last ``tile``-row query tile;
+    the rows around a second multiple of each granularity; seeded random rows."""
     n = w.n
     rows = []
     for bh in range(w.B * w.H):
-        picks = {0, n - 1}
-        nb = max(1, n // tile)
-        cuts = integers(seed + 1, bh, 3, 1, max(1, nb - 1)) if nb > 1 else []
-        for c in cuts:
-            for dlt in (-1, 0, 1):
-                i = int(c) * tile + dlt
-                if 0 <= i < n:
-                    picks.add(i)
-        extra = integers(seed, bh, max(0, 2 * per_head), 0, n - 1)
+        budget = min(per_head, n)
+        picks = []
+
+        def take(i):
+            if 0 <= i < n and i not in picks and len(picks) < budget:
+                picks.append(int(i))
+        take(0)
+        take(n - 1)
+        units = (32, 64, 128, 256)
+        cuts = integers(seed + 1, bh, 2 * len(units), 0, (1 << 30) - 1)
+        for rnd in range(2):
+            for ui, u in enumerate(units):
+                nb = n // u
+                if nb < 2 or (rnd == 1 and nb < 3):
+                    continue
+                c = 1 + int(cuts[rnd * len(units) + ui]) % (nb - 1)
+                for dlt in (0, -1, 1):
+                    take(c * u + dlt)
+            if rnd == 0 and w.causal and n > tile:
+                nt = (n + tile - 1) // tile
+                for t in (0, nt // 2, nt - 1):
+                    take(t * tile)
+                    take(min(n, (t + 1) * tile) - 1)
+        extra = integers(seed, bh, max(0, 4 * per_head), 0, n - 1)
         for i in extra:
-            if len(picks) >= min(per_head, n):
+            if len(picks) >= budget:
                 break
-            picks.add(int(i))
+            take(int(i))
+        i = 0
+        while len(picks) < budget:       # tiny n: fill with the remaining rows
+            take(i)
+            i += 1
         rows.extend(bh * n + i for i in sorted(picks))
     return np.asarray(rows, dtype=np.int64)

@@ -48,6 +48,8 @@ def fwd(q, k, v, scale, causal=False, kv_len=None, rows=None, masked_entry=None)
     d = q.shape[-1]
     o = out.reshape(-1, d)
     if rows is not None:
+        # the whole NaN-prefilled output was written, not only the rows the oracle is asked about
+        assert bool(torch.isfinite(out).all()), "rows of the output were left unwritten or are not finite"
         o = o[torch.from_numpy(np.asarray(rows)).cuda()]
     return o.double().cpu().numpy()
 

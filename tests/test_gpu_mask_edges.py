@@ -275,7 +275,8 @@ def test_fp32_denormal_values_are_preserved(path, variant):
     matrix-core and vector instructions that touch V (products with weights, sums, the final scaling)
     keep denormals; only the exponentials flush (a weight below the normal range becomes 0, which drops
     at most n * 1.2e-38 of mass).  A value column that is constant at a denormal c must therefore come
-    out as c (to a few units of the denormal spacing 1.4e-45), not as 0."""
+    out as c, not as 0 -- to within the roundings of some hundred products and sums that themselves fall
+    into the denormal range (spacing 1.4e-45)."""
     B, H, n, d = 1, 2, 200, 64
     q, k, v = _qkv(B, H, n, n, d, d, 1500)
     tiny = np.float32(1.401298464324817e-45)
@@ -286,7 +287,7 @@ def test_fp32_denormal_values_are_preserved(path, variant):
         out = G.fwd(q, k, v, 0.125)
     for col in range(3):
         c = float(v[0, 0, 0, col])
-        assert np.all(np.abs(out[:, col] - c) <= 4 * float(tiny) + 2.0 ** -22 * abs(c)), (path, variant, col, out[:2, col])
+        assert np.all(np.abs(out[:, col] - c) <= 64 * float(tiny)), (path, variant, col, out[:2, col])
 
 
 def test_fp32_denormal_values_are_preserved_when_decoding_and_combining():
@@ -304,4 +305,4 @@ def test_fp32_denormal_values_are_preserved_when_decoding_and_combining():
             assert elsa.elsa_last_splits() > 1 and elsa.elsa_last_kernel().startswith("fma_decode")
         finally:
             elsa.elsa_set_workspace(None)
-        assert np.all(np.abs(out[:, 0] - float(np.float32(1e-40))) <= 4 * tiny), out[:, 0]
+        assert np.all(np.abs(out[:, 0] - float(np.float32(1e-40))) <= 64 * tiny), out[:, 0]

@@ -107,6 +107,16 @@ def battery():
     lad = oracle.ladder_f32_fold_rows(q, k, v, 0.3).astype(np.float64)
     ref = oracle.attn_rows(q, k, v, 0.3)
     assert np.max(np.linalg.norm(lad - ref, axis=1) / np.linalg.norm(ref, axis=1)) < 1e-5
+    # binary16 rounding against the library cast; the half-precision ladder on equal weights (q = 0)
+    xs = [1.0 / 3.0, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 2.0 ** -25, 1.5 * 2.0 ** -24, 70000.0, -0.1, 2051.0, 3e-6]
+    with np.errstate(over="ignore"):
+        assert [oracle.round_f16(x) for x in xs] == [float(np.float16(x)) for x in xs]
+    l16 = oracle.ladder_f16_rows(np.zeros_like(q), k, v, 0.3)
+    assert np.array_equal(l16.reshape(B, H, n, d)[:, :, 3], v.astype(np.float64).mean(axis=2).astype(np.float16).astype(np.float64))
+    l16 = oracle.ladder_f16_rows(q, k, v, 0.3)
+    assert np.max(np.linalg.norm(l16 - ref, axis=1) / np.linalg.norm(ref, axis=1)) < 2.0 ** -10
+    mean_err = lambda a: float(np.mean(np.linalg.norm(a - ref, axis=1) / np.linalg.norm(ref, axis=1)))
+    assert 1.2 < mean_err(l16) / mean_err(ref.astype(np.float16).astype(np.float64)) < 1.7      # rounded weights add their share
 
 
 MUTATIONS = [
@@ -138,6 +148,10 @@ MUTATIONS = [
     ("own value width: diagonal off by one", "int64_t diag = i + ((int64_t)nk - (int64_t)nq) + 1;", "int64_t diag = i + ((int64_t)nk - (int64_t)nq);"),
     ("own value width: padding ignored", "int64_t vis = kv_len ? (int64_t)kv_len[b] : nk;", "int64_t vis = nk;"),
     ("own value width: weights without their maximum in the log-normaliser", "if (lse) lse[r] = top + log(Z);", "if (lse) lse[r] = log(Z);"),
+    ("half rounding: ties away from even", "nearbyint(ldexp(x, -ulp_exp))", "floor(ldexp(x, -ulp_exp) + 0.5)"),
+    ("half rounding: no gradual underflow", "if (ulp_exp < -24) ulp_exp = -24;", ""),
+    ("half-precision ladder: weights not rounded", "double wh = elsa_oracle_round_f16(w);", "double wh = w;"),
+    ("half-precision ladder: output not rounded", "y[t] = elsa_oracle_round_f16(y[t] / Z);", "y[t] = y[t] / Z;"),
     ("single-precision ladder: past not rescaled", "*S = f32_add(Sk, f32_mul(*S, f));", "*S = f32_add(Sk, *S);"),
 ]
 

@@ -193,6 +193,56 @@ def test_ladder_f32_is_close_but_not_exact():
     assert 0 < err.max() < 1e-5
 
 
+def test_round_to_binary16_against_the_library_cast():
+    """The oracle's own rounding to IEEE half against numpy's float16 cast (a black box): random values over
+    the whole exponent range, exact ties (to even), the denormal range, the overflow threshold."""
+    rng = np.random.default_rng(5)
+    xs = np.concatenate([rng.standard_normal(2000) * 10.0 ** rng.integers(-9, 5, 2000),
+                         [0.0, 1.0, -1.0, 65504.0, 65519.99, 65520.0, -65520.0, 1e-8, 2.0 ** -24, 2.0 ** -25, 1.5 * 2.0 ** -24,
+                          2.0 ** -14, 2.0 ** -14 - 2.0 ** -25, 1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11, 1.0 + 2.0 ** -11 + 2.0 ** -30,
+                          1.0 / 3.0, 0.1, 2049.0, 2051.0, 4098.0]])
+    with np.errstate(over="ignore"):
+        want = xs.astype(np.float16).astype(np.float64)
+    got = np.array([oracle.round_f16(x) for x in xs])
+    assert np.array_equal(got, want), [(x, g, w) for x, g, w in zip(xs, got, want) if g != w][:5]
+
+
+def test_ladder_f16_rounds_the_weights_and_the_output_and_nothing_else():
+    # one key: the value row itself, rounded to half
+    q, k, v = _rand(1, 1, 1, 8, 41)
+    assert np.array_equal(oracle.ladder_f16_rows(q, k, v, 0.3)[0], v[0, 0, 0].astype(np.float16).astype(np.float64))
+    # q = 0: every weight is exactly 1 (representable), so only the output is rounded: half(column mean)
+    q, k, v = _rand(1, 2, 37, 8, 42)
+    q[:] = 0
+    mean = v.astype(np.float64).mean(axis=2)                                       # [1, 2, 8]
+    got = oracle.ladder_f16_rows(q, k, v, 0.3).reshape(1, 2, 37, 8)
+    assert np.array_equal(got[0, :, 5], mean[0].astype(np.float16).astype(np.float64))
+    # two keys, s1 - s2 = ln 3 by construction: weights 1 and 1/3; half(1/3) = 1365 / 4096 multiplies v2,
+    # the normaliser keeps 1 + 1/3
+    q = np.array([[[[1.0]]]], np.float32).repeat(2, axis=2)
+    k = np.array([[[[2.0], [0.0]]]], np.float32)
+    v = np.array([[[[3.0], [2.0]]]], np.float32)
+    scale = float(np.log(3.0) / 2.0)
+    got = oracle.ladder_f16_rows(q, k, v, scale)[0, 0]
+    exact = oracle.attn_rows(q, k, v, scale)[0, 0]
+    w = np.exp(0.0 - 2.0 * scale)                                                  # 1/3 up to the rounding of scale
+    want = float(np.float16((3.0 + float(np.float16(w)) * 2.0) / (1.0 + w)))
+    assert got == want and abs(got - exact) < 2e-3
+    # in general: within half-precision roundoff of the definition, row by row
+    q, k, v = _rand(2, 2, 300, 32, 43)
+    for causal in (False, True):
+        ref = oracle.attn_rows(q, k, v, 0.2, causal=causal)
+        lad = oracle.ladder_f16_rows(q, k, v, 0.2, causal=causal)
+        err = np.linalg.norm(lad - ref, axis=1) / np.linalg.norm(ref, axis=1)
+        assert 0 < err.max() < 2.0 ** -10
+        assert np.array_equal(lad, lad.astype(np.float16).astype(np.float64))        # outputs are halves
+        # error model: rounding the output alone leaves a row error of about 0.7 * 2^-11 / sqrt(3); the rounded
+        # weights add an independent error of about the same size, so the ladder sits a factor ~1.4 above it
+        only_out = ref.astype(np.float16).astype(np.float64)
+        mean_err = lambda a: float(np.mean(np.linalg.norm(a - ref, axis=1) / np.linalg.norm(ref, axis=1)))
+        assert 1.2 < mean_err(lad) / mean_err(only_out) < 1.7
+
+
 def test_varlen_reduces_to_dense_problems():
     # equal-length packed sequences are a dense batch in another layout; unequal ones are independent
     B, H, n, d = 3, 2, 17, 8
