@@ -119,9 +119,11 @@ def bench_configs(names, launches, per_head):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(); step(); e1.record(); torch.cuda.synchronize()
         reps = max(launches, min(2000, int(20.0 / max(e0.elapsed_time(e1), 1e-3))))
-        for _ in range(min(reps, 50)):
-            step()
-        torch.cuda.synchronize()
+        tw = time.perf_counter()                   # untimed launches for a quarter second: short workloads otherwise
+        while time.perf_counter() - tw < 0.25:     # run before the clocks have ramped up again after the host-side work
+            for _ in range(min(reps, 50)):
+                step()
+            torch.cuda.synchronize()
         e0.record()
         for _ in range(reps):
             step()

@@ -7,6 +7,8 @@
 // step.  Keys are taken G at a time so the running state is rescaled once per group
 // (the merge operator applied to the group's state) instead of once per key.  The WK
 // waves of a block that split the key range merge their states through LDS.
+#include <type_traits>
+
 #include "elsa_common.hpp"
 
 namespace elsa {
@@ -65,16 +67,21 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
     const T *__restrict__ kp = static_cast<const T *>(p.k) + wi.kbase;
     const T *__restrict__ vp = static_cast<const T *>(p.v) + wi.kbase;
 
-    for (int j0 = wbeg; j0 < wend; j0 += G) {
+    // One group of G keys merged into the state (Eq. 3 with the group's state).  TAIL: the group sticks out of the
+    // wave's range -- keys at or beyond wend are the identity for every row and are skipped, not multiplied by a
+    // zero weight (their rows may be padding that holds anything, NaN and Inf included).
+    auto group = [&](int j0, auto tail_tag) __attribute__((always_inline)) {
+        constexpr bool TAIL = decltype(tail_tag)::value;
         float s[G];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const int key = min(j0 + g, wi.nk - 1);                // clamp: never read past the tensor
-            const T *__restrict__ kj = kp + (long long)key * ts;
+            s[g] = -INFINITY;
+            if (TAIL && j0 + g >= wend) continue;
+            const T *__restrict__ kj = kp + (long long)(j0 + g) * ts;
             float acc = 0.f;
 #pragma unroll
             for (int t = 0; t < D; ++t) acc = fmaf(qr[t], ld_uniform(kj, t), acc);
-            s[g] = (j0 + g < lim) ? acc : -INFINITY;
+            if (j0 + g < lim) s[g] = acc;
         }
         float mt = s[0];
 #pragma unroll
@@ -94,14 +101,15 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_fma_kernel(FwdParams p)
         for (int t = 0; t < D; ++t) W[t] *= alpha;
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            // a key at or beyond the wave's range is the identity for every row: it is skipped, not multiplied
-            // by a zero weight (its value row may be padding that holds anything, NaN and Inf included)
-            if (j0 + g >= wend) break;
+            if (TAIL && j0 + g >= wend) continue;
             const T *__restrict__ vj = vp + (long long)(j0 + g) * ts;
 #pragma unroll
             for (int t = 0; t < D; ++t) W[t] = fmaf(e[g], ld_uniform(vj, t), W[t]);
         }
-    }
+    };
+    int j0 = wbeg;
+    for (; j0 + G <= wend; j0 += G) group(j0, std::false_type{});
+    if (j0 < wend) group(j0, std::true_type{});
 
     if constexpr (WK > 1) {
         extern __shared__ __align__(16) float smem[];

@@ -26,7 +26,7 @@ __device__ __forceinline__ f32x16 mfma16(f16x8 a, f16x8 b, f32x16 c) {
 }
 
 // D: columns of q and k (the contraction of the scores); DV: columns of v and out (rows of W^T).
-template <int D, int NQ, int WQ, int WK, int KS, int WPE, int DV = D>
+template <int D, int NQ, int WQ, int WK, int KS, int WPE, int DV = D, int TRIM = 1>
 __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams p) {
     constexpr int NT = 64 * WQ * WK;
     constexpr int TQ = 32 * NQ * WQ;
@@ -193,8 +193,9 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
         const unsigned char *Vb = Vs + buf * VBUFB;
         const int kg0 = kbeg + t * TKB + wk * KS;
         const int nact = min(KS / 32, max(0, (wave_lim - kg0 + 31) / 32));
-#pragma unroll 1
-        for (int ks = 0; ks < nact; ++ks) {
+        // TRIM: the steps of a tile are separate copies of the loop body, so that a step's place inside the tile is
+        // a constant of its LDS reads (no address arithmetic per step)
+        auto step = [&](const int ks) __attribute__((always_inline)) {
             const int kl = wk * KS + ks * 32;
             const int kg = kg0 + ks * 32;
 
@@ -242,12 +243,14 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
             f16x8 pb[NQ][2];
 #pragma unroll
             for (int nq = 0; nq < NQ; ++nq) {
+                // (no hand-written instructions on values that come straight out of an MFMA: the wait states between
+                // an MFMA and the first read of its result are the compiler's to insert, and it does not look into asm)
                 float mt = sacc[nq][0];
 #pragma unroll
                 for (int i = 1; i < 16; ++i) mt = fmaxf(mt, sacc[nq][i]);
                 mt = half_max(mt);
                 const float mnew = fmaxf(mrun[nq], mt);
-                const float msafe = (mnew == -INFINITY) ? 0.f : mnew;
+                const float msafe = (mnew == -INFINITY) ? 0.f : mnew;      // TRIM: only the (rare) rescale uses it
                 if (__builtin_amdgcn_ballot_w64(mnew > mrun[nq]) != 0) {
                     const float alpha = (mrun[nq] == -INFINITY) ? 0.f : exp2_fast((mrun[nq] - msafe) * cs);
                     srun[nq] *= alpha;
@@ -257,13 +260,16 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
                         for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
                     mrun[nq] = mnew;
                 }
-                const float nmc = -msafe * cs;
+                // -m*c; while the row has seen no key (m = -inf) a large finite value instead of +inf, so that the
+                // exponent of a masked score stays -inf + finite = -inf (one minimum instead of compare + select)
+                const float nmc = TRIM ? fminf(-mnew * cs, 3.0e38f) : -msafe * cs;
                 float ps = 0.f;
                 float e[16];
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     e[i] = exp2_fast(__builtin_fmaf(sacc[nq][i], cs, nmc));
-                    ps += e[i];
+                    if (TRIM && i == 0) ps = e[0];
+                    else ps += e[i];
                 }
                 srun[nq] += ps;
 #pragma unroll
@@ -299,6 +305,14 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
                     for (int nq = 0; nq < NQ; ++nq) oacc[nq][mb] = mfma16(vf, pb[nq][u], oacc[nq][mb]);
                 }
             }
+        };
+        if constexpr (TRIM != 0) {
+#pragma unroll
+            for (int ks = 0; ks < KS / 32; ++ks)
+                if (ks < nact) step(ks);
+        } else {
+#pragma unroll 1
+            for (int ks = 0; ks < nact; ++ks) step(ks);
         }
         if (t + 1 < ntiles) lstore(buf ^ 1);
         __syncthreads();
@@ -401,14 +415,14 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
     }
 }
 
-template <int D, int NQ, int WQ, int WK, int KS, int WPE, int DV = D>
+template <int D, int NQ, int WQ, int WK, int KS, int WPE, int DV = D, int TRIM = 1>
 static int launch_one16(const FwdParams &p, hipStream_t s) {
     constexpr int TKB = KS * WK;
     constexpr size_t kv_bytes = (size_t)2 * (TKB * (D * 2 + 16) + TKB * (DV * 2 + 32));
     constexpr size_t xw_bytes = WK > 1 ? (size_t)(WK / 2) * WQ * NQ * (2 + DV / 2) * 64 * sizeof(float) : 0;
     constexpr size_t smem = kv_bytes > xw_bytes ? kv_bytes : xw_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");
-    auto kern = fwd_mfma16_kernel<D, NQ, WQ, WK, KS, WPE, DV>;
+    auto kern = fwd_mfma16_kernel<D, NQ, WQ, WK, KS, WPE, DV, TRIM>;
     static bool attr_done[kMaxDevices] = {};   // per instantiation and device
     if (hipError_t e = allow_dynamic_lds(kern, smem, attr_done); e != hipSuccess) return (int)e;
     const long long total = p.cu_seqlens ? (long long)p.var_tiles * p.H : (long long)p.q_tiles * p.B * p.H * p.num_splits;

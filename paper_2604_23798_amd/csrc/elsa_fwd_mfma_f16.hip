@@ -6,8 +6,9 @@ namespace elsa {
 
 // ---- variants: 1 q128 (4 query waves)   2 q256 (4 waves x 2 query groups)   3 waves split the keys
 //                4 q64xw2 (two query waves x two key waves; the key-splitting shape of d >= 96)
+//                5 q256 without the instruction trims of the fold (comparison; d <= 64 only)
 
-static const char *kNames16[kMfma16Variants] = {"mfma16_q128_w4", "mfma16_q256_w4", "mfma16_xwave", "mfma16_q64_xw2"};
+static const char *kNames16[kMfma16Variants] = {"mfma16_q128_w4", "mfma16_q256_w4", "mfma16_xwave", "mfma16_q64_xw2", "mfma16_q256_plain"};
 
 int mfma16_variant_tq(int variant, int d) {
     switch (variant) {
@@ -15,6 +16,7 @@ int mfma16_variant_tq(int variant, int d) {
         case 2: return d <= 64 ? 256 : 128;
         case 3: return d <= 64 ? 32 : 64;       // d >= 96: two query waves x two key waves
         case 4: return 64;
+        case 5: return d <= 64 ? 256 : 0;
         default: return 0;
     }
 }
@@ -41,6 +43,9 @@ static int launch_variant16(const FwdParams &p, int variant, hipStream_t s) {
             if constexpr (D == 128) return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
             else return launch_one16<D, 1, 1, 4, 32, 2>(p, s);
         case 4: return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
+        case 5:
+            if constexpr (D <= 64) return launch_one16<D, 2, 4, 1, 64, 2, D, 0>(p, s);
+            else return (int)hipErrorInvalidValue;
         default: return (int)hipErrorInvalidValue;
     }
 }
