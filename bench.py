@@ -289,6 +289,48 @@ def tile_sweep(a):
             "mean": sum(r) / len(r), "max": max(r), "rows": rows}
 
 
+def issue_rates(a):
+    """Issue cost of the instruction kinds the fold is made of (``elsa_debug_issue_probe``): alone at one and two
+    waves per SIMD, and beside the FP32 / FP16 matrix-core instructions of the other wave of the SIMD.  Reported
+    in nanoseconds per instruction and SIMD (constant 100 MHz counter inside the kernel) and in cycles at the
+    nominal 2.4 GHz; the clock the part sustains under each load is not read, so the cycle figures are upper bounds."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    kinds = ["v_exp_f32", "v_fma_f32", "v_add_f32", "v_max3_f32", "v_cvt_pk_f16_f32", "v_mfma_f32_32x32x2_f32",
+             "v_mfma_f32_32x32x16_f16", "none"]
+    per_iter = [16, 16, 16, 16, 16, 8, 8, 0]
+    out = torch.zeros(8 + 256 * 512, device="cuda")
+    iters = 4000
+
+    def run(ka, kb, waves):
+        for _ in range(2):
+            elsa.elsa_debug_issue_probe(out, ka, kb, waves, iters)
+        torch.cuda.synchronize()
+        t = out[:8].cpu().numpy() * 10.0                      # ns per wave of block 0
+        ns_a = float(t[:4].mean()) / iters
+        ns_b = float(t[4:8].mean()) / iters if waves == 2 else 0.0
+        return ns_a, ns_b
+    rows = []
+    for k in range(7):
+        for waves in (1, 2):
+            ns_a, ns_b = run(k, k, waves)
+            # two waves share the SIMD: per instruction and SIMD it is the longer wave's time over both streams
+            ns = max(ns_a, ns_b) / (per_iter[k] * waves)
+            rows.append({"a": kinds[k], "b": kinds[k] if waves == 2 else None, "waves_per_simd": waves,
+                         "ns_per_instr_and_simd": ns, "cycles_at_2.4GHz": ns * 2.4})
+    for m in (5, 6):
+        base_a, _ = run(m, 7, 2)
+        for k in range(5):
+            alone, _ = run(k, 7, 2)
+            ns_a, ns_b = run(m, k, 2)
+            rows.append({"a": kinds[m], "b": kinds[k], "waves_per_simd": 2,
+                         "mfma_ns_per_instr": ns_a / 8, "mfma_alone_ns_per_instr": base_a / 8,
+                         "b_ns_per_instr": ns_b / 16, "b_alone_ns_per_instr": alone / 16,
+                         "b_slowdown": ns_b / alone, "mfma_slowdown": ns_a / base_a})
+    return {"metric": "instruction issue cost on one SIMD (ns per instruction; 16 independent instructions per iteration)",
+            "n_gpus": 1, "iters": iters, "rows": rows}
+
+
 def fit_scaling_law(ns, ts, block=128):
     """Least-squares fit of T(n) = a*L(n,B) + b*n^2 + c (the paper's scaling model, L from Eq. 5)
     to latencies ``ts`` at lengths ``ns``.  Returns n, L, a, b, c and R^2."""
@@ -333,6 +375,8 @@ def main():
                     help="after the headline, time the other workloads briefly and append them as `configs`: auto = all of "
                          "them in the default run (no --workload / --path / --variant given), none, or a comma-separated list")
     ap.add_argument("--config-rows", type=int, default=8, help="oracle rows per head of each `configs` entry (0 = no parity)")
+    ap.add_argument("--issue-rates", action="store_true",
+                    help="instead of a workload: issue cost of the fold's instruction kinds, alone and beside another wave's MFMAs")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 256 MiB device copy (reference point for rocprofv3 byte counters)")
     a = ap.parse_args()
@@ -352,6 +396,9 @@ def main():
         return
     if a.tile_sweep:
         print(json.dumps(tile_sweep(a)))
+        return
+    if a.issue_rates:
+        print(json.dumps(issue_rates(a)))
         return
     varlen = a.workload.startswith("varlen_8x1792")
     decode = a.workload.startswith("decode_32k")

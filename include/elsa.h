@@ -278,6 +278,20 @@ const char *elsa_status_string(int code);
  */
 int elsa_debug_layout_probe(float *out_5x16x64, void *stream);
 
+/*
+ * Measurement hook, not part of the attention path: the issue cost of the instruction kinds the fold between the
+ * two contractions is made of, alone and beside the matrix-core instructions of another wave of the same SIMD
+ * (what the kernels' distance from the matrix-core roof is made of; `bench.py --issue-rates` prints the table).
+ * One block per CU with waves_per_simd (1 or 2) x 4 waves; waves 0-3 issue `iters` x 16 independent instructions
+ * of kind_a (iters x 8 for the MFMA kinds), waves 4-7 of kind_b.
+ *   kinds: 0 v_exp_f32, 1 v_fma_f32, 2 v_add_f32, 3 v_max3_f32, 4 v_cvt_pk_f16_f32, 5 v_mfma_f32_32x32x2_f32,
+ *          6 v_mfma_f32_32x32x16_f16, 7 nothing.
+ *   out: device buffer of 8 + 256 * 512 floats; out[w] = ticks of the constant 100 MHz counter that wave w of
+ *        block 0 took, the rest is scratch.
+ * ELSA_ERR_INVALID_ARG for a NULL buffer, an unknown kind, waves_per_simd not in {1, 2}, iters outside [1, 2^20].
+ */
+int elsa_debug_issue_probe(float *out, int kind_a, int kind_b, int waves_per_simd, int iters, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

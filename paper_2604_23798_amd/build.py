@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libelsa.so")
 SOURCES = ["elsa_api.hip", "elsa_fwd_mfma.hip", "elsa_fwd_mfma_f16.hip", "elsa_fwd_fma.hip", "elsa_fwd_small.hip", "elsa_fwd_decode.hip", "elsa_combine.hip",
-           "elsa_fwd_dv.hip", "elsa_fwd_dv_f16.hip"]
+           "elsa_fwd_dv.hip", "elsa_fwd_dv_f16.hip", "elsa_probe.hip"]
 HOST_SOURCES = ["elsa_plan.cpp"]       # plain C++ (launch planning): also built under sanitizers by a CPU test
 HOST_FLAGS = ["-O2", "-std=c++17", "-fPIC", "-Wall", "-Wextra"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",

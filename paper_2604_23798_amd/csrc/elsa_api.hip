@@ -602,4 +602,11 @@ int elsa_debug_layout_probe(float *out_5x16x64, void *stream) {
     return elsa::launch_probe(out_5x16x64, static_cast<hipStream_t>(stream)) == 0 ? ELSA_OK : ELSA_ERR_HIP;
 }
 
+// Measurement hook (not part of the attention path): runs the instruction issue-rate probe, see elsa_probe.hip.
+int elsa_debug_issue_probe(float *out, int kind_a, int kind_b, int waves_per_simd, int iters, void *stream) {
+    if (!out) return ELSA_ERR_INVALID_ARG;
+    const int rc = elsa::launch_issue_probe(out, kind_a, kind_b, waves_per_simd, iters, static_cast<hipStream_t>(stream));
+    return rc == 0 ? ELSA_OK : rc == (int)hipErrorInvalidValue ? ELSA_ERR_INVALID_ARG : ELSA_ERR_HIP;
+}
+
 }  // extern "C"

@@ -329,6 +329,7 @@ int launch_fwd_dv16(const FwdParams &p, int d, int dv, int variant, hipStream_t 
 int dv_variant_tq(int fp16_tiles, int variant, int d, int dv);   // queries per block (0: no such tile)
 int launch_combine(const CombineParams &p, int d, hipStream_t s);
 int launch_probe(float *out, hipStream_t s);
+int launch_issue_probe(float *out, int kind_a, int kind_b, int waves_per_simd, int iters, hipStream_t s);
 int mfma_variant_tq(int variant, int d);   // queries per block of a variant (0 if unknown)
 int fma_variant_tq(int variant, int d);
 int mfma16_variant_tq(int variant, int d);

@@ -26,6 +26,9 @@ __device__ __forceinline__ f32x16 mfma16(f16x8 a, f16x8 b, f32x16 c) {
 }
 
 // D: columns of q and k (the contraction of the scores); DV: columns of v and out (rows of W^T).
+// TRIM: 0 = the fold as first written (comparison), 1 = fewer instructions per step (the steps of a tile are separate
+// copies of the body, so LDS offsets are constants; one minimum instead of compare + select for rows that have seen no
+// key; row sum started from the first weight), 2 = as 1, and the K fragments of the next step are requested early.
 template <int D, int NQ, int WQ, int WK, int KS, int WPE, int DV = D, int TRIM = 1>
 __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams p) {
     constexpr int NT = 64 * WQ * WK;
@@ -195,6 +198,8 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
         const int nact = min(KS / 32, max(0, (wave_lim - kg0 + 31) / 32));
         // TRIM: the steps of a tile are separate copies of the loop body, so that a step's place inside the tile is
         // a constant of its LDS reads (no address arithmetic per step)
+        constexpr bool KPRE = TRIM == 2;
+        f16x8 kpre[KPRE ? KC : 1];
         auto step = [&](const int ks) __attribute__((always_inline)) {
             const int kl = wk * KS + ks * 32;
             const int kg = kg0 + ks * 32;
@@ -210,6 +215,25 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
             // there spilled 50 registers more and ran 2.9 times slower: 16.9 against 5.8 ms at H = 16,
             // n = 16384); the reads then overlap the MFMA chain instead of being waited for one by one
             constexpr int PF = (KC <= 12 || WPE == 1) ? KC : 2;
+            // KPRE: the fragments of the NEXT step of the tile are requested as soon as this step's score MFMAs are
+            // issued, so that their LDS latency passes under the fold instead of in front of the next MFMA chain
+            // (the first step of a tile has to wait for the barrier and reads its own)
+            if constexpr (KPRE) {
+                if (ks == 0) {
+#pragma unroll
+                    for (int cc = 0; cc < KC; ++cc)
+                        kpre[cc] = *reinterpret_cast<const f16x8 *>(Kb + (kl + j) * KROWB + 32 * cc + 16 * h);
+                }
+#pragma unroll
+                for (int cc = 0; cc < KC; ++cc)
+#pragma unroll
+                    for (int nq = 0; nq < NQ; ++nq) sacc[nq] = mfma16(kpre[cc], qf[nq][cc], sacc[nq]);
+                if (ks + 1 < KS / 32) {
+#pragma unroll
+                    for (int cc = 0; cc < KC; ++cc)
+                        kpre[cc] = *reinterpret_cast<const f16x8 *>(Kb + (kl + 32 + j) * KROWB + 32 * cc + 16 * h);
+                }
+            } else {
 #pragma unroll
             for (int c0 = 0; c0 < KC; c0 += PF) {
                 f16x8 kf[PF];
@@ -222,6 +246,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
                     for (int nq = 0; nq < NQ; ++nq) sacc[nq] = mfma16(kf[cc], qf[nq][c0 + cc], sacc[nq]);
                 __builtin_amdgcn_sched_group_barrier(0x100, PF, 0);          // PF LDS reads
                 __builtin_amdgcn_sched_group_barrier(0x008, PF * NQ, 0);     // then the MFMAs
+            }
             }
 
             // ---- (a2) masks

@@ -6,7 +6,7 @@ namespace elsa {
 
 // ---- variants: 1 q128 (4 query waves)   2 q256 (4 waves x 2 query groups)   3 waves split the keys
 //                4 q64xw2 (two query waves x two key waves; the key-splitting shape of d >= 96)
-//                5 q256 without the instruction trims of the fold (comparison; d <= 64 only)
+//                5 q256 as first built: 64-key tiles, one loop body per step, no early K request (comparison; d <= 64 only)
 
 static const char *kNames16[kMfma16Variants] = {"mfma16_q128_w4", "mfma16_q256_w4", "mfma16_xwave", "mfma16_q64_xw2", "mfma16_q256_plain"};
 
@@ -38,7 +38,10 @@ static int launch_variant16(const FwdParams &p, int variant, hipStream_t s) {
         case 1: return launch_one16<D, 1, 4, 1, 64, 2>(p, s);
         case 2:
             if constexpr (D == 128) return launch_one16<D, 1, 4, 1, 64, 2>(p, s);   // two query groups would spill
-            else return launch_one16<D, 2, 4, 1, 64, 2>(p, s);
+            // 128-key tiles (78 KB of LDS; registers allow two blocks per CU anyway) and the K fragments of the next
+            // step requested early: +2-4 % over 64-key tiles (measured in one process: 893 against 874 TFLOP/s at
+            // n = 16384, 846 against 818 at 8192); at d = 128 the early request measured -1 % and is not used
+            else return launch_one16<D, 2, 4, 1, 128, 2, D, 2>(p, s);
         case 3:
             if constexpr (D == 128) return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
             else return launch_one16<D, 1, 1, 4, 32, 2>(p, s);

@@ -21,7 +21,7 @@ OK, ERR_INVALID_ARG, ERR_UNSUPPORTED, ERR_WORKSPACE, ERR_HIP = 0, 1, 2, 3, 4
 EXPORTS = ("elsa_attn_fwd", "elsa_attn_fwd_masked", "elsa_attn_fwd_static", "elsa_static_scratch_bytes", "elsa_attn_fwd_lse", "elsa_attn_fwd_cross", "elsa_attn_fwd_dv", "elsa_attn_fwd_varlen", "elsa_attn_fwd_split_kv", "elsa_combine",
            "elsa_stream_state_bytes", "elsa_attn_stream_step", "elsa_attn_stream_finish",
            "elsa_split_kv_workspace_bytes", "elsa_set_workspace", "elsa_set_option", "elsa_get_option",
-           "elsa_variant_name", "elsa_last_kernel", "elsa_last_splits", "elsa_status_string", "elsa_debug_layout_probe")
+           "elsa_variant_name", "elsa_last_kernel", "elsa_last_splits", "elsa_status_string", "elsa_debug_layout_probe", "elsa_debug_issue_probe")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError("libelsa.so is not built: run `python -c 'import __graft_entry__ as g; g.build()'` "
@@ -54,6 +54,7 @@ _lib.elsa_last_kernel.restype = ctypes.c_char_p
 _lib.elsa_status_string.argtypes = [_i]
 _lib.elsa_status_string.restype = ctypes.c_char_p
 _lib.elsa_debug_layout_probe.argtypes = [_vp, _vp]
+_lib.elsa_debug_issue_probe.argtypes = [_vp, _i, _i, _i, _i, _vp]
 
 
 class ElsaError(RuntimeError):
@@ -298,6 +299,14 @@ def elsa_last_splits() -> int:
 
 def elsa_debug_layout_probe(out, stream=None):
     _check(_lib.elsa_debug_layout_probe(_ptr(out), _stream(stream, out)))
+    return out
+
+
+def elsa_debug_issue_probe(out, kind_a, kind_b, waves_per_simd, iters, stream=None):
+    """Measurement hook: ``out`` is a float32 device tensor of at least 8 + 256 * 512 elements."""
+    import torch
+    assert out.is_cuda and out.is_contiguous() and out.dtype == torch.float32 and out.numel() >= 8 + 256 * 512
+    _check(_lib.elsa_debug_issue_probe(_ptr(out), int(kind_a), int(kind_b), int(waves_per_simd), int(iters), _stream(stream, out)))
     return out
 
 

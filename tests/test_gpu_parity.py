@@ -58,6 +58,30 @@ def test_mfma_layout_and_half_wave_exchange():
     assert np.all(np.abs(r[4, 0] - ex) <= 4 * 2.0 ** -24 * ex)
 
 
+def test_issue_probe_hook_runs_and_orders_the_instruction_kinds():
+    """The measurement hook behind ``bench.py --issue-rates``: every kind runs, rejects bad arguments, and the two
+    facts the kernels' design rests on hold -- an exponential costs more issue time than an add, and a wave's adds
+    are barely slowed by FP16 MFMAs of the other wave of its SIMD while FP32 MFMAs stop them."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    out = torch.zeros(8 + 256 * 512, device="cuda")
+    t = {}
+    for ka, kb, waves in [(0, 0, 1), (2, 2, 1), (2, 7, 2), (6, 2, 2), (5, 2, 2), (1, 1, 2), (3, 3, 1), (4, 4, 1)]:
+        elsa.elsa_debug_issue_probe(out, ka, kb, waves, 2000)
+        elsa.elsa_debug_issue_probe(out, ka, kb, waves, 2000)
+        torch.cuda.synchronize()
+        r = out[:8].cpu().numpy()
+        assert np.all(r[:4 * waves] > 0)
+        t[(ka, kb, waves)] = (r[:4].mean(), r[4:8].mean())
+    assert t[(0, 0, 1)][0] > 1.2 * t[(2, 2, 1)][0]                 # exp vs add
+    add_alone = t[(2, 7, 2)][0]
+    assert t[(6, 2, 2)][1] < 1.5 * add_alone                       # adds beside FP16 MFMAs: nearly unhindered
+    assert t[(5, 2, 2)][1] > 2.0 * add_alone                       # adds beside FP32 MFMAs: they wait
+    for bad in [(-1, 0, 1, 10), (0, 8, 1, 10), (0, 0, 3, 10), (0, 0, 1, 0)]:
+        with pytest.raises(elsa.ElsaError):
+            elsa.elsa_debug_issue_probe(out, *bad)
+
+
 @pytest.mark.parametrize("path,variant", ALL_KERNELS)
 @pytest.mark.parametrize("shape", [(1, 2, 197, 64), (2, 2, 330, 64), (1, 2, 300, 128), (2, 3, 200, 32)])
 @pytest.mark.parametrize("causal", [False, True])
