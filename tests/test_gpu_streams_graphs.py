@@ -85,3 +85,64 @@ def test_graph_capture_and_replays(case):
     if case != "decode":
         got = got[rows]
     assert_parity(got, ref, tolerance(n, False), "graph " + case)
+
+
+def test_two_host_threads_on_two_streams_match_the_serial_run():
+    """Options, the lent workspace and the last-launch record are per host thread: two threads, each with its own
+    stream, workspace and forced configuration, run different problems at the same time and get, bit for bit,
+    what the same calls give one after the other; each thread reads back its own kernel name and chunk count."""
+    import threading
+    import torch
+    from paper_2604_23798_amd import elsa
+
+    jobs = []
+    for idx, (n, causal, variant, splits) in enumerate([(1100, False, 7, 3), (777, True, 11, 2)]):
+        w = inputs.sweep(1024).with_(n=n, H=6, name="thr%d" % idx, seed=1500 + idx)
+        q, k, v, _ = inputs.make(w)
+        jobs.append(dict(w=w, tq=G.to_dev(q), tk=G.to_dev(k), tv=G.to_dev(v), causal=causal, variant=variant, splits=splits))
+
+    def run(job, out, stream, record):
+        ws = torch.empty(elsa.elsa_split_kv_workspace_bytes(1, 6, job["w"].n, 64, job["splits"]), dtype=torch.uint8, device="cuda")
+        elsa.elsa_set_workspace(ws)
+        elsa.elsa_set_option(elsa.OPT_PATH, 2)
+        elsa.elsa_set_option(elsa.OPT_VARIANT, job["variant"])
+        elsa.elsa_set_option(elsa.OPT_SPLITS, job["splits"])
+        try:
+            for _ in range(20):
+                elsa.elsa_attn_fwd(job["tq"], job["tk"], job["tv"], out, job["w"].scale, job["causal"], stream=stream)
+                record.append((elsa.elsa_last_kernel(), elsa.elsa_last_splits()))
+            stream.synchronize()
+        finally:
+            for o in (elsa.OPT_PATH, elsa.OPT_VARIANT, elsa.OPT_SPLITS):
+                elsa.elsa_set_option(o, 0)
+            elsa.elsa_set_workspace(None)
+
+    serial, serial_rec = [], []
+    for job in jobs:
+        out = torch.full_like(job["tq"], float("nan"))
+        rec = []
+        run(job, out, torch.cuda.Stream(), rec)
+        serial.append(out)
+        serial_rec.append(rec[0])
+    assert serial_rec[0] == ("mfma_q128_k32", 3) and serial_rec[1] == ("mfma_q64_xw2", 2)
+
+    outs = [torch.full_like(job["tq"], float("nan")) for job in jobs]
+    recs, errors = [[], []], []
+
+    def worker(i):
+        try:
+            assert elsa.elsa_get_option(elsa.OPT_VARIANT) == 0          # a new thread starts from the defaults
+            run(jobs[i], outs[i], torch.cuda.Stream(), recs[i])
+        except BaseException as e:       # noqa: BLE001
+            errors.append(repr(e))
+    ts = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in ts:
+        t.start()
+    for t in ts:
+        t.join(120)
+    torch.cuda.synchronize()
+    assert not errors, errors
+    for i in range(2):
+        assert all(r == serial_rec[i] for r in recs[i]), (i, recs[i][:3])
+        assert torch.equal(outs[i], serial[i]), "thread %d differs from the serial run" % i
+    assert elsa.elsa_get_option(elsa.OPT_VARIANT) == 0                  # nothing leaked into this thread
