@@ -28,8 +28,16 @@ __device__ __forceinline__ f32x16 mfma16(f16x8 a, f16x8 b, f32x16 c) {
 // D: columns of q and k (the contraction of the scores); DV: columns of v and out (rows of W^T).
 // TRIM: 0 = the fold as first written (comparison), 1 = fewer instructions per step (the steps of a tile are separate
 // copies of the body, so LDS offsets are constants; one minimum instead of compare + select for rows that have seen no
-// key; row sum started from the first weight), 2 = as 1, and the K fragments of the next step are requested early.
-template <int D, int NQ, int WQ, int WK, int KS, int WPE, int DV = D, int TRIM = 1>
+// key; row sum started from the first weight), 2 = as 1, and the K fragments of the next step are requested early,
+// 3 = as 2 with a lagging reference (below), 4 = as 1 with a lagging reference.
+// Lagging reference (launches that write the output, not a state): the m of the running state is allowed to lag the
+// true maximum.  (m, S, W) and (m', S e^(m-m'), W e^(m-m')) are the same element of the monoid and give the same W / S,
+// so a step first forms its weights against the stored m and keeps them if every lane's partial row sum stays below
+// kLagLimit (then no weight exceeds it either: no FP16 overflow, and a reference BELOW the true maximum only moves
+// the weights away from the FP16 subnormals).  Otherwise -- the first keys of a row, a score more than ~2^10 above the
+// stored reference, a NaN -- the step is redone the exact way: maximum, rescale, new reference.  This removes the
+// row maximum (10 instructions), its half-wave exchange and test (4) from nearly every step.
+template <int D, int NQ, int WQ, int WK, int KS, int WPE, int DV = D, int TRIM = 4>
 __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams p) {
     constexpr int NT = 64 * WQ * WK;
     constexpr int TQ = 32 * NQ * WQ;
@@ -102,12 +110,16 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
         }
     }
 
+    constexpr bool LAG = TRIM >= 3;
+    constexpr float kLagLimit = 1024.f;
     float mrun[NQ], srun[NQ];               // mrun in raw score units
+    float nmcr[NQ];                         // LAG: -m*c of the stored reference (3e38 while the row has seen no key)
     f32x16 oacc[NQ][MB];
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
         mrun[nq] = -INFINITY;
         srun[nq] = 0.f;
+        nmcr[nq] = 3.0e38f;
 #pragma unroll
         for (int mb = 0; mb < MB; ++mb)
 #pragma unroll
@@ -198,7 +210,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
         const int nact = min(KS / 32, max(0, (wave_lim - kg0 + 31) / 32));
         // TRIM: the steps of a tile are separate copies of the loop body, so that a step's place inside the tile is
         // a constant of its LDS reads (no address arithmetic per step)
-        constexpr bool KPRE = TRIM == 2;
+        constexpr bool KPRE = TRIM == 2 || TRIM == 3;
         f16x8 kpre[KPRE ? KC : 1];
         auto step = [&](const int ks) __attribute__((always_inline)) {
             const int kl = wk * KS + ks * 32;
@@ -270,6 +282,19 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
             for (int nq = 0; nq < NQ; ++nq) {
                 // (no hand-written instructions on values that come straight out of an MFMA: the wait states between
                 // an MFMA and the first read of its result are the compiler's to insert, and it does not look into asm)
+                float ps = 0.f;
+                float e[16];
+                bool redo = true;
+                if constexpr (LAG) {
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        e[i] = exp2_fast(__builtin_fmaf(sacc[nq][i], cs, nmcr[nq]));
+                        if (i == 0) ps = e[0];
+                        else ps += e[i];
+                    }
+                    redo = __builtin_amdgcn_ballot_w64(!(ps < kLagLimit)) != 0;
+                }
+                if (redo) {
                 float mt = sacc[nq][0];
 #pragma unroll
                 for (int i = 1; i < 16; ++i) mt = fmaxf(mt, sacc[nq][i]);
@@ -288,13 +313,13 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
                 // -m*c; while the row has seen no key (m = -inf) a large finite value instead of +inf, so that the
                 // exponent of a masked score stays -inf + finite = -inf (one minimum instead of compare + select)
                 const float nmc = TRIM ? fminf(-mnew * cs, 3.0e38f) : -msafe * cs;
-                float ps = 0.f;
-                float e[16];
+                if constexpr (LAG) nmcr[nq] = nmc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     e[i] = exp2_fast(__builtin_fmaf(sacc[nq][i], cs, nmc));
                     if (TRIM && i == 0) ps = e[0];
                     else ps += e[i];
+                }
                 }
                 srun[nq] += ps;
 #pragma unroll
@@ -440,13 +465,17 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma16_kernel(FwdParams
     }
 }
 
-template <int D, int NQ, int WQ, int WK, int KS, int WPE, int DV = D, int TRIM = 1>
+template <int D, int NQ, int WQ, int WK, int KS, int WPE, int DV = D, int TRIM = 4>
 static int launch_one16(const FwdParams &p, hipStream_t s) {
     constexpr int TKB = KS * WK;
     constexpr size_t kv_bytes = (size_t)2 * (TKB * (D * 2 + 16) + TKB * (DV * 2 + 32));
     constexpr size_t xw_bytes = WK > 1 ? (size_t)(WK / 2) * WQ * NQ * (2 + DV / 2) * 64 * sizeof(float) : 0;
     constexpr size_t smem = kv_bytes > xw_bytes ? kv_bytes : xw_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");
+    // a launch that writes states keeps the exact maximum in them: the same tile without the lagging reference
+    if constexpr (TRIM >= 3) {
+        if (p.emit_partials) return launch_one16<D, NQ, WQ, WK, KS, WPE, DV, (TRIM == 3 ? 2 : 1)>(p, s);
+    }
     auto kern = fwd_mfma16_kernel<D, NQ, WQ, WK, KS, WPE, DV, TRIM>;
     static bool attr_done[kMaxDevices] = {};   // per instantiation and device
     if (hipError_t e = allow_dynamic_lds(kern, smem, attr_done); e != hipSuccess) return (int)e;

@@ -31,8 +31,10 @@ static int launch_variant16(const FwdParams &p, int variant, hipStream_t s) {
         if (variant == 3 || variant == 4) return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
         return launch_one16<D, 1, 4, 1, 64, 2>(p, s);
     } else if constexpr (D == 256) {
+        // (the 128-row tile fills its 256 registers: the second copy of the exponentials that the lagging reference
+        // needs spilled 20 bytes more and ran 9 % slower, so it keeps the exact maximum per step)
         if (variant == 3 || variant == 4) return launch_one16<D, 1, 2, 2, 32, 1>(p, s);
-        return launch_one16<D, 1, 4, 1, 32, 2>(p, s);
+        return launch_one16<D, 1, 4, 1, 32, 2, D, 1>(p, s);
     } else
     switch (variant) {
         case 1: return launch_one16<D, 1, 4, 1, 64, 2>(p, s);
@@ -41,7 +43,7 @@ static int launch_variant16(const FwdParams &p, int variant, hipStream_t s) {
             // 128-key tiles (78 KB of LDS; registers allow two blocks per CU anyway) and the K fragments of the next
             // step requested early: +2-4 % over 64-key tiles (measured in one process: 893 against 874 TFLOP/s at
             // n = 16384, 846 against 818 at 8192); at d = 128 the early request measured -1 % and is not used
-            else return launch_one16<D, 2, 4, 1, 128, 2, D, 2>(p, s);
+            else return launch_one16<D, 2, 4, 1, 128, 2, D, 3>(p, s);
         case 3:
             if constexpr (D == 128) return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
             else return launch_one16<D, 1, 1, 4, 32, 2>(p, s);
