@@ -39,44 +39,49 @@ const char *mfma_variant_name(int variant) {
 
 template <int D, typename T>
 static int launch_variant(const FwdParams &p, int variant, hipStream_t s) {
+    // The last template argument (1) turns on the lagging reference where the sixteen extra registers per query group
+    // neither spill nor cost a resident block; the 256-row tiles, the eight-wave tile, the four-chain and the
+    // single-buffered tile at d = 128 and every tile at d = 256 stay on the exact maximum per step.
     // d = 96 and d = 256: one tile shape (128 rows, 32-key tiles; two waves per SIMD at d = 96, one at
     // d = 256 where the state and the query fragment fill the register file) and, for d = 96, the
     // key-splitting shape
     if constexpr (D == 96) {
-        if (variant == 3 || variant == 11) return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
-        return launch_one<D, T, 1, 4, 1, 32, 2, 2, 1>(p, s);
+        if (variant == 3 || variant == 11) return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1, D, 1>(p, s);
+        return launch_one<D, T, 1, 4, 1, 32, 2, 2, 1, D, 1>(p, s);
     } else if constexpr (D == 256) {
         return launch_one<D, T, 1, 4, 1, 32, 1, 1, 1>(p, s);
     } else {
     // keys per LDS buffer: 64 for d <= 64, 32 for d = 128 (same bytes)
     constexpr int KS = D == 128 ? 32 : 64;
     switch (variant) {
-        case 1: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1>(p, s);
+        case 1: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1, D, 1>(p, s);
         case 2:
-            if constexpr (D == 128) return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1>(p, s);   // no room for two query groups
+            if constexpr (D == 128) return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1, D, 1>(p, s);   // no room for two query groups
             else return launch_one<D, T, 2, 4, 1, KS, 2, 2, 1>(p, s);
         case 3:
             // d = 128: two 64-key tiles of K and V fill the LDS of a CU, so one block (one wave per SIMD)
             // is resident anyway: no register cap (the cap of two waves per SIMD spilled 20 registers)
-            if constexpr (D == 128) return launch_one<D, T, 1, 2, 2, 32, 1, 2, 1>(p, s);
-            else return launch_one<D, T, 1, 1, 4, 32, 2, 2, 1>(p, s);
+            if constexpr (D == 128) return launch_one<D, T, 1, 2, 2, 32, 1, 2, 1, D, 1>(p, s);
+            else return launch_one<D, T, 1, 1, 4, 32, 2, 2, 1, D, 1>(p, s);
         case 4:
             // d = 64: 8 waves on 32-key tiles, 4 per SIMD in 128 registers.  d = 128 has no such
             // configuration (the state alone needs more registers): same as id 5.
             if constexpr (D == 64) return launch_one<D, T, 1, 8, 1, 32, 4, 2, 1>(p, s);
             else if constexpr (D == 32) return launch_one<D, T, 1, 8, 1, 64, 4, 2, 1>(p, s);
-            else return launch_one<D, T, 1, 4, 1, KS, 2, 1, 1>(p, s);
-        case 5: return launch_one<D, T, 1, 4, 1, KS, 2, 1, 1>(p, s);
+            else return launch_one<D, T, 1, 4, 1, KS, 2, 1, 1, D, 1>(p, s);
+        case 5: return launch_one<D, T, 1, 4, 1, KS, 2, 1, 1, D, 1>(p, s);
         case 6: return launch_one<D, T, 1, 4, 1, KS, 2, 4, 1>(p, s);
         case 7:
-            if constexpr (D == 128) return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1>(p, s);
-            else return launch_one<D, T, 1, 4, 1, 32, 3, 2, 1>(p, s);
-        case 8: return launch_one<D, T, 1, 4, 1, KS, 2, 2, 0>(p, s);
+            if constexpr (D == 128) return launch_one<D, T, 1, 4, 1, KS, 2, 2, 1, D, 1>(p, s);
+            else return launch_one<D, T, 1, 4, 1, 32, 3, 2, 1, D, 1>(p, s);
+        case 8:
+            if constexpr (D == 128) return launch_one<D, T, 1, 4, 1, KS, 2, 2, 0>(p, s);     // (would spill)
+            else return launch_one<D, T, 1, 4, 1, KS, 2, 2, 0, D, 1>(p, s);
         case 11:
-            if constexpr (D == 128) return launch_one<D, T, 1, 2, 2, 32, 1, 2, 1>(p, s);
-            else return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1>(p, s);
+            if constexpr (D == 128) return launch_one<D, T, 1, 2, 2, 32, 1, 2, 1, D, 1>(p, s);
+            else return launch_one<D, T, 1, 2, 2, 32, 2, 2, 1, D, 1>(p, s);
         case 12:
-            if constexpr (D == 128) return launch_one<D, T, 1, 1, 4, 32, 1, 2, 2>(p, s);
+            if constexpr (D == 128) return launch_one<D, T, 1, 1, 4, 32, 1, 2, 2, D, 1>(p, s);
             else return (int)hipErrorInvalidValue;
         case 13:
             if constexpr (D == 128) return launch_one<D, T, 1, 2, 2, 32, 2, 2, 2>(p, s);

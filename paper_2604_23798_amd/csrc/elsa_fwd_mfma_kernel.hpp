@@ -26,7 +26,7 @@ __device__ __forceinline__ f32x16 mfma32(float a, float b, f32x16 c) {
 }
 
 // D: columns of q and k (the contraction of the scores); DV: columns of v and out (rows of W^T).
-template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int BUFL, int DV = D>
+template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int BUFL, int DV = D, int LAG = 0>
 __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p) {
     constexpr int NT = 64 * WQ * WK;
     constexpr int TQ = 32 * NQ * WQ;
@@ -47,6 +47,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     static_assert(TKB * QPR % NT == 0 && TKB * QPRV % NT == 0, "tile must divide evenly over the threads");
     static_assert(D % 8 == 0 && DV % 32 == 0, "head dimensions");
     static_assert(KS % 32 == 0, "a wave consumes keys 32 at a time");
+    static_assert(!LAG || NACC == 1 || NACC == 2, "the reference is split exactly over one or two chains");
 
     extern __shared__ __align__(16) float smem[];
     // BUFL = 2: one LDS buffer instead of two, for tiles too large to double (the next tile waits in
@@ -100,6 +101,16 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 
     float mrun[NQ], srun[NQ];
     f32x16 oacc[NQ][MB];
+    // LAG: every accumulation chain of the score MFMAs starts from -m / NACC (sixteen copies: the accumulator they add
+    // to), so a step's scores come out relative to the stored reference; 0 while the row has seen no key (mrun = -inf).
+    // Splitting -m over the chains keeps their partial sums as small as those of a sum started from 0 (started from
+    // -m in one chain they were three times as large on average, and so was the rounding error at |m| ~ 300).
+    constexpr float kLagLimit = 65536.f;
+    f32x16 negm[LAG ? NQ : 1];
+#pragma unroll
+    for (int nq = 0; nq < (LAG ? NQ : 1); ++nq)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) negm[nq][i] = 0.f;
 #pragma unroll
     for (int nq = 0; nq < NQ; ++nq) {
         mrun[nq] = -INFINITY;
@@ -228,7 +239,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 #pragma unroll
                     for (int a = 0; a < NACC; ++a)
 #pragma unroll
-                        for (int i = 0; i < 16; ++i) part[nq][a][i] = 0.f;
+                        for (int i = 0; i < 16; ++i) part[nq][a][i] = LAG ? negm[nq][i] : 0.f;
                 // K fragments are fetched one column group ahead of the MFMAs that consume them
                 const float *krow = &Kb[(kl + j) * KROW + 4 * h];
                 f32x4 kf = *reinterpret_cast<const f32x4 *>(krow);
@@ -280,6 +291,47 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
             // ---- (a3) fold the tile into (m, S, W): merge operator with the tile's state
 #pragma unroll
             for (int nq = 0; nq < NQ; ++nq) {
+                if constexpr (LAG != 0) {
+                    // the scores are relative to the stored reference already: weights and their sum first; the
+                    // reference is renewed only if a partial row sum passes the limit or the row has no reference yet
+                    float ps = 0.f;
+                    float e[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) {
+                        e[i] = exp2_fast(sacc[nq][i]);
+                        ps += e[i];
+                    }
+                    const bool started = mrun[nq] != -INFINITY;
+                    if (__builtin_amdgcn_ballot_w64(!(ps < kLagLimit) || !started) != 0) {
+                        float mt = sacc[nq][0];
+#pragma unroll
+                        for (int i = 1; i < 16; ++i) mt = fmaxf(mt, sacc[nq][i]);
+                        mt = half_max(mt);                   // relative to the stored reference (to 0 for a first key)
+                        const bool moves = started ? (mt > 0.f) : (mt != -INFINITY);
+                        const float up = moves ? mt : 0.f;
+                        if (__builtin_amdgcn_ballot_w64(moves) != 0) {
+                            const float alpha = started ? exp2_fast(-up) : 0.f;
+                            srun[nq] *= alpha;
+#pragma unroll
+                            for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+                                for (int i = 0; i < 16; ++i) oacc[nq][mb][i] *= alpha;
+                            if (moves) mrun[nq] = (started ? mrun[nq] : 0.f) + up;
+                            const float nm = (mrun[nq] == -INFINITY) ? 0.f : -mrun[nq] * (1.0f / NACC);
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) negm[nq][i] = nm;
+                        }
+                        ps = 0.f;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) {
+                            e[i] = exp2_fast(sacc[nq][i] - up);
+                            ps += e[i];
+                        }
+                    }
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) sacc[nq][i] = e[i];
+                    srun[nq] += ps;
+                } else {
                 float mt = sacc[nq][0];
 #pragma unroll
                 for (int i = 1; i < 16; ++i) mt = fmaxf(mt, sacc[nq][i]);
@@ -304,6 +356,7 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
                     ps += e;
                 }
                 srun[nq] += ps;
+                }
             }
 
             // ---- (a4) W^T += V^T P^T.  Step i contracts keys 8g+t (lower half-wave) and
@@ -472,14 +525,18 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
     }
 }
 
-template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int BUFL, int DV = D>
+template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int BUFL, int DV = D, int LAG = 0>
 static int launch_one(const FwdParams &p, hipStream_t s) {
+    // a launch that writes states keeps the exact maximum in them: the same tile without the lagging reference
+    if constexpr (LAG != 0) {
+        if (p.emit_partials) return launch_one<D, T, NQ, WQ, WK, KS, WPE, NACC, BUFL, DV, 0>(p, s);
+    }
     constexpr int TKB = KS * WK;
     constexpr size_t kv_bytes = (size_t)(BUFL == 2 ? 1 : 2) * (TKB * (D + 4) + TKB * DV) * sizeof(float);
     constexpr size_t xw_bytes = WK > 1 ? (size_t)(WK / 2) * WQ * NQ * (2 + DV / 2) * 64 * sizeof(float) : 0;
     constexpr size_t smem = kv_bytes > xw_bytes ? kv_bytes : xw_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");
-    auto kern = fwd_mfma_kernel<D, T, NQ, WQ, WK, KS, WPE, NACC, BUFL, DV>;
+    auto kern = fwd_mfma_kernel<D, T, NQ, WQ, WK, KS, WPE, NACC, BUFL, DV, LAG>;
     static bool attr_done[kMaxDevices] = {};   // per instantiation and device
     if (hipError_t e = allow_dynamic_lds(kern, smem, attr_done); e != hipSuccess) return (int)e;
     const long long total = p.cu_seqlens ? (long long)p.var_tiles * p.H : (long long)p.q_tiles * p.B * p.H * p.num_splits;

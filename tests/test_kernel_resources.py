@@ -53,9 +53,9 @@ def test_default_kernels_of_the_benchmarked_workloads_do_not_spill_and_keep_thei
         assert len(hits) == 1, pattern
         return hits[0]
     # FP32 headline tile (d = 64, 128 rows, 32-key tiles): three waves per SIMD
-    assert one(r"fwd_mfma_kernelILi64EfLi1ELi4ELi1ELi32ELi3ELi2ELi1ELi64E") == (0, 3)
+    assert one(r"fwd_mfma_kernelILi64EfLi1ELi4ELi1ELi32ELi3ELi2ELi1ELi64ELi1E") == (0, 3)
     # FP32 d = 128 tile, FP16 tiles at d = 64 (256 rows) and d = 128: two waves per SIMD
-    assert one(r"fwd_mfma_kernelILi128EfLi1ELi4ELi1ELi32ELi2ELi2ELi1ELi128E") == (0, 2)
+    assert one(r"fwd_mfma_kernelILi128EfLi1ELi4ELi1ELi32ELi2ELi2ELi1ELi128ELi1E") == (0, 2)
     assert one(r"fwd_mfma16_kernelILi64ELi2ELi4ELi1ELi128ELi2ELi64ELi3E") == (0, 2)
     assert one(r"fwd_mfma16_kernelILi128ELi1ELi4ELi1ELi64ELi2ELi128ELi4E") == (0, 2)
     # decoding: one query per block, no scratch
