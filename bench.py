@@ -28,7 +28,8 @@ PEAK_FP16_TFLOPS = 2500.0       # MI355X dense FP16 MFMA
 # HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, each scaled by what the same
 # counter reads for a plain copy of known size in the same run (profiles/*_counters.md).
 # Keyed by (workload, kernel actually launched); the value names the summary the figure comes from.
-MEASURED_TRAFFIC = {("sweep_n16384", "mfma_q128_k32"): (1.156e9, "profiles/fwd_mfma_sweep_n16384_counters.md"),
+MEASURED_TRAFFIC = {("sweep_n16384", "mfma_q128_k32"): (1.38e9, "profiles/fwd_mfma_sweep_n16384_counters.md"),
+                    ("sweep_n16384_fp16", "mfma16_q256_w4"): (3.06e8, "profiles/fwd_mfma16_experiments.md"),
                     ("sweep_n16384", "mfma_q256_w4"): (6.606e8, "profiles/fwd_mfma_sweep_n16384_counters.md"),
                     ("decode_32k", "fma_decode_q1"): (2.685e9, "profiles/fwd_decode_decode_32k.md")}
 # the other workloads, appended to the default run's JSON line as `configs` (each timed briefly after the headline)
