@@ -19,12 +19,13 @@ static int launch_dv32(const FwdParams &p, int variant, hipStream_t s) {
     constexpr bool small = D <= 64 && DV <= 64;
     if (variant == 3) {
         if constexpr (D == 192) return (int)hipErrorInvalidValue;
-        else if constexpr (small) return launch_one<D, T, 1, 1, 4, 32, 2, 2, 1, DV>(p, s);
-        else return launch_one<D, T, 1, 2, 2, 32, 1, 2, 1, DV>(p, s);   // its tiles leave room for one block per CU: no register cap
+        else if constexpr (small) return launch_one<D, T, 1, 1, 4, 32, 2, 2, 1, DV, 1>(p, s);
+        else return launch_one<D, T, 1, 2, 2, 32, 1, 2, 1, DV, 1>(p, s);   // its tiles leave room for one block per CU: no register cap
     }
     // waves per SIMD the registers allow: three for the narrow pairs, one at d = 192
     constexpr int WPE = D == 192 ? 1 : small ? 3 : 2;
-    return launch_one<D, T, 1, 4, 1, 32, WPE, 2, 1, DV>(p, s);
+    // (last argument: the lagging reference of the d_v = d tiles; every pair has the sixteen registers it needs)
+    return launch_one<D, T, 1, 4, 1, 32, WPE, 2, 1, DV, 1>(p, s);
 }
 
 int launch_fwd_dv32(const FwdParams &p, int d, int dv, int f16, int variant, hipStream_t s, const char **name) {
