@@ -328,8 +328,17 @@ def issue_rates(a):
                          "mfma_ns_per_instr": ns_a / 8, "mfma_alone_ns_per_instr": base_a / 8,
                          "b_ns_per_instr": ns_b / 16, "b_alone_ns_per_instr": alone / 16,
                          "b_slowdown": ns_b / alone, "mfma_slowdown": ns_a / base_a})
+    # register-only model of one fold step of the FP16 256-row tile (kinds 8 = its MFMAs, 9 = its fold, 10 = whole step;
+    # two query groups per wave and iteration): ns per 32 x 32 step and SIMD at one and two waves per SIMD
+    model = []
+    names = {8: "MFMAs alone (8 per 32x32 step)", 9: "fold alone", 10: "whole step"}
+    for k in (8, 9, 10):
+        for waves in (1, 2):
+            ns_a, ns_b = run(k, k if waves == 2 else 7, waves)
+            ns = max(ns_a, ns_b) / (2 * waves)
+            model.append({"part": names[k], "waves_per_simd": waves, "ns_per_step_and_simd": ns, "cycles_at_2.4GHz": ns * 2.4})
     return {"metric": "instruction issue cost on one SIMD (ns per instruction; 16 independent instructions per iteration)",
-            "n_gpus": 1, "iters": iters, "rows": rows}
+            "n_gpus": 1, "iters": iters, "rows": rows, "fp16_step_model": model}
 
 
 def fit_scaling_law(ns, ts, block=128):

@@ -285,7 +285,11 @@ int elsa_debug_layout_probe(float *out_5x16x64, void *stream);
  * One block per CU with waves_per_simd (1 or 2) x 4 waves; waves 0-3 issue `iters` x 16 independent instructions
  * of kind_a (iters x 8 for the MFMA kinds), waves 4-7 of kind_b.
  *   kinds: 0 v_exp_f32, 1 v_fma_f32, 2 v_add_f32, 3 v_max3_f32, 4 v_cvt_pk_f16_f32, 5 v_mfma_f32_32x32x2_f32,
- *          6 v_mfma_f32_32x32x16_f16, 7 nothing.
+ *          6 v_mfma_f32_32x32x16_f16, 7 nothing;
+ *          8, 9, 10: a register-only model of one fold step of the FP16 256-row tile (two query groups per wave,
+ *          d = 64, no LDS, no staging, no barrier): per iteration 8 = its 16 MFMAs alone, 9 = its fold alone (2 x
+ *          (16 FMA, 16 exponentials, 16 additions, 8 conversions, the limit test)), 10 = the whole step.  A model kind
+ *          runs beside itself, another model kind or kind 7 only.
  *   out: device buffer of 8 + 256 * 512 floats; out[w] = ticks of the constant 100 MHz counter that wave w of
  *        block 0 took, the rest is scratch.
  * ELSA_ERR_INVALID_ARG for a NULL buffer, an unknown kind, waves_per_simd not in {1, 2}, iters outside [1, 2^20].

@@ -77,9 +77,20 @@ def test_issue_probe_hook_runs_and_orders_the_instruction_kinds():
     add_alone = t[(2, 7, 2)][0]
     assert t[(6, 2, 2)][1] < 1.5 * add_alone                       # adds beside FP16 MFMAs: nearly unhindered
     assert t[(5, 2, 2)][1] > 2.0 * add_alone                       # adds beside FP32 MFMAs: they wait
-    for bad in [(-1, 0, 1, 10), (0, 8, 1, 10), (0, 0, 3, 10), (0, 0, 1, 0)]:
+    for bad in [(-1, 0, 1, 10), (0, 11, 1, 10), (0, 0, 3, 10), (0, 0, 1, 0), (10, 1, 2, 10), (0, 9, 2, 10)]:
         with pytest.raises(elsa.ElsaError):
             elsa.elsa_debug_issue_probe(out, *bad)
+    # the register-only model of one FP16 fold step (kinds 8 = its MFMAs, 9 = its fold, 10 = the whole step): the
+    # whole step takes at least its longer part and no more than both parts one after the other (plus 15 %)
+    m = {}
+    for k in (8, 9, 10):
+        for _ in range(2):
+            elsa.elsa_debug_issue_probe(out, k, k, 2, 1000)
+        torch.cuda.synchronize()
+        r = out[:8].cpu().numpy()
+        assert np.all(r > 0)
+        m[k] = float(r.max())
+    assert max(m[8], m[9]) <= m[10] <= 1.15 * (m[8] + m[9]), m
 
 
 @pytest.mark.parametrize("path,variant", ALL_KERNELS)
