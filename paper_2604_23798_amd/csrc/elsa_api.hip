@@ -358,6 +358,10 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
         x.variant = tc.variant;
         C = tc.splits;
     }
+    // FP16 tiles at d >= 96: the 256-row tile of eight query waves where its coarser blocks still fill the CUs
+    if (fp16_tiles && C == 1 && g.opt[ELSA_OPT_VARIANT] == 0 && (long long)n * 8 > nk &&
+        elsa::plan::wide_fp16_tile_pays((long long)B * H, n, d, causal))
+        x.variant = 6;
     if (C == 1) {
         x.lse = lse;
         return run_forward(q, k, v, out, nullptr, nullptr, nullptr, B, H, n, d, scale, causal, kv_len, 1, 0, 0, dtype,

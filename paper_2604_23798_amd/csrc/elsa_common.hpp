@@ -338,6 +338,6 @@ const char *mfma_variant_name(int variant);
 const char *fma_variant_name(int variant);
 constexpr int kMfmaVariants = 13;
 constexpr int kFmaVariants = 5;
-constexpr int kMfma16Variants = 5;
+constexpr int kMfma16Variants = 6;
 
 }  // namespace elsa

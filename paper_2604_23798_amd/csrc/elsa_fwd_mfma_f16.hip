@@ -7,8 +7,10 @@ namespace elsa {
 // ---- variants: 1 q128 (4 query waves)   2 q256 (4 waves x 2 query groups)   3 waves split the keys
 //                4 q64xw2 (two query waves x two key waves; the key-splitting shape of d >= 96)
 //                5 q256 as first built: 64-key tiles, one loop body per step, no early K request (comparison; d <= 64 only)
+//                6 q256w8 (d >= 96 only): eight query waves of one group each share the K/V tiles of 256 query rows, one
+//                  block per CU: half the tile staging per query row of the 128-row tile
 
-static const char *kNames16[kMfma16Variants] = {"mfma16_q128_w4", "mfma16_q256_w4", "mfma16_xwave", "mfma16_q64_xw2", "mfma16_q256_plain"};
+static const char *kNames16[kMfma16Variants] = {"mfma16_q128_w4", "mfma16_q256_w4", "mfma16_xwave", "mfma16_q64_xw2", "mfma16_q256_plain", "mfma16_q256_w8"};
 
 int mfma16_variant_tq(int variant, int d) {
     switch (variant) {
@@ -17,6 +19,7 @@ int mfma16_variant_tq(int variant, int d) {
         case 3: return d <= 64 ? 32 : 64;       // d >= 96: two query waves x two key waves
         case 4: return 64;
         case 5: return d <= 64 ? 256 : 0;
+        case 6: return d >= 96 ? 256 : 0;
         default: return 0;
     }
 }
@@ -28,11 +31,13 @@ template <int D>
 static int launch_variant16(const FwdParams &p, int variant, hipStream_t s) {
     // d = 96, 256: one query group per wave; 32-key tiles at d = 256 keep two blocks per CU in LDS
     if constexpr (D == 96) {
+        if (variant == 6) return launch_one16<D, 1, 8, 1, 128, 2>(p, s);
         if (variant == 3 || variant == 4) return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
         return launch_one16<D, 1, 4, 1, 64, 2>(p, s);
     } else if constexpr (D == 256) {
         // (the 128-row tile fills its 256 registers: the second copy of the exponentials that the lagging reference
         // needs spilled 20 bytes more and ran 9 % slower, so it keeps the exact maximum per step)
+        if (variant == 6) return launch_one16<D, 1, 8, 1, 32, 2, D, 1>(p, s);
         if (variant == 3 || variant == 4) return launch_one16<D, 1, 2, 2, 32, 1>(p, s);
         return launch_one16<D, 1, 4, 1, 32, 2, D, 1>(p, s);
     } else
@@ -50,6 +55,9 @@ static int launch_variant16(const FwdParams &p, int variant, hipStream_t s) {
         case 4: return launch_one16<D, 1, 2, 2, 32, 2>(p, s);
         case 5:
             if constexpr (D <= 64) return launch_one16<D, 2, 4, 1, 64, 2, D, 0>(p, s);
+            else return (int)hipErrorInvalidValue;
+        case 6:
+            if constexpr (D == 128) return launch_one16<D, 1, 8, 1, 64, 2>(p, s);
             else return (int)hipErrorInvalidValue;
         default: return (int)hipErrorInvalidValue;
     }

@@ -171,6 +171,24 @@ TileChoice choose_tiles_dv(bool fp16_tiles, long long BH, int n, int nk, int d, 
     return best;
 }
 
+// The 256-row FP16 tile of eight query waves owns a CU (two waves per SIMD, like two 128-row blocks) and stages every K/V
+// tile once for 256 rows instead of twice.  Staging is 19 % of the 128-row tile's time at d = 128 and more at d = 256, so
+// the wide tile wins wherever its coarser blocks still fill the CUs evenly.  Measured on B = 1, H = 8 / 16 / 40,
+// n = 1024 ... 16384 (ratio 128-row / 256-row time; b = number of 256-row blocks):
+//   d = 128, no mask: b = 256 1.06-1.14, 512 1.12, 1024 1.09, 1280 1.10, 2560 1.05; but 320 0.91, 640 0.99 (2.5 rounds of
+//            256 blocks cost 3); d = 96 the same picture (256: 1.02-1.08, 512: 1.12-1.13, 320: 0.90, 640: 0.95)
+//   d = 128 / 96, causal: 1024 1.05-1.08, 1280 1.02-1.04, 2560 1.05, 32K x 40 heads 1.07; 512 0.90-0.95
+//   d = 256: no mask 1.03-1.05 at b = 128, 1.23-1.37 from 160 up; causal 1.08-1.32 from b = 256 up, 0.74-0.87 below
+bool wide_fp16_tile_pays(long long BH, int n, int d, int causal) {
+    if (d < 96 || BH <= 0 || n <= 0) return false;
+    const long long b = BH * ((n + 255) / 256);
+    if (d == 256) return causal ? b >= kCus : b >= kCus / 2;
+    if (causal) return b >= 4 * kCus;
+    if (b < kCus) return false;
+    const long long rounds = (b + kCus - 1) / kCus;
+    return 100 * b >= 88 * rounds * kCus;            // the last round of blocks is at least ~90 % full on average
+}
+
 size_t workspace_bytes(int B, int H, int n, int d, int num_splits) {
     if (B <= 0 || H <= 0 || n <= 0 || !head_dim_ok(d) || num_splits < 1) return 0;
     const size_t rows = (size_t)B * H * num_splits * n;

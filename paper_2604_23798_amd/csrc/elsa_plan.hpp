@@ -29,5 +29,9 @@ TileChoice choose_tiles_dv(bool fp16_tiles, long long BH, int n, int nk, int d, 
 // count (requested <= 0) -- or the requested count, clamped to what the keys and the workspace allow.
 int auto_splits(int requested, int B, int H, int n, int nk, int d, bool fp16_tiles, size_t ws_bytes);
 
+// FP16 tiles at d >= 96: does the 256-row tile of eight query waves (one block per CU, the K/V tiles staged once for
+// twice the rows) beat the 128-row tile of four?  Measured rule, see elsa_plan.cpp.
+bool wide_fp16_tile_pays(long long BH, int n, int d, int causal);
+
 }  // namespace plan
 }  // namespace elsa

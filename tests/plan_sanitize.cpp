@@ -77,10 +77,16 @@ int main() {
         // (the library calls it for at most 12 x 256 blocks of 128 rows) plus a margin
         if (BH * ((n + 31) / 32) > 400000) continue;
         one(fp16, BH, n, nk, d, causal, max_c);
+        // the wide FP16 tile is never chosen below d = 96 nor for fewer blocks than half the CUs
+        const bool wide = wide_fp16_tile_pays(BH, n, d, causal);
+        CHECK(!wide || (d >= 96 && BH * ((n + 255) / 256) >= kCus / 2));
         static const int pairs[7][2] = {{32, 64}, {64, 32}, {64, 128}, {128, 64}, {32, 128}, {128, 32}, {192, 128}};
         const int *pr = pairs[next() % 7];
         one_dv(fp16, BH, n, nk, pr[0], pr[1], causal, max_c);
     }
+
+    CHECK(wide_fp16_tile_pays(40, 32768, 128, 1) && wide_fp16_tile_pays(16, 8192, 128, 0) && !wide_fp16_tile_pays(40, 2048, 128, 0));
+    CHECK(!wide_fp16_tile_pays(16, 16384, 64, 0) && !wide_fp16_tile_pays(0, 1024, 128, 0) && !wide_fp16_tile_pays(4096, 1 << 20, 128, 1) == false);
 
     // chunk counts: never more than the keys or the workspace allow, never below one
     for (int it = 0; it < 20000; ++it) {

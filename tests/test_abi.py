@@ -43,7 +43,7 @@ def test_status_strings_and_options():
         elsa.elsa_set_option(9, 0)
     assert elsa.elsa_variant_name(2, 1).startswith("mfma") and elsa.elsa_variant_name(1, 1).startswith("fma")
     assert elsa.elsa_variant_name(2, 99) is None
-    assert elsa.elsa_variant_name(3, 1).startswith("mfma16") and elsa.elsa_variant_name(3, 6) is None
+    assert elsa.elsa_variant_name(3, 1).startswith("mfma16") and elsa.elsa_variant_name(3, 6) == "mfma16_q256_w8" and elsa.elsa_variant_name(3, 7) is None
 
 
 def test_workspace_bytes():

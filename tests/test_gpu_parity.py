@@ -165,9 +165,57 @@ def test_fp16_matrix_core_path_masks_splits_and_edges(variant):
                   "fp16 split + combine")
 
 
-@pytest.mark.parametrize("path,variant", [(MFMA16, 1), (MFMA16, 2), (MFMA16, 3), (MFMA16, 4), (MFMA, 1), (MFMA, 3), (MFMA, 7), (MFMA, 11)])
+@pytest.mark.parametrize("d", [96, 128, 256])
+def test_fp16_wide_tile_of_eight_query_waves(d):
+    """FP16 tile 6 (d >= 96): 256 query rows per block, eight query waves of one group each on shared K/V tiles.
+    Ragged sizes around its tile edges, causal mask, key padding with NaN beyond kv_len, log-normaliser, and the
+    states it writes (through the exact-maximum instantiation) against the FP64 oracle; unsupported below d = 96."""
+    import torch
+    from paper_2604_23798_amd import elsa
+    tol = 2e-3
+    scale = 1.0 / math.sqrt(d)
+    for n in (700, 257, 255, 33):
+        q, k, v = _rand(2, 2, n, d, 300 + n + d, fp16=True)
+        qf, kf, vf = _f32(q, k, v)
+        for causal in (False, True):
+            with G.Options(path=MFMA16, variant=6):
+                out, lse = G.fwd_cross(q, k, v, scale, causal=causal, want_lse=True)
+                assert elsa.elsa_last_kernel() == "mfma16_q256_w8"
+            assert_parity(out, oracle.attn_rows(qf, kf, vf, scale, causal=causal), tol, "w8 d%d n%d causal=%d" % (d, n, causal))
+            assert np.all(np.abs(lse - oracle.lse_rows(qf, kf, scale, causal=causal)) <= tol)
+    B, H, n = 3, 2, 600
+    q, k, v = _rand(B, H, n, d, 310 + d, fp16=True)
+    kv_len = np.array([600, 0, 301], np.int32)
+    for b in range(B):
+        k[b, :, kv_len[b]:] = np.nan
+        v[b, :, kv_len[b]:] = np.inf
+    qf, kf, vf = _f32(q, k, v)
+    for causal in (False, True):
+        with G.Options(path=MFMA16, variant=6):
+            out = G.fwd(q, k, v, scale, causal=causal, kv_len=kv_len)
+        assert np.all(np.isfinite(out))
+        assert_parity(out, oracle.attn_rows(qf, kf, vf, scale, causal=causal, kv_len=kv_len), tol, "w8 padded d%d" % d)
+    q, k, v = _rand(1, 2, 520, d, 320 + d, fp16=True)
+    qf, kf, vf = _f32(q, k, v)
+    with G.Options(path=MFMA16, variant=6):
+        pm, pS, pW = G.split_kv(q, k, v, scale, 2, causal=True)
+    gm, gS, gW = G.parts_to_rows(pm, pS, pW)
+    om, oS, oW = oracle.partials_rows(qf, kf, vf, scale, 2, causal=True)
+    live = ~np.isneginf(om)
+    assert np.array_equal(np.isneginf(gm), ~live)
+    assert np.all(np.abs(gm[live] - om[live]) <= 4e-6 * (1 + np.abs(om[live])))             # the exact chunk maximum
+    assert np.all(np.abs(gm[live] + np.log(gS[live]) - om[live] - np.log(oS[live])) <= 1e-3)
+    q, k, v = _rand(1, 1, 300, 64, 330, fp16=True)
+    with G.Options(path=MFMA16, variant=6):
+        with pytest.raises(elsa.ElsaError):
+            G.fwd(q, k, v, 0.125)
+
+
+@pytest.mark.parametrize("path,variant", [(MFMA16, 1), (MFMA16, 2), (MFMA16, 3), (MFMA16, 4), (MFMA16, 6), (MFMA, 1), (MFMA, 3), (MFMA, 7), (MFMA, 11)])
 @pytest.mark.parametrize("d", [64, 128])
 def test_reference_that_lags_the_maximum(path, variant, d):
+    if path == MFMA16 and variant == 6 and d < 96:
+        pytest.skip("tile 6 serves d >= 96 only")
     """The matrix-core tiles let the m of the running state lag the true maximum and redo a step the exact way when
     a partial row sum passes their limit (2^10 with FP16 weights, 2^16 with FP32 ones) or a row meets its first
     key.  Score profiles along the keys that exercise both sides of that test: a slow creep (no single step jumps,

@@ -41,7 +41,12 @@ def test_headline_and_long_sequences_take_the_128_row_tiles_in_one_pass():
     assert plan(16, 12, 512, 512, 64, ws_mib=256) == ("mfma_q128_k32", 1)
     assert plan(1, 16, 16384, 16384, 64, dtype=1) == ("mfma16_q256_w4", 1)
     assert plan(1, 16, 16384, 16384, 64, dtype=1, causal=True) == ("mfma16_q128_w4", 1)   # diagonal tiles waste less
-    assert plan(1, 40, 32768, 32768, 128, causal=True, dtype=1) == ("mfma16_q128_w4", 1)
+    # FP16 at d >= 96: the 256-row tile of eight query waves where its blocks fill the CUs evenly, else the 128-row tile
+    assert plan(1, 40, 32768, 32768, 128, causal=True, dtype=1) == ("mfma16_q256_w8", 1)
+    assert plan(1, 16, 8192, 8192, 128, dtype=1) == ("mfma16_q256_w8", 1)
+    assert plan(1, 40, 4096, 4096, 128, dtype=1) == ("mfma16_q128_w4", 1)                    # 640 blocks: 2.5 rounds
+    assert plan(1, 16, 8192, 8192, 128, dtype=1, causal=True) == ("mfma16_q128_w4", 1)
+    assert plan(1, 40, 1024, 1024, 256, dtype=1) == ("mfma16_q256_w8", 1)
     assert plan(1, 16, 8192, 8192, 96) == ("mfma_q128_w4", 1) and plan(1, 16, 8192, 8192, 256) == ("mfma_q128_w4", 1)
 
 
@@ -77,7 +82,7 @@ def test_small_problems_follow_the_block_placement_model():
     assert plan(1, 16, 4096, 4096, 256, causal=True, ws_mib=256) == ("mfma_q128_w4", 2)          # 1.37 against 1.63 ms in one pass
     assert plan(1, 16, 2048, 2048, 96, dtype=1, causal=True) == ("mfma16_q64_xw2", 1)           # 33 against 48 us
     assert plan(1, 16, 2048, 2048, 256, dtype=1, causal=True) == ("mfma16_q64_xw2", 1)          # 114 against 167 us
-    assert plan(1, 16, 16384, 16384, 256, dtype=1) == ("mfma16_q128_w4", 1)
+    assert plan(1, 16, 16384, 16384, 256, dtype=1) == ("mfma16_q256_w8", 1)                       # 2.07 against 2.70 ms (H = 8)
     # a forced tile or chunk count switches the model off
     assert plan(1, 16, 1024, 1024, 64, ws_mib=64, variant=7) == ("mfma_q128_k32", 2)
     assert plan(1, 16, 1024, 1024, 64, ws_mib=64, splits=3)[1] == 3
