@@ -87,9 +87,18 @@ int pick_variant(int path, long long BH, int n, int nk, int d, int splits, int c
     }
     const long long b256 = BH * ((n + 255) / 256) * splits;
     const long long b128 = BH * ((n + 127) / 128) * splits;
-    // FP16: the 256-row tile wins only without a causal mask (its diagonal tiles waste twice as much:
-    // 436 vs 287 TFLOP/s at n = 4096, 794 vs 756 at n = 16384, causal, d = 64)
-    if (path == 3) return (d <= 64 && n >= 256 && b256 >= 2 * kNumCu && !causal) ? 2 : (b128 >= (3 * kNumCu) / 4 ? 1 : 3);
+    // FP16, d <= 64: the 256-row tile (two blocks per CU) wins from 512 such blocks up when they fill the 512 places
+    // evenly (640 blocks = 1.25 rounds: 0.92-0.96 of the 128-row tile's speed; 512 / 1024 / 1280 / 2560: 1.02-1.10); under a
+    // causal mask its diagonal tiles waste twice as much, which pays off only on long sequences with many blocks
+    // (n >= 16384 and 1024 blocks: 1.04-1.07; n = 8192 or 512 blocks: 0.83-0.98)
+    if (path == 3) {
+        if (d <= 64 && n >= 256) {
+            const long long places = 2 * kNumCu, rounds = (b256 + places - 1) / places;
+            if (!causal && b256 >= places && 100 * b256 >= 80 * rounds * places) return 2;
+            if (causal && n >= 16384 && b256 >= 4 * kNumCu) return 2;
+        }
+        return b128 >= (3 * kNumCu) / 4 ? 1 : 3;
+    }
     if (b128 < (3 * kNumCu) / 4) return 3;
     return d <= 64 ? 7 : 1;
 }

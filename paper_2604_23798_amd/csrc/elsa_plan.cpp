@@ -39,7 +39,9 @@ TileChoice play_through(const TileShape *shapes, int nshapes, double dscale, uns
     double free_at[kNumCu];                  // min-heap: when a CU takes its next block (no host allocation)
     for (int si = 0; si < nshapes; ++si) {
         const TileShape &sh = shapes[si];
-        if (fp16_tiles && sh.rows == 256 && causal) continue;   // its diagonal tiles waste twice as much (measured: never the best under a causal mask)
+        // under a causal mask the 256-row tile's diagonal tiles waste twice as much: measured best only on long sequences
+        // with at least 1024 such blocks (n >= 16384: 1.04-1.07 of the 128-row tile's speed; shorter or fewer: 0.83-0.98)
+        if (fp16_tiles && sh.rows == 256 && causal && !(n >= 16384 && BH * ((n + 255) / 256) >= 4 * kNumCu)) continue;
         if (!fp16_tiles && sh.variant == 13 && nk < 1024) continue;   // the single-buffered tile pays from about sixteen 64-key tiles per block up
         const int q_tiles = (n + sh.rows - 1) / sh.rows;
         for (int C = 1; C <= max_splits; ++C) {

@@ -40,7 +40,10 @@ def test_headline_and_long_sequences_take_the_128_row_tiles_in_one_pass():
     assert plan(1, 40, 32768, 32768, 128, causal=True, ws_mib=256) == ("mfma_q128_w4", 1)
     assert plan(16, 12, 512, 512, 64, ws_mib=256) == ("mfma_q128_k32", 1)
     assert plan(1, 16, 16384, 16384, 64, dtype=1) == ("mfma16_q256_w4", 1)
-    assert plan(1, 16, 16384, 16384, 64, dtype=1, causal=True) == ("mfma16_q128_w4", 1)   # diagonal tiles waste less
+    assert plan(1, 16, 16384, 16384, 64, dtype=1, causal=True) == ("mfma16_q256_w4", 1)   # long and many blocks: 961 against 927 TFLOP/s
+    assert plan(1, 16, 8192, 8192, 64, dtype=1, causal=True) == ("mfma16_q128_w4", 1)     # else its diagonal tiles waste less
+    assert plan(1, 8, 16384, 16384, 64, dtype=1, causal=True) == ("mfma16_q128_w4", 1)
+    assert plan(1, 40, 4096, 4096, 64, dtype=1) == ("mfma16_q128_w4", 1)                  # 640 256-row blocks: 1.25 rounds
     # FP16 at d >= 96: the 256-row tile of eight query waves where its blocks fill the CUs evenly, else the 128-row tile
     assert plan(1, 40, 32768, 32768, 128, causal=True, dtype=1) == ("mfma16_q256_w8", 1)
     assert plan(1, 16, 8192, 8192, 128, dtype=1) == ("mfma16_q256_w8", 1)
