@@ -239,9 +239,14 @@ int run_forward_dv(const void *q, const void *k, const void *v, void *out, float
     const long long esz = dtype == ELSA_F16 ? 2 : 4;
     if ((long long)(nk > n ? nk : n) * (d > dv ? d : dv) * esz >= 0x7fffffffLL) return ELSA_ERR_UNSUPPORTED;
     int variant = g.opt[ELSA_OPT_VARIANT];
-    if (variant != 0 && variant != 1 && variant != 3) return ELSA_ERR_UNSUPPORTED;
+    if (variant != 0 && variant != 1 && variant != 3 && variant != 6) return ELSA_ERR_UNSUPPORTED;
     const int tq3 = elsa::dv_variant_tq(fp16_tiles, 3, d, dv);
     if (variant == 0 && chosen_variant != 0) variant = chosen_variant;    // from the block-placement model
+    // FP16 tiles with a 128-wide (or wider) operand: the 256-row tile of eight query waves where its blocks fill the CUs
+    // evenly (the rule measured at d_v = d = 128)
+    if (g.opt[ELSA_OPT_VARIANT] == 0 && fp16_tiles && !emit && num_splits == 1 && (long long)n * 8 > nk &&
+        elsa::dv_variant_tq(1, 6, d, dv) > 0 && elsa::plan::wide_fp16_tile_pays((long long)B * H, n, 128, causal))
+        variant = 6;
     if (variant == 0) {
         const long long b128 = (long long)B * H * ((n + 127) / 128) * num_splits;
         variant = 1;

@@ -7,8 +7,10 @@ namespace elsa {
 
 // tile ids: 1 = 128 query rows (four query waves, 32-key LDS tiles)
 //           3 = the waves of a block split the key range (32 query rows when d, d_v <= 64, else 64)
+//           6 = FP16 tiles with d or d_v >= 128 only: 256 query rows, eight query waves on shared K/V tiles
 int dv_variant_tq(int fp16_tiles, int variant, int d, int dv) {
     if (variant == 1) return 128;
+    if (variant == 6) return (fp16_tiles && (d >= 128 || dv >= 128)) ? 256 : 0;
     if (variant != 3) return 0;
     if (!fp16_tiles && d == 192) return 0;       // two FP32 tiles of 64 keys x (192 + 128) columns exceed the LDS
     return (d <= 64 && dv <= 64) ? 32 : 64;

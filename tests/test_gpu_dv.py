@@ -40,9 +40,16 @@ SHAPES = [(1, 777), (37, 2000), (200, 64), (129, 131), (300, 333), (515, 515)]
 
 @pytest.mark.parametrize("d,dv", PAIRS)
 @pytest.mark.parametrize("fp16", [False, True])
-@pytest.mark.parametrize("variant", [1, 3])
+@pytest.mark.parametrize("variant", [1, 3, 6])
 def test_every_pair_on_both_tiles(d, dv, fp16, variant):
     from paper_2604_23798_amd import elsa
+    if variant == 6 and not (fp16 and max(d, dv) >= 128):
+        # the 256-row tile of eight query waves exists for FP16 tiles with a 128-wide (or wider) operand only
+        q, k, v = _rect(1, 1, 8, 8, d, dv, 1, fp16=fp16)
+        with G.Options(variant=6), pytest.raises(elsa.ElsaError) as e:
+            G.fwd_dv(q, k, v, 0.1)
+        assert e.value.code == elsa.ERR_UNSUPPORTED
+        return
     if variant == 3 and d == 192 and not fp16:
         q, k, v = _rect(1, 1, 8, 8, d, dv, 1)
         with G.Options(variant=3), pytest.raises(elsa.ElsaError) as e:
@@ -57,7 +64,7 @@ def test_every_pair_on_both_tiles(d, dv, fp16, variant):
             with G.Options(variant=variant):
                 out, lse = G.fwd_dv(q, k, v, d ** -0.5, causal=causal, want_lse=True)
                 name = elsa.elsa_last_kernel()
-            assert name == ("mfma16_dv_" if fp16 else "mfma_dv_") + ("q128" if variant == 1 else "xwave")
+            assert name == ("mfma16_dv_" if fp16 else "mfma_dv_") + {1: "q128", 3: "xwave", 6: "q256_w8"}[variant]
             assert out.shape == ref.shape
             assert_parity(out, ref, tolerance(max(nq, nk), fp16), "dv %s %dx%d d%d dv%d c%d" % (name, nq, nk, d, dv, causal))
             vis = np.isfinite(ref_lse)
