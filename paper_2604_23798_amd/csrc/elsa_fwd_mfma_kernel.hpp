@@ -13,6 +13,13 @@
 //   3. accumulates W^T += V^T P^T with the same MFMA: the exponentials sit in the
 //      accumulator registers exactly where the B operand of the next MFMA wants
 //      them, so P never moves between lanes and never touches LDS.
+// LAG = 1 (the default tiles; launches that write the output, not a state): the m of the running state may lag the
+// true maximum.  (m, S, W) and (m', S 2^(m-m'), W 2^(m-m')) are the same element of the monoid and give the same W / S,
+// so step 1 starts every accumulation chain from -m / NACC of the stored m -- the scores come out relative to it --
+// and step 2 is exponentials and row sum only, as long as every lane's partial row sum stays below kLagLimit; otherwise
+// (a row's first keys, a score far above the stored reference, a NaN) the step is redone the exact way: maximum,
+// rescale, new reference.  LAG = 0 is the merge as printed in every step (tiles without the sixteen registers per
+// query group that hold -m / NACC; launches that write states, whose m is the exact maximum).
 // When WK > 1 the waves that split the key range merge their states through LDS
 // (log2(WK) levels of the same operator).  The block then writes either
 // out = W / S (Alg. 1, last line) or the state itself (Prop. 1 block state).
