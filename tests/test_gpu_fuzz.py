@@ -46,7 +46,7 @@ def _case(rng):
     if r == 1:
         opts = dict(path=2, variant=int(rng.choice([1, 3] if wide else [1, 2, 3, 4, 7, 8, 11] + ([12, 13] if d == 128 else []))))
     elif r == 2 and fp16:
-        opts = dict(path=3, variant=int(rng.choice([1, 2, 3, 4])))
+        opts = dict(path=3, variant=int(rng.choice([1, 2, 3, 4] + ([6] if d >= 96 else []))))
     elif r == 3 and not wide:
         opts = dict(path=1, variant=int(rng.choice([1, 2])))
     opts["snake"] = int(rng.integers(0, 2))
