@@ -118,6 +118,7 @@ struct Extra {
     bool has_coff = false;                       // causal diagonal given explicitly (streamed chunks)
     int coff = 0;
     int variant = 0;                             // matrix-core tile chosen by the caller (0: pick_variant decides)
+    bool states_internal = false;                // the states written are consumed by the library's own combine pass only
 };
 
 int run_forward(const void *q, const void *k, const void *v, void *out, float *pm, float *pS, float *pW,
@@ -180,6 +181,7 @@ int run_forward(const void *q, const void *k, const void *v, void *out, float *p
     p.accumulate = x.accumulate;
     p.coff = x.has_coff ? x.coff : nk - n;       // last query aligned with the last key
     p.m_natural = m_natural;
+    p.states_internal = (emit && x.states_internal && !x.accumulate && !m_natural) ? 1 : 0;
     p.q_tiles = (n + tq - 1) / tq;
     p.tq = tq;
     p.kv_once = p.q_tiles == 1 ? 1 : 0;
@@ -383,7 +385,9 @@ static int attn_fwd_impl(const void *q, const void *k, const void *v, void *out,
     }
     float *pm, *pS, *pW;
     carve(ws, B, H, n, d, C, &pm, &pS, &pW);
-    // internal split: maxima stay in log2 units, so the second pass adds no rounding of m
+    // internal split: maxima stay in log2 units, so the second pass adds no rounding of m; the states never leave the
+    // library, so the tiles may keep their lagging reference in them
+    x.states_internal = true;
     rc = run_forward(q, k, v, nullptr, pm, pS, pW, B, H, n, d, scale, causal, kv_len, C, 1, 0, dtype, stream, x);
     if (rc != ELSA_OK) return rc;
     if (g.opt[ELSA_OPT_DRY_RUN]) return ELSA_OK;

@@ -41,6 +41,7 @@ struct FwdParams {
                                      //    2 = also the four-run rule (kernels that keep three blocks per CU resident)
     int coff;                        // dense layout, causal: key j is visible to query i iff j <= i + coff
     int m_natural;                   // 1: part_m in natural-log units, 0: log2 units (internal)
+    int states_internal;             // 1: the states written stay inside the library (internal key split): their m may be any valid reference, not the exact maximum
     int xcd_map;                     // block -> work item order, see decode_work
     int kv_once;                     // 1: one query tile per (batch, head) -- every K/V byte is read once, loads may stream
     int q_tiles;                     // ceil(n / T_q) for the launched configuration

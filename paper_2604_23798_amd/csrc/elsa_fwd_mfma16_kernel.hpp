@@ -472,9 +472,10 @@ static int launch_one16(const FwdParams &p, hipStream_t s) {
     constexpr size_t xw_bytes = WK > 1 ? (size_t)(WK / 2) * WQ * NQ * (2 + DV / 2) * 64 * sizeof(float) : 0;
     constexpr size_t smem = kv_bytes > xw_bytes ? kv_bytes : xw_bytes;
     static_assert(smem <= 160 * 1024, "tile does not fit the LDS of a CU");
-    // a launch that writes states keeps the exact maximum in them: the same tile without the lagging reference
+    // a launch that writes states for a caller keeps the exact maximum in them: the same tile without the lagging
+    // reference (states of the library's own key split may carry any valid reference)
     if constexpr (TRIM >= 3) {
-        if (p.emit_partials) return launch_one16<D, NQ, WQ, WK, KS, WPE, DV, (TRIM == 3 ? 2 : 1)>(p, s);
+        if (p.emit_partials && !p.states_internal) return launch_one16<D, NQ, WQ, WK, KS, WPE, DV, (TRIM == 3 ? 2 : 1)>(p, s);
     }
     auto kern = fwd_mfma16_kernel<D, NQ, WQ, WK, KS, WPE, DV, TRIM>;
     static bool attr_done[kMaxDevices] = {};   // per instantiation and device

@@ -534,9 +534,10 @@ __global__ __launch_bounds__(64 * WQ * WK, WPE) void fwd_mfma_kernel(FwdParams p
 
 template <int D, typename T, int NQ, int WQ, int WK, int KS, int WPE, int NACC, int BUFL, int DV = D, int LAG = 0>
 static int launch_one(const FwdParams &p, hipStream_t s) {
-    // a launch that writes states keeps the exact maximum in them: the same tile without the lagging reference
+    // a launch that writes states for a caller keeps the exact maximum in them: the same tile without the lagging
+    // reference (states of the library's own key split may carry any valid reference)
     if constexpr (LAG != 0) {
-        if (p.emit_partials) return launch_one<D, T, NQ, WQ, WK, KS, WPE, NACC, BUFL, DV, 0>(p, s);
+        if (p.emit_partials && !p.states_internal) return launch_one<D, T, NQ, WQ, WK, KS, WPE, NACC, BUFL, DV, 0>(p, s);
     }
     constexpr int TKB = KS * WK;
     constexpr size_t kv_bytes = (size_t)(BUFL == 2 ? 1 : 2) * (TKB * (D + 4) + TKB * DV) * sizeof(float);
