@@ -177,7 +177,7 @@ TileChoice choose_tiles_dv(bool fp16_tiles, long long BH, int n, int nk, int d, 
 // tile once for 256 rows instead of twice.  Staging is 19 % of the 128-row tile's time at d = 128 and more at d = 256, so
 // the wide tile wins wherever its coarser blocks still fill the CUs evenly.  Measured on B = 1, H = 8 / 16 / 40,
 // n = 1024 ... 16384 (ratio 128-row / 256-row time; b = number of 256-row blocks):
-//   d = 128, no mask: b = 256 1.06-1.14, 512 1.12, 1024 1.09, 1280 1.10, 2560 1.05; but 320 0.91, 640 0.99 (2.5 rounds of
+//   d = 128, no mask: b = 128 0.86, 160 1.18 (against the 64-row tile the planner picks there), 256 1.06-1.14, 512 1.12, 1024 1.09, 1280 1.10, 2560 1.05; but 320 0.91, 640 0.99 (2.5 rounds of
 //            256 blocks cost 3); d = 96 the same picture (256: 1.02-1.08, 512: 1.12-1.13, 320: 0.90, 640: 0.95)
 //   d = 128 / 96, causal: 1024 1.05-1.08, 1280 1.02-1.04, 2560 1.05, 32K x 40 heads 1.07; 512 0.90-0.95
 //   d = 256: no mask 1.03-1.05 at b = 128, 1.23-1.37 from 160 up; causal 1.08-1.32 from b = 256 up, 0.74-0.87 below
@@ -186,7 +186,7 @@ bool wide_fp16_tile_pays(long long BH, int n, int d, int causal) {
     const long long b = BH * ((n + 255) / 256);
     if (d == 256) return causal ? b >= kCus : b >= kCus / 2;
     if (causal) return b >= 4 * kCus;
-    if (b < kCus) return false;
+    if (b < kCus) return 8 * b >= 5 * kCus;          // one partial round: from 160 blocks up (1.13-1.18 at 160, 0.86 at 128)
     const long long rounds = (b + kCus - 1) / kCus;
     return 100 * b >= 88 * rounds * kCus;            // the last round of blocks is at least ~90 % full on average
 }

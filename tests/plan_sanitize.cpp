@@ -79,7 +79,7 @@ int main() {
         one(fp16, BH, n, nk, d, causal, max_c);
         // the wide FP16 tile is never chosen below d = 96 nor for fewer blocks than half the CUs
         const bool wide = wide_fp16_tile_pays(BH, n, d, causal);
-        CHECK(!wide || (d >= 96 && BH * ((n + 255) / 256) >= kCus / 2));
+        CHECK(!wide || (d >= 96 && BH * ((n + 255) / 256) >= kCus / 2));          // (d = 256 from half the CUs, else from 5/8)
         static const int pairs[7][2] = {{32, 64}, {64, 32}, {64, 128}, {128, 64}, {32, 128}, {128, 32}, {192, 128}};
         const int *pr = pairs[next() % 7];
         one_dv(fp16, BH, n, nk, pr[0], pr[1], causal, max_c);

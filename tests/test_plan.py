@@ -50,6 +50,8 @@ def test_headline_and_long_sequences_take_the_128_row_tiles_in_one_pass():
     assert plan(1, 40, 4096, 4096, 128, dtype=1) == ("mfma16_q128_w4", 1)                    # 640 blocks: 2.5 rounds
     assert plan(1, 16, 8192, 8192, 128, dtype=1, causal=True) == ("mfma16_q128_w4", 1)
     assert plan(1, 40, 1024, 1024, 256, dtype=1) == ("mfma16_q256_w8", 1)
+    assert plan(1, 40, 1024, 1024, 128, dtype=1) == ("mfma16_q256_w8", 1)                    # 160 blocks: 35.6 against 41-46 us
+    assert plan(1, 16, 2048, 2048, 128, dtype=1) != ("mfma16_q256_w8", 1)                    # 128 blocks: too few
     assert plan(1, 16, 8192, 8192, 96) == ("mfma_q128_w4", 1) and plan(1, 16, 8192, 8192, 256) == ("mfma_q128_w4", 1)
 
 
