@@ -57,28 +57,31 @@ def _case(rng):
     return dict(kind=kind, B=B, H=H, nq=nq, nk=nk, d=d, fp16=fp16, causal=causal, kv_len=kv_len, opts=opts, splits=splits)
 
 
-def _tensors(c, seed):
+def _tensors(c, seed, sigma=1.0):
     B, H, nq, nk, d = c["B"], c["H"], c["nq"], c["nk"], c["d"]
-    q = inputs.normal(seed, 0, 0, B * H * nq * d).reshape(B, H, nq, d)
-    k = inputs.normal(seed, 1, 0, B * H * nk * d).reshape(B, H, nk, d)
+    q = inputs.normal(seed, 0, 0, B * H * nq * d, sigma).reshape(B, H, nq, d)
+    k = inputs.normal(seed, 1, 0, B * H * nk * d, sigma).reshape(B, H, nk, d)
     v = inputs.normal(seed, 2, 0, B * H * nk * d).reshape(B, H, nk, d)
     if c["fp16"]:
         q, k, v = (t.astype(np.float16) for t in (q, k, v))
     return q, k, v
 
 
-@pytest.mark.parametrize("block", range(16))
-def test_random_cases(block):
+# sigma = 3: Q, K ~ N(0, 9), scores with a standard deviation of 9 nats -- the running maximum keeps moving, so the tiles
+# renew their lagging reference again and again (sigma = 1 renews it on a row's first keys only)
+@pytest.mark.parametrize("block,sigma", [(b, 1.0) for b in range(16)] + [(b, 3.0) for b in range(8)])
+def test_random_cases(block, sigma):
     import torch
     from paper_2604_23798_amd import elsa
-    rng = np.random.default_rng(9000 + block + OFFSET)
+    rng = np.random.default_rng(9000 + block + OFFSET + (0 if sigma == 1.0 else 50000))
+    wide = 1.0 if sigma == 1.0 else 4.0           # FP32 dot products of 9x the magnitude are rounded 9x as coarsely
     ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
     for i in range(20):
         c = _case(rng)
         seed = 9100 + 100 * block + i + OFFSET
         d, scale = c["d"], float(np.float32(c["d"] ** -0.5))
-        what = "fuzz %d/%d %s" % (block, i, {k_: v_ for k_, v_ in c.items() if k_ != "kv_len"})
-        tol = tolerance(max(c["nq"], c["nk"]), c["fp16"])
+        what = "fuzz %d/%d sigma=%g %s" % (block, i, sigma, {k_: v_ for k_, v_ in c.items() if k_ != "kv_len"})
+        tol = wide * tolerance(max(c["nq"], c["nk"]), c["fp16"])
         if c["kind"] == "varlen":
             lengths = [int(x) for x in rng.integers(0, 200, size=int(rng.integers(1, 9)))]
             if sum(lengths) == 0:
@@ -89,7 +92,7 @@ def test_random_cases(block):
                 out = G.fwd_varlen(q, k, v, cu, max(lengths), scale, causal=c["causal"])
             assert_parity(out.reshape(-1, d), ref.reshape(-1, d), tol, what)
             continue
-        q, k, v = _tensors(c, seed)
+        q, k, v = _tensors(c, seed, sigma)
         ref, ref_lse = oracle.cross_rows(f32(q), f32(k), f32(v), scale, causal=c["causal"], kv_len=c["kv_len"])
         opts = dict(c["opts"], splits=c["splits"])
         try:
@@ -115,7 +118,7 @@ def test_random_cases(block):
                     out, lse = G.fwd_cross(q, k, v, scale, causal=c["causal"], kv_len=c["kv_len"], want_lse=True)
                     vis = np.isfinite(ref_lse)
                     assert np.all(np.isneginf(lse[~vis])), what
-                    assert np.max(np.abs(lse[vis] - ref_lse[vis]), initial=0.0) < (5e-3 if c["fp16"] else 3e-5), what
+                    assert np.max(np.abs(lse[vis] - ref_lse[vis]), initial=0.0) < wide * (5e-3 if c["fp16"] else 3e-5), what
         finally:
             elsa.elsa_set_workspace(None)
         assert_parity(out, ref, tol, what)
